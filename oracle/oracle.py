@@ -1,0 +1,283 @@
+"""ctypes front end of the CPU oracle (ivit_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Compiles the C file with gcc on first use (plain -O2, no threads) and exposes
+numpy-in / numpy-out wrappers.  All arithmetic lives in the C file; this module
+only marshals arguments.  It imports nothing from the GPU package.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ivit_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+__all__ = [
+    "build", "rnd_shift", "clamp_k", "requant", "shiftexp", "intdiv", "isqrt10",
+    "shiftgelu_raw", "shiftgelu", "shiftmax", "ilayernorm", "linear_requant",
+    "attention", "encoder_block", "forward", "ShiftParams", "Dyadic",
+    "requant_vec", "rnd_shift_vec", "isqrt10_vec", "shiftexp_vec", "TAP_NAMES",
+]
+
+
+class ShiftParams(C.Structure):
+    _fields_ = [("i0", C.c_int32), ("n_shift", C.c_int32), ("m_bits", C.c_int32), ("k_out", C.c_int32)]
+
+
+class Dyadic(C.Structure):
+    _fields_ = [("b", C.c_int32), ("c", C.c_int32)]
+
+
+class _Dims(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "T", "C", "H", "F")]
+
+
+_P = C.c_void_p
+
+
+class _BlockParams(C.Structure):
+    _fields_ = [
+        ("ln1_gamma", _P), ("ln1_beta", _P), ("ln1_f_bits", C.c_int32), ("ln1_c_shift", C.c_int32),
+        ("w_qkv", _P), ("bias_qkv", _P), ("qkv_rq_b", _P), ("qkv_rq_c", _P),
+        ("qk_rq", Dyadic), ("rel_bias", _P), ("softmax", ShiftParams), ("pv_rq", Dyadic),
+        ("w_proj", _P), ("bias_proj", _P), ("proj_rq_b", _P), ("proj_rq_c", _P), ("res1_rq", Dyadic),
+        ("ln2_gamma", _P), ("ln2_beta", _P), ("ln2_f_bits", C.c_int32), ("ln2_c_shift", C.c_int32),
+        ("w_fc1", _P), ("bias_fc1", _P), ("fc1_rq_b", _P), ("fc1_rq_c", _P),
+        ("gelu", ShiftParams), ("gelu_rq", Dyadic),
+        ("w_fc2", _P), ("bias_fc2", _P), ("fc2_rq_b", _P), ("fc2_rq_c", _P), ("res2_rq", Dyadic),
+    ]
+
+
+class _Taps(C.Structure):
+    _fields_ = [(n, _P) for n in ("u", "qkv", "scores", "probs", "o", "xhat", "v", "h")]
+
+
+def build(force=False):
+    """Compile ivit_oracle.c into liboracle.so (gcc -O2).  Returns the path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fwrapv", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _L():
+    global _lib
+    if _lib is None:
+        lib = C.CDLL(build())
+        i64, i32 = C.c_int64, C.c_int32
+        lib.orc_rnd_shift.restype = i64; lib.orc_rnd_shift.argtypes = [i64, i32]
+        lib.orc_clamp_k.restype = i64; lib.orc_clamp_k.argtypes = [i64, i32]
+        lib.orc_requant.restype = i64; lib.orc_requant.argtypes = [i64, i32, i32]
+        lib.orc_shiftexp.restype = i64; lib.orc_shiftexp.argtypes = [i64, i32, i32]
+        lib.orc_intdiv.restype = i64; lib.orc_intdiv.argtypes = [i64, i64, i32, i32]
+        lib.orc_isqrt10.restype = i64; lib.orc_isqrt10.argtypes = [i64]
+        lib.orc_shiftgelu_raw.restype = None; lib.orc_shiftgelu_raw.argtypes = [_P, _P, i64, ShiftParams]
+        lib.orc_shiftgelu.restype = None; lib.orc_shiftgelu.argtypes = [_P, _P, i64, ShiftParams, Dyadic]
+        lib.orc_shiftmax.restype = None
+        lib.orc_shiftmax.argtypes = [_P, _P, i32, i32, _P, i64, i32, i32, ShiftParams]
+        lib.orc_ilayernorm.restype = None; lib.orc_ilayernorm.argtypes = [_P, _P, _P, _P, i64, i32, i32, i32]
+        lib.orc_linear_requant.restype = None
+        lib.orc_linear_requant.argtypes = [_P, _P, _P, _P, _P, _P, Dyadic, C.POINTER(ShiftParams), Dyadic,
+                                           _P, i64, i32, i32]
+        lib.orc_attention.restype = None
+        lib.orc_attention.argtypes = [_P, _P, _P, _Dims, Dyadic, ShiftParams, Dyadic, _P, _P]
+        lib.orc_encoder_block.restype = None
+        lib.orc_encoder_block.argtypes = [_P, _P, C.POINTER(_BlockParams), _Dims, C.POINTER(_Taps)]
+        lib.orc_forward.restype = None
+        lib.orc_forward.argtypes = [_P, _P, C.POINTER(_BlockParams), i32, _P, _P, i32, i32, _Dims]
+        lib.orc_requant_vec.restype = None; lib.orc_requant_vec.argtypes = [_P, _P, i64, i32, i32]
+        lib.orc_rnd_shift_vec.restype = None; lib.orc_rnd_shift_vec.argtypes = [_P, _P, i64, i32]
+        lib.orc_isqrt10_vec.restype = None; lib.orc_isqrt10_vec.argtypes = [_P, _P, i64]
+        lib.orc_shiftexp_vec.restype = None; lib.orc_shiftexp_vec.argtypes = [_P, _P, i64, i32, i32]
+        _lib = lib
+    return _lib
+
+
+def _arr(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(_P)
+
+
+def _sp(p):
+    return p if isinstance(p, ShiftParams) else ShiftParams(int(p["i0"]), int(p["n_shift"]), int(p["m_bits"]), int(p["k_out"]))
+
+
+def _dy(p):
+    if p is None:
+        return Dyadic(0, 0)
+    return p if isinstance(p, Dyadic) else Dyadic(int(p[0]), int(p[1]))
+
+
+# ------------------------------------------------------------------ scalars
+def rnd_shift(v, c): return int(_L().orc_rnd_shift(int(v), int(c)))
+def clamp_k(v, k): return int(_L().orc_clamp_k(int(v), int(k)))
+def requant(v, b, c): return int(_L().orc_requant(int(v), int(b), int(c)))
+def shiftexp(i, i0, n_shift): return int(_L().orc_shiftexp(int(i), int(i0), int(n_shift)))
+def intdiv(i1, i2, k_out, m_bits): return int(_L().orc_intdiv(int(i1), int(i2), int(k_out), int(m_bits)))
+def isqrt10(v): return int(_L().orc_isqrt10(int(v)))
+
+
+def _vec(fn, v, *args):
+    v = _arr(v, np.int64)
+    out = np.empty_like(v)
+    fn(_ptr(v), _ptr(out), v.size, *args)
+    return out
+
+
+def requant_vec(v, b, c): return _vec(_L().orc_requant_vec, v, int(b), int(c))
+def rnd_shift_vec(v, c): return _vec(_L().orc_rnd_shift_vec, v, int(c))
+def isqrt10_vec(v): return _vec(_L().orc_isqrt10_vec, v)
+def shiftexp_vec(v, i0, n_shift): return _vec(_L().orc_shiftexp_vec, v, int(i0), int(n_shift))
+
+
+# ------------------------------------------------------------------ tensors
+def shiftgelu_raw(x, p):
+    x = _arr(x, np.int8)
+    g = np.empty(x.shape, np.int32)
+    _L().orc_shiftgelu_raw(_ptr(x), _ptr(g), x.size, _sp(p))
+    return g
+
+
+def shiftgelu(x, p, out_rq):
+    x = _arr(x, np.int8)
+    y = np.empty(x.shape, np.int8)
+    _L().orc_shiftgelu(_ptr(x), _ptr(y), x.size, _sp(p), _dy(out_rq))
+    return y
+
+
+def shiftmax(x, p, bias=None, H=1, T=1, cols=None):
+    """x: int8 [rows, ld]; the first `cols` entries of each row are used."""
+    x = _arr(x, np.int8)
+    rows, ld = x.shape
+    cols = ld if cols is None else cols
+    if bias is not None:
+        bias = _arr(bias, np.int8)
+    y = np.empty((rows, cols), np.int8)
+    _L().orc_shiftmax(_ptr(x), _ptr(bias), int(H), int(T), _ptr(y), rows, cols, ld, _sp(p))
+    return y
+
+
+def ilayernorm(x, gamma_q, beta_q, f_bits, c_shift):
+    x = _arr(x, np.int8)
+    g = _arr(gamma_q, np.int32); b = _arr(beta_q, np.int32)
+    rows, Cc = x.shape
+    assert g.shape == (Cc,) and b.shape == (Cc,)
+    y = np.empty_like(x)
+    _L().orc_ilayernorm(_ptr(x), _ptr(g), _ptr(b), _ptr(y), rows, Cc, int(f_bits), int(c_shift))
+    return y
+
+
+def linear_requant(x, w, bias, rq_b, rq_c, residual=None, res_rq=None, gelu=None, gelu_rq=None):
+    x = _arr(x, np.int8); w = _arr(w, np.int8)
+    M, K = x.shape
+    N, K2 = w.shape
+    assert K == K2
+    bias = None if bias is None else _arr(bias, np.int32)
+    rq_b = _arr(rq_b, np.int32); rq_c = _arr(rq_c, np.int32)
+    assert rq_b.shape == (N,) and rq_c.shape == (N,)
+    residual = None if residual is None else _arr(residual, np.int8)
+    if residual is not None:
+        assert residual.shape == (M, N)
+    y = np.empty((M, N), np.int8)
+    g = None if gelu is None else C.pointer(_sp(gelu))
+    _L().orc_linear_requant(_ptr(x), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c), _ptr(residual), _dy(res_rq),
+                            g, _dy(gelu_rq), _ptr(y), M, N, K)
+    return y
+
+
+def _dims(d):
+    return _Dims(int(d["B"]), int(d["T"]), int(d["C"]), int(d["H"]), int(d["F"]))
+
+
+def attention(qkv, dims, qk_rq, softmax, pv_rq, rel_bias=None, want_taps=False):
+    qkv = _arr(qkv, np.int8)
+    B, T, Cc, H = dims["B"], dims["T"], dims["C"], dims["H"]
+    assert qkv.shape == (B * T, 3 * Cc)
+    rel_bias = None if rel_bias is None else _arr(rel_bias, np.int8)
+    o = np.empty((B * T, Cc), np.int8)
+    sc = np.empty((B, H, T, T), np.int8) if want_taps else None
+    pr = np.empty((B, H, T, T), np.int8) if want_taps else None
+    _L().orc_attention(_ptr(qkv), _ptr(rel_bias), _ptr(o), _dims(dims), _dy(qk_rq), _sp(softmax), _dy(pv_rq),
+                       _ptr(sc), _ptr(pr))
+    return (o, sc, pr) if want_taps else o
+
+
+_PTR_FIELDS = {
+    "ln1_gamma": np.int32, "ln1_beta": np.int32, "w_qkv": np.int8, "bias_qkv": np.int32, "qkv_rq_b": np.int32,
+    "qkv_rq_c": np.int32, "rel_bias": np.int8, "w_proj": np.int8, "bias_proj": np.int32, "proj_rq_b": np.int32,
+    "proj_rq_c": np.int32, "ln2_gamma": np.int32, "ln2_beta": np.int32, "w_fc1": np.int8, "bias_fc1": np.int32,
+    "fc1_rq_b": np.int32, "fc1_rq_c": np.int32, "w_fc2": np.int8, "bias_fc2": np.int32, "fc2_rq_b": np.int32,
+    "fc2_rq_c": np.int32,
+}
+_INT_FIELDS = ("ln1_f_bits", "ln1_c_shift", "ln2_f_bits", "ln2_c_shift")
+_DY_FIELDS = ("qk_rq", "pv_rq", "res1_rq", "gelu_rq", "res2_rq")
+_SP_FIELDS = ("softmax", "gelu")
+
+
+def _block(p, keep):
+    """Build the C struct from a dict of numpy arrays / ints / tuples / dicts."""
+    bp = _BlockParams()
+    for name, dt in _PTR_FIELDS.items():
+        a = p.get(name)
+        if a is None:
+            setattr(bp, name, None)
+        else:
+            a = _arr(a, dt); keep.append(a)
+            setattr(bp, name, a.ctypes.data)
+    for name in _INT_FIELDS:
+        setattr(bp, name, int(p[name]))
+    for name in _DY_FIELDS:
+        setattr(bp, name, _dy(p[name]))
+    for name in _SP_FIELDS:
+        setattr(bp, name, _sp(p[name]))
+    return bp
+
+
+TAP_NAMES = ("u", "qkv", "scores", "probs", "o", "xhat", "v", "h")
+
+
+def encoder_block(x, params, dims, want_taps=False):
+    """x: int8 [B*T, C].  Returns y, or (y, taps dict) with every intermediate tensor."""
+    x = _arr(x, np.int8)
+    B, T, Cc, H, F = (dims[k] for k in "BTCHF")
+    R = B * T
+    assert x.shape == (R, Cc)
+    keep = []
+    bp = _block(params, keep)
+    y = np.empty_like(x)
+    taps = None
+    tp = None
+    if want_taps:
+        taps = {"u": np.empty((R, Cc), np.int8), "qkv": np.empty((R, 3 * Cc), np.int8),
+                "scores": np.empty((B, H, T, T), np.int8), "probs": np.empty((B, H, T, T), np.int8),
+                "o": np.empty((R, Cc), np.int8), "xhat": np.empty((R, Cc), np.int8),
+                "v": np.empty((R, Cc), np.int8), "h": np.empty((R, F), np.int8)}
+        t = _Taps(*[taps[n].ctypes.data for n in TAP_NAMES])
+        tp = C.pointer(t)
+    _L().orc_encoder_block(_ptr(x), _ptr(y), C.byref(bp), _dims(dims), tp)
+    return (y, taps) if want_taps else y
+
+
+def forward(x, blocks, dims, final_ln=None):
+    """x: int8 [B*T, C]; blocks: list of parameter dicts; final_ln: None or dict(gamma, beta, f_bits, c_shift)."""
+    x = _arr(x, np.int8)
+    keep = []
+    arr = (_BlockParams * len(blocks))(*[_block(p, keep) for p in blocks])
+    y = np.empty_like(x)
+    if final_ln is None:
+        g = b = None; fb = cs = 0
+    else:
+        g = _arr(final_ln["gamma"], np.int32); b = _arr(final_ln["beta"], np.int32)
+        fb, cs = int(final_ln["f_bits"]), int(final_ln["c_shift"])
+    _L().orc_forward(_ptr(x), _ptr(y), arr, len(blocks), _ptr(g), _ptr(b), fb, cs, _dims(dims))
+    return y
