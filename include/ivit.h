@@ -1,0 +1,181 @@
+/*
+ * ivit.h - C ABI of the MI355X (gfx950) integer-only ViT encoder library.
+ *
+ * The library computes the integer-only forward pass of a Vision-Transformer
+ * encoder as described in "I-ViT: Integer-only Quantization for Efficient
+ * Vision Transformer Inference" (arXiv 2207.01405): int8 x int8 -> int32
+ * Dense / MatMul with dyadic requantisation (Sec. 3.2), Shiftmax (Sec. 3.3,
+ * Algorithm 1), ShiftGELU (Sec. 3.4, Algorithm 2) and I-LayerNorm (Sec. 3.5).
+ *
+ * General rules
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
+ *    never allocates, frees or keeps device memory.  Scratch space for the
+ *    block / forward calls is a caller-supplied workspace.
+ *  - Parameter structs (ivit_shift_params, ivit_dyadic, ivit_dims,
+ *    ivit_block_params, ivit_final_ln, ivit_debug_taps) are HOST structs read
+ *    before the launch; pointers inside them are device pointers.
+ *  - `stream` is a hipStream_t (NULL = the default stream).  Work is enqueued
+ *    on it and the call returns without synchronising.
+ *  - Tensors are row-major and dense unless a leading dimension is given.
+ *    Weights are [N_out, K] with K contiguous.  Per-channel parameters are
+ *    int32 [N_out] device arrays.
+ *  - Every function returns IVIT_OK (0) or a negative ivit_status.  Arguments
+ *    are validated before anything is launched; a failed call launches nothing.
+ *    Nothing throws or aborts.  Input and output may not alias unless stated.
+ *  - Integer semantics: ">>" is an arithmetic shift (floor); round(v, c) =
+ *    (v + 2^(c-1)) >> c; clamp8(v) = min(max(v, -127), 127);
+ *    requant(v; b, c) = clamp8(round(b * v, c)) with the product in 64 bits.
+ *  - Values in device parameter arrays cannot be checked on the host: rq_b must
+ *    hold 1 <= b < 2^31 and rq_c must hold 1 <= c <= 46; other values give
+ *    unspecified results (never a fault).
+ */
+#ifndef IVIT_H
+#define IVIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    IVIT_OK = 0,
+    IVIT_ERR_NULL = -1,       /* a required pointer is NULL                                  */
+    IVIT_ERR_SHAPE = -2,      /* a dimension is negative, zero where not allowed, too large,
+                                 or not a multiple the kernels need                          */
+    IVIT_ERR_PARAM = -3,      /* an integer parameter is outside its stated range            */
+    IVIT_ERR_ALIGN = -4,      /* a pointer is not aligned as stated                          */
+    IVIT_ERR_WORKSPACE = -5,  /* workspace is NULL or smaller than ivit_workspace_bytes()    */
+    IVIT_ERR_HIP = -6         /* the HIP runtime reported an error at launch                 */
+} ivit_status;
+
+/* Parameters of ShiftExp / IntDiv (Algorithm 1, Eq. 13-16):
+ *   i0      I_0 = round(1 / S_in), the integer image of 1.0 at the input scale, >= 1
+ *   n_shift N, the left pre-shift of ShiftExp (Algorithm 1, footnote); i0 << n_shift <= 65535
+ *   m_bits  M of IntDiv (Eq. 16), k_out - 1 <= m_bits <= 31
+ *   k_out   output bit width of IntDiv, 2..8 (output scale 1 / 2^(k_out-1)) */
+typedef struct { int32_t i0, n_shift, m_bits, k_out; } ivit_shift_params;
+
+/* A per-tensor dyadic number b / 2^c (Eq. 9): 1 <= b < 2^31, 1 <= c <= 46. */
+typedef struct { int32_t b, c; } ivit_dyadic;
+
+/* Shape of an encoder: B images (or attention windows), T tokens each, width C,
+ * H heads (C = H * d, d in {32, 64}), MLP width F.  Rows R = B * T. */
+typedef struct { int32_t B, T, C, H, F; } ivit_dims;
+
+/* Everything one encoder block needs (Eq. 1-5).  Pointers are device pointers. */
+typedef struct {
+    const int32_t *ln1_gamma, *ln1_beta;  int32_t ln1_f_bits, ln1_c_shift;   /* I-LayerNorm before MSA   */
+    const int8_t  *w_qkv;                                                    /* [3C, C]: Q rows, K rows, V rows */
+    const int32_t *bias_qkv /*nullable*/, *qkv_rq_b, *qkv_rq_c;              /* [3C]                     */
+    ivit_dyadic    qk_rq;                 /* rescale of Q K^T to int8 scores; carries 1/sqrt(d) (Eq. 4)  */
+    const int8_t  *rel_bias;              /* nullable, [H, T, T]: added to the int8 scores (windowed attention) */
+    ivit_shift_params softmax;            /* Shiftmax on the score rows                                  */
+    ivit_dyadic    pv_rq;                 /* rescale of P V to int8                                      */
+    const int8_t  *w_proj;  const int32_t *bias_proj /*nullable*/, *proj_rq_b, *proj_rq_c;   /* [C, C], [C] */
+    ivit_dyadic    res1_rq;               /* rescale of the residual X before the first add (Eq. 1)      */
+    const int32_t *ln2_gamma, *ln2_beta;  int32_t ln2_f_bits, ln2_c_shift;   /* I-LayerNorm before MLP   */
+    const int8_t  *w_fc1;   const int32_t *bias_fc1 /*nullable*/, *fc1_rq_b, *fc1_rq_c;      /* [F, C], [F] */
+    ivit_shift_params gelu;  ivit_dyadic gelu_rq;                            /* ShiftGELU and its int8 rescale */
+    const int8_t  *w_fc2;   const int32_t *bias_fc2 /*nullable*/, *fc2_rq_b, *fc2_rq_c;      /* [C, F], [C] */
+    ivit_dyadic    res2_rq;               /* rescale of the residual Xhat before the second add (Eq. 2)  */
+} ivit_block_params;
+
+/* Optional device buffers that receive every intermediate int8 tensor of a block
+ * (any member may be NULL): u = LN1(x) [R,C]; qkv [R,3C]; scores = requantised Q K^T
+ * before the bias [B,H,T,T]; probs = Shiftmax output [B,H,T,T]; o = attention output
+ * [R,C]; xhat [R,C]; v = LN2(xhat) [R,C]; h = MLP hidden after ShiftGELU [R,F]. */
+typedef struct { int8_t *u, *qkv, *scores, *probs, *o, *xhat, *v, *h; } ivit_debug_taps;
+
+/* Final I-LayerNorm after the last block (optional in ivit_forward). */
+typedef struct { const int32_t *gamma, *beta; int32_t f_bits, c_shift; } ivit_final_ln;
+
+/* Text for a status code (static storage, never NULL). */
+const char* ivit_strerror(int status);
+
+/* Dense / MatMul with the dyadic pipeline (Sec. 3.2, Eq. 7-10), optionally fused
+ * with the residual add of Eq. 1-2 or with ShiftGELU (Eq. 5, Algorithm 2).
+ *   acc[m][j] = sum_k x[m][k] * w[j][k] + bias[j]                      (exact, int32)
+ *   y[m][j]   = requant(acc; rq_b[j], rq_c[j])                                        plain
+ *   y[m][j]   = clamp8(round(rq_b[j]*acc, rq_c[j]) + round(res_rq.b*residual[m][j], res_rq.c))  residual != NULL
+ *   y[m][j]   = requant(ShiftGELU(requant(acc; ...); *gelu); gelu_rq)                 gelu != NULL
+ * x [M,K] int8, w [N,K] int8, bias [N] int32 or NULL, rq_b / rq_c [N] int32,
+ * residual [M,N] int8 or NULL, y [M,N] int8.  residual and gelu exclude each other.
+ * Requirements: M >= 0 (M == 0 is a no-op), N >= 1, 16 <= K <= 65536, K % 16 == 0;
+ * x, w, y, residual 16-byte aligned, int32 arrays 4-byte aligned.
+ * res_rq / gelu_rq are ignored when the matching pointer is NULL.
+ * Errors: NULL, SHAPE, PARAM (dyadic or shift parameters out of range, both fusions at once), ALIGN, HIP. */
+int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias,
+                        const int32_t* rq_b, const int32_t* rq_c,
+                        const int8_t* residual, ivit_dyadic res_rq,
+                        const ivit_shift_params* gelu, ivit_dyadic gelu_rq,
+                        int8_t* y, int64_t M, int32_t N, int32_t K);
+
+/* Shiftmax (Sec. 3.3, Algorithm 1) on each row: subtract the row maximum, ShiftExp,
+ * IntDiv by the row sum, limit to 2^(k_out-1) - 1.
+ * x [rows, ld] int8 (the first `cols` entries of each row are used, ld >= cols),
+ * y [rows, cols] int8 dense.  bias (nullable) is an int8 table [H, T, cols] added to the
+ * input before the maximum is taken; row r uses bias[(r / T) % H][r % T][:] (rows ordered
+ * image-or-window major, then head, then query token).  With bias == NULL, H and T are ignored.
+ * Requirements: rows >= 0, 1 <= cols <= 1024; with bias: H >= 1, T >= 1.
+ * Errors: NULL, SHAPE, PARAM (shift parameters), HIP. */
+int ivit_shiftmax(void* stream, const int8_t* x, const int8_t* bias, int32_t H, int32_t T,
+                  int8_t* y, int64_t rows, int32_t cols, int32_t ld, ivit_shift_params p);
+
+/* ShiftGELU (Sec. 3.4, Algorithm 2) elementwise, the maximum of the algorithm read per
+ * element as max(I_p, 0), followed by the dyadic rescale of I_in * I_div to int8.
+ * x, y [n] int8 (y may alias x).  n >= 0.  Errors: NULL, SHAPE, PARAM, HIP. */
+int ivit_shiftgelu(void* stream, const int8_t* x, int8_t* y, int64_t n,
+                   ivit_shift_params p, ivit_dyadic out_rq);
+
+/* Same, but returns the raw product I_in * I_div (|value| <= 127 * 2^(k_out-1)) as int16,
+ * i.e. the tensor before its rescale to int8.  y16 [n] int16, 2-byte aligned. */
+int ivit_shiftgelu_raw(void* stream, const int8_t* x, int16_t* y16, int64_t n, ivit_shift_params p);
+
+/* I-LayerNorm (Sec. 3.5, Eq. 19-20) on each row of x [rows, C]:
+ *   mean = floor((sum x + floor(C/2)) / C);  var = floor(sum (x - mean)^2 / C);
+ *   std  = max(1, tenth iterate of I <- (I + floor(var / I)) >> 1 from I = 2^floor(bitlen(var)/2));
+ *   f = floor(2^f_bits / std);  y = clamp8(round((x - mean) * f * gamma_q[i] + beta_q[i], c_shift)).
+ * gamma_q, beta_q [C] int32 carry the output scale (folded by the host).
+ * Requirements: rows >= 0, 4 <= C <= 1024, C % 4 == 0, 1 <= f_bits <= 20, 1 <= c_shift <= 31,
+ * x and y 4-byte aligned; |gamma_q| < 2^15 and |(x - mean) * f * gamma_q + beta_q| < 2^31 - 2^(c_shift-1)
+ * (a precondition on device data; otherwise the result wraps modulo 2^32).
+ * Errors: NULL, SHAPE, PARAM, ALIGN, HIP. */
+int ivit_ilayernorm(void* stream, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
+                    int8_t* y, int64_t rows, int32_t C, int32_t f_bits, int32_t c_shift);
+
+/* Bytes of workspace ivit_encoder_block / ivit_forward need for these dimensions
+ * (0 if the dimensions are invalid). */
+size_t ivit_workspace_bytes(const ivit_dims* d);
+
+/* One encoder block (Eq. 1-2): xhat = MSA(LN(x)) + x;  y = MLP(LN(xhat)) + xhat, every
+ * step integer-only.  x, y [B*T, C] int8 (y must not alias x).  The packed qkv tensor is
+ * [B*T, 3C] with columns [0,C) = Q, [C,2C) = K, [2C,3C) = V and head h owning columns
+ * h*d .. (h+1)*d of each third.  taps may be NULL.
+ * Requirements: B >= 0, 1 <= T <= 256, C = H*d with d in {32, 64}, C % 16 == 0, F % 16 == 0,
+ * C, F <= 65536 (C <= 1024 for the LayerNorm); workspace 256-byte aligned.
+ * Errors: NULL, SHAPE, PARAM, ALIGN, WORKSPACE, HIP. */
+int ivit_encoder_block(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* p,
+                       const ivit_dims* d, void* workspace, size_t workspace_bytes,
+                       const ivit_debug_taps* taps);
+
+/* n_blocks encoder blocks in sequence (n_blocks >= 0), then the optional final
+ * I-LayerNorm.  `blocks` is a host array.  x, y [B*T, C] int8 (y must not alias x). */
+int ivit_forward(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* blocks, int32_t n_blocks,
+                 const ivit_final_ln* final_ln, const ivit_dims* d, void* workspace, size_t workspace_bytes);
+
+/* Fused multi-head attention on a packed qkv tensor [B*T, 3C] (Eq. 3-4), the step of the
+ * block between the QKV Dense and the projection:
+ *   A = requant(Q K^T; qk_rq) [+ rel_bias];  P = Shiftmax(rows of A);  O = requant(P V; pv_rq),
+ * heads concatenated into o [B*T, C].  tap_scores / tap_probs (nullable) receive A before the
+ * bias and P, each [B,H,T,T] int8.  Requirements as for ivit_encoder_block; qkv and o 16-byte aligned.
+ * Errors: NULL, SHAPE, PARAM, ALIGN, HIP. */
+int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8_t* o, const ivit_dims* d,
+                   ivit_dyadic qk_rq, ivit_shift_params softmax, ivit_dyadic pv_rq,
+                   int8_t* tap_scores, int8_t* tap_probs);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IVIT_H */

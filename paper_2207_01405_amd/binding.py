@@ -1,0 +1,234 @@
+"""Thin ctypes binding over the C ABI of libivit.so (see include/ivit.h).
+
+Argument marshalling only: every step of the hot path runs in the HIP kernels.  Functions carry the
+names of the C entry points; tensors are torch CUDA tensors (device memory and streams are all torch
+is used for).  There is no CPU path: loading fails loudly if the library has not been built.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libivit.so")
+
+IVIT_OK = 0
+ERRORS = {"NULL": -1, "SHAPE": -2, "PARAM": -3, "ALIGN": -4, "WORKSPACE": -5, "HIP": -6}
+
+EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftgelu", "ivit_shiftgelu_raw",
+           "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward")
+
+
+class ShiftParams(C.Structure):
+    _fields_ = [("i0", C.c_int32), ("n_shift", C.c_int32), ("m_bits", C.c_int32), ("k_out", C.c_int32)]
+
+
+class Dyadic(C.Structure):
+    _fields_ = [("b", C.c_int32), ("c", C.c_int32)]
+
+
+class Dims(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("B", "T", "C", "H", "F")]
+
+
+_P = C.c_void_p
+
+
+class BlockParams(C.Structure):
+    _fields_ = [
+        ("ln1_gamma", _P), ("ln1_beta", _P), ("ln1_f_bits", C.c_int32), ("ln1_c_shift", C.c_int32),
+        ("w_qkv", _P), ("bias_qkv", _P), ("qkv_rq_b", _P), ("qkv_rq_c", _P),
+        ("qk_rq", Dyadic), ("rel_bias", _P), ("softmax", ShiftParams), ("pv_rq", Dyadic),
+        ("w_proj", _P), ("bias_proj", _P), ("proj_rq_b", _P), ("proj_rq_c", _P), ("res1_rq", Dyadic),
+        ("ln2_gamma", _P), ("ln2_beta", _P), ("ln2_f_bits", C.c_int32), ("ln2_c_shift", C.c_int32),
+        ("w_fc1", _P), ("bias_fc1", _P), ("fc1_rq_b", _P), ("fc1_rq_c", _P),
+        ("gelu", ShiftParams), ("gelu_rq", Dyadic),
+        ("w_fc2", _P), ("bias_fc2", _P), ("fc2_rq_b", _P), ("fc2_rq_c", _P), ("res2_rq", Dyadic),
+    ]
+
+
+TAP_NAMES = ("u", "qkv", "scores", "probs", "o", "xhat", "v", "h")
+
+
+class DebugTaps(C.Structure):
+    _fields_ = [(n, _P) for n in TAP_NAMES]
+
+
+class FinalLN(C.Structure):
+    _fields_ = [("gamma", _P), ("beta", _P), ("f_bits", C.c_int32), ("c_shift", C.c_int32)]
+
+
+class IvitError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (where, strerror(status), status))
+
+
+_lib = None
+
+
+def load():
+    """Load libivit.so.  Raises if it is missing: build it with `python -m paper_2207_01405_amd.build`."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libivit.so is not built (%s); run `python -m paper_2207_01405_amd.build`" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    i32, i64 = C.c_int32, C.c_int64
+    lib.ivit_strerror.restype = C.c_char_p; lib.ivit_strerror.argtypes = [C.c_int]
+    lib.ivit_linear_requant.restype = C.c_int
+    lib.ivit_linear_requant.argtypes = [_P, _P, _P, _P, _P, _P, _P, Dyadic, C.POINTER(ShiftParams), Dyadic, _P, i64, i32, i32]
+    lib.ivit_shiftmax.restype = C.c_int
+    lib.ivit_shiftmax.argtypes = [_P, _P, _P, i32, i32, _P, i64, i32, i32, ShiftParams]
+    lib.ivit_shiftgelu.restype = C.c_int; lib.ivit_shiftgelu.argtypes = [_P, _P, _P, i64, ShiftParams, Dyadic]
+    lib.ivit_shiftgelu_raw.restype = C.c_int; lib.ivit_shiftgelu_raw.argtypes = [_P, _P, _P, i64, ShiftParams]
+    lib.ivit_ilayernorm.restype = C.c_int; lib.ivit_ilayernorm.argtypes = [_P, _P, _P, _P, _P, i64, i32, i32, i32]
+    lib.ivit_workspace_bytes.restype = C.c_size_t; lib.ivit_workspace_bytes.argtypes = [C.POINTER(Dims)]
+    lib.ivit_attention.restype = C.c_int
+    lib.ivit_attention.argtypes = [_P, _P, _P, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
+    lib.ivit_encoder_block.restype = C.c_int
+    lib.ivit_encoder_block.argtypes = [_P, _P, _P, C.POINTER(BlockParams), C.POINTER(Dims), _P, C.c_size_t,
+                                       C.POINTER(DebugTaps)]
+    lib.ivit_forward.restype = C.c_int
+    lib.ivit_forward.argtypes = [_P, _P, _P, C.POINTER(BlockParams), i32, C.POINTER(FinalLN), C.POINTER(Dims), _P,
+                                 C.c_size_t]
+    _lib = lib
+    return lib
+
+
+def strerror(status):
+    return load().ivit_strerror(int(status)).decode()
+
+
+def _check(status, where):
+    if status != IVIT_OK:
+        raise IvitError(status, where)
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream):
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def shift_params(p):
+    return p if isinstance(p, ShiftParams) else ShiftParams(int(p["i0"]), int(p["n_shift"]), int(p["m_bits"]), int(p["k_out"]))
+
+
+def dyadic(p):
+    if p is None:
+        return Dyadic(0, 0)
+    return p if isinstance(p, Dyadic) else Dyadic(int(p[0]), int(p[1]))
+
+
+def dims(d):
+    return d if isinstance(d, Dims) else Dims(*(int(d[k]) for k in "BTCHF"))
+
+
+# ------------------------------------------------------------------ entry points (same names as the C ABI)
+def ivit_linear_requant(x, w, bias, rq_b, rq_c, y, residual=None, res_rq=None, gelu=None, gelu_rq=None, stream=None):
+    M, K = x.shape
+    N = w.shape[0]
+    g = None if gelu is None else C.byref(shift_params(gelu))
+    st = load().ivit_linear_requant(_stream(stream), _ptr(x), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c),
+                                    _ptr(residual), dyadic(res_rq), g, dyadic(gelu_rq), _ptr(y), M, N, K)
+    _check(st, "ivit_linear_requant")
+    return y
+
+
+def ivit_shiftmax(x, y, p, bias=None, H=1, T=1, cols=None, stream=None):
+    rows, ld = x.shape
+    cols = ld if cols is None else cols
+    st = load().ivit_shiftmax(_stream(stream), _ptr(x), _ptr(bias), H, T, _ptr(y), rows, cols, ld, shift_params(p))
+    _check(st, "ivit_shiftmax")
+    return y
+
+
+def ivit_shiftgelu(x, y, p, out_rq, stream=None):
+    st = load().ivit_shiftgelu(_stream(stream), _ptr(x), _ptr(y), x.numel(), shift_params(p), dyadic(out_rq))
+    _check(st, "ivit_shiftgelu")
+    return y
+
+
+def ivit_shiftgelu_raw(x, y16, p, stream=None):
+    st = load().ivit_shiftgelu_raw(_stream(stream), _ptr(x), _ptr(y16), x.numel(), shift_params(p))
+    _check(st, "ivit_shiftgelu_raw")
+    return y16
+
+
+def ivit_ilayernorm(x, gamma_q, beta_q, y, f_bits, c_shift, stream=None):
+    rows, Cc = x.shape
+    st = load().ivit_ilayernorm(_stream(stream), _ptr(x), _ptr(gamma_q), _ptr(beta_q), _ptr(y), rows, Cc,
+                                int(f_bits), int(c_shift))
+    _check(st, "ivit_ilayernorm")
+    return y
+
+
+def ivit_workspace_bytes(d):
+    return int(load().ivit_workspace_bytes(C.byref(dims(d))))
+
+
+def ivit_attention(qkv, o, d, qk_rq, softmax, pv_rq, rel_bias=None, tap_scores=None, tap_probs=None, stream=None):
+    st = load().ivit_attention(_stream(stream), _ptr(qkv), _ptr(rel_bias), _ptr(o), C.byref(dims(d)), dyadic(qk_rq),
+                               shift_params(softmax), dyadic(pv_rq), _ptr(tap_scores), _ptr(tap_probs))
+    _check(st, "ivit_attention")
+    return o
+
+
+_PTR_FIELDS = ("ln1_gamma", "ln1_beta", "w_qkv", "bias_qkv", "qkv_rq_b", "qkv_rq_c", "rel_bias", "w_proj", "bias_proj",
+               "proj_rq_b", "proj_rq_c", "ln2_gamma", "ln2_beta", "w_fc1", "bias_fc1", "fc1_rq_b", "fc1_rq_c", "w_fc2",
+               "bias_fc2", "fc2_rq_b", "fc2_rq_c")
+_INT_FIELDS = ("ln1_f_bits", "ln1_c_shift", "ln2_f_bits", "ln2_c_shift")
+_DY_FIELDS = ("qk_rq", "pv_rq", "res1_rq", "gelu_rq", "res2_rq")
+_SP_FIELDS = ("softmax", "gelu")
+
+
+def block_params(p):
+    """BlockParams struct from a dict whose tensor entries are torch CUDA tensors (kept alive by the caller)."""
+    if isinstance(p, BlockParams):
+        return p
+    bp = BlockParams()
+    for k in _PTR_FIELDS:
+        setattr(bp, k, _ptr(p.get(k)))
+    for k in _INT_FIELDS:
+        setattr(bp, k, int(p[k]))
+    for k in _DY_FIELDS:
+        setattr(bp, k, dyadic(p[k]))
+    for k in _SP_FIELDS:
+        setattr(bp, k, shift_params(p[k]))
+    return bp
+
+
+def to_device(p, device="cuda"):
+    """Copy the numpy arrays of a parameter dict to the device (torch tensors); other entries are kept."""
+    import numpy as np
+    import torch
+    return {k: (torch.from_numpy(np.ascontiguousarray(v)).to(device) if isinstance(v, np.ndarray) else v)
+            for k, v in p.items()}
+
+
+def ivit_encoder_block(x, y, p, d, workspace, taps=None, stream=None):
+    tp = None
+    if taps is not None:
+        tp = C.byref(DebugTaps(*[_ptr(taps.get(n)) for n in TAP_NAMES]))
+    bp = block_params(p)
+    st = load().ivit_encoder_block(_stream(stream), _ptr(x), _ptr(y), C.byref(bp), C.byref(dims(d)),
+                                   _ptr(workspace), workspace.numel() * workspace.element_size(), tp)
+    _check(st, "ivit_encoder_block")
+    return y
+
+
+def ivit_forward(x, y, blocks, d, workspace, final_ln=None, stream=None):
+    arr = (BlockParams * max(1, len(blocks)))(*[block_params(p) for p in blocks])
+    fl = None
+    if final_ln is not None:
+        fl = C.byref(FinalLN(_ptr(final_ln["gamma"]), _ptr(final_ln["beta"]), int(final_ln["f_bits"]),
+                             int(final_ln["c_shift"])))
+    st = load().ivit_forward(_stream(stream), _ptr(x), _ptr(y), arr, len(blocks), fl, C.byref(dims(d)),
+                             _ptr(workspace), workspace.numel() * workspace.element_size())
+    _check(st, "ivit_forward")
+    return y

@@ -1,0 +1,278 @@
+// C-ABI layer of libivit.so: argument validation (host only, before any launch), the launch sequence of
+// one encoder block (I-ViT, arXiv 2207.01405, Eq. 1-5) and of the block stack.  See include/ivit.h.
+#include "../../include/ivit.h"
+
+#include "ivit_kernels.hpp"
+
+namespace {
+
+using ivit::Dyadic;
+using ivit::ShiftParams;
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+inline int check_dyadic(ivit_dyadic d) { return (d.b >= 1 && d.c >= 1 && d.c <= 46) ? IVIT_OK : IVIT_ERR_PARAM; }
+
+inline int check_shift(const ivit_shift_params& p) {
+    if (p.i0 < 1 || p.n_shift < 0 || p.n_shift > 16) return IVIT_ERR_PARAM;
+    if (((int64_t)p.i0 << p.n_shift) > 65535) return IVIT_ERR_PARAM;
+    if (p.k_out < 2 || p.k_out > 8) return IVIT_ERR_PARAM;
+    if (p.m_bits < p.k_out - 1 || p.m_bits > 31) return IVIT_ERR_PARAM;
+    return IVIT_OK;
+}
+
+inline int check_ln(int32_t C, int32_t f_bits, int32_t c_shift) {
+    if (C < 4 || C > 1024 || (C & 3)) return IVIT_ERR_SHAPE;
+    if (f_bits < 1 || f_bits > 20 || c_shift < 1 || c_shift > 31) return IVIT_ERR_PARAM;
+    return IVIT_OK;
+}
+
+inline ShiftParams sp(const ivit_shift_params& p) { return ShiftParams{p.i0, p.n_shift, p.m_bits, p.k_out}; }
+inline Dyadic dy(ivit_dyadic d) { return Dyadic{d.b, d.c}; }
+inline int hip_status(hipError_t e) { return e == hipSuccess ? IVIT_OK : IVIT_ERR_HIP; }
+
+int check_dims(const ivit_dims* d) {
+    if (!d) return IVIT_ERR_NULL;
+    if (d->B < 0 || d->T < 1 || d->T > 256 || d->C < 16 || d->H < 1 || d->F < 16) return IVIT_ERR_SHAPE;
+    if (d->C % d->H != 0) return IVIT_ERR_SHAPE;
+    const int hd = d->C / d->H;
+    if (hd != 32 && hd != 64) return IVIT_ERR_SHAPE;
+    if ((d->C & 15) || (d->F & 15) || d->C > 1024 || d->F > 65536) return IVIT_ERR_SHAPE;
+    if ((int64_t)d->B * d->T > 0x7fffffffLL) return IVIT_ERR_SHAPE;
+    return IVIT_OK;
+}
+
+inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Workspace { int8_t *act0, *act1, *u, *qkv, *o, *xhat, *h; };
+
+size_t carve(const ivit_dims* d, void* base, Workspace* w) {
+    const size_t R = (size_t)d->B * d->T, C = d->C, F = d->F;
+    size_t off = 0;
+    auto take = [&](size_t n) { size_t o = off; off += up256(n); return base ? static_cast<int8_t*>(base) + o : nullptr; };
+    int8_t* a0 = take(R * C); int8_t* a1 = take(R * C); int8_t* u = take(R * C); int8_t* qkv = take(R * 3 * C);
+    int8_t* o = take(R * C); int8_t* xh = take(R * C); int8_t* h = take(R * F);
+    if (w) *w = Workspace{a0, a1, u, qkv, o, xh, h};
+    return off;
+}
+
+int check_block(const ivit_block_params* p, const ivit_dims* d) {
+    if (!p) return IVIT_ERR_NULL;
+    if (!p->ln1_gamma || !p->ln1_beta || !p->w_qkv || !p->qkv_rq_b || !p->qkv_rq_c || !p->w_proj || !p->proj_rq_b ||
+        !p->proj_rq_c || !p->ln2_gamma || !p->ln2_beta || !p->w_fc1 || !p->fc1_rq_b || !p->fc1_rq_c || !p->w_fc2 ||
+        !p->fc2_rq_b || !p->fc2_rq_c)
+        return IVIT_ERR_NULL;
+    int st;
+    if ((st = check_ln(d->C, p->ln1_f_bits, p->ln1_c_shift)) != IVIT_OK) return st;
+    if ((st = check_ln(d->C, p->ln2_f_bits, p->ln2_c_shift)) != IVIT_OK) return st;
+    if ((st = check_dyadic(p->qk_rq)) != IVIT_OK || (st = check_dyadic(p->pv_rq)) != IVIT_OK ||
+        (st = check_dyadic(p->res1_rq)) != IVIT_OK || (st = check_dyadic(p->res2_rq)) != IVIT_OK ||
+        (st = check_dyadic(p->gelu_rq)) != IVIT_OK)
+        return st;
+    if ((st = check_shift(p->softmax)) != IVIT_OK || (st = check_shift(p->gelu)) != IVIT_OK) return st;
+    if (!aligned(p->w_qkv, 16) || !aligned(p->w_proj, 16) || !aligned(p->w_fc1, 16) || !aligned(p->w_fc2, 16))
+        return IVIT_ERR_ALIGN;
+    const void* i32s[] = {p->ln1_gamma, p->ln1_beta, p->bias_qkv, p->qkv_rq_b, p->qkv_rq_c, p->bias_proj, p->proj_rq_b,
+                          p->proj_rq_c, p->ln2_gamma, p->ln2_beta, p->bias_fc1, p->fc1_rq_b, p->fc1_rq_c, p->bias_fc2,
+                          p->fc2_rq_b, p->fc2_rq_c};
+    for (const void* q : i32s)
+        if (!aligned(q, 4)) return IVIT_ERR_ALIGN;
+    return IVIT_OK;
+}
+
+// Launch sequence of one block on buffers of the carved workspace.  Arguments already validated.
+hipError_t run_block(hipStream_t s, const int8_t* x, int8_t* y, const ivit_block_params* p, const ivit_dims* d,
+                     const Workspace& w, const ivit_debug_taps* taps) {
+    const int64_t R = (int64_t)d->B * d->T;
+    const int C = d->C, F = d->F;
+    if (R == 0) return hipSuccess;
+    hipError_t e;
+    auto tap = [&](int8_t* dst, const int8_t* src, size_t n) -> hipError_t {
+        return dst ? hipMemcpyAsync(dst, src, n, hipMemcpyDeviceToDevice, s) : hipSuccess;
+    };
+    // u = LN1(x)
+    if ((e = ivit::launch_ilayernorm(s, x, p->ln1_gamma, p->ln1_beta, w.u, R, C, p->ln1_f_bits, p->ln1_c_shift))) return e;
+    if (taps && (e = tap(taps->u, w.u, (size_t)R * C))) return e;
+    // qkv = Dense(u)
+    ivit::LinearArgs la{};
+    la.x = w.u; la.w = p->w_qkv; la.bias = p->bias_qkv; la.rq_b = p->qkv_rq_b; la.rq_c = p->qkv_rq_c;
+    la.residual = nullptr; la.gelu = false; la.y = w.qkv; la.M = R; la.N = 3 * C; la.K = C;
+    if ((e = ivit::launch_linear(s, la))) return e;
+    if (taps && (e = tap(taps->qkv, w.qkv, (size_t)R * 3 * C))) return e;
+    // o = attention(qkv)
+    ivit::AttentionArgs aa{};
+    aa.qkv = w.qkv; aa.rel_bias = p->rel_bias; aa.o = w.o; aa.B = d->B; aa.T = d->T; aa.C = C; aa.H = d->H;
+    aa.qk_rq = dy(p->qk_rq); aa.sm = sp(p->softmax); aa.pv_rq = dy(p->pv_rq);
+    aa.tap_scores = taps ? taps->scores : nullptr; aa.tap_probs = taps ? taps->probs : nullptr;
+    if ((e = ivit::launch_attention(s, aa))) return e;
+    if (taps && (e = tap(taps->o, w.o, (size_t)R * C))) return e;
+    // xhat = Dense(o) + x
+    la = ivit::LinearArgs{};
+    la.x = w.o; la.w = p->w_proj; la.bias = p->bias_proj; la.rq_b = p->proj_rq_b; la.rq_c = p->proj_rq_c;
+    la.residual = x; la.res_rq = dy(p->res1_rq); la.gelu = false; la.y = w.xhat; la.M = R; la.N = C; la.K = C;
+    if ((e = ivit::launch_linear(s, la))) return e;
+    if (taps && (e = tap(taps->xhat, w.xhat, (size_t)R * C))) return e;
+    // v = LN2(xhat)   (reuses the u buffer)
+    if ((e = ivit::launch_ilayernorm(s, w.xhat, p->ln2_gamma, p->ln2_beta, w.u, R, C, p->ln2_f_bits, p->ln2_c_shift))) return e;
+    if (taps && (e = tap(taps->v, w.u, (size_t)R * C))) return e;
+    // h = ShiftGELU(Dense(v))
+    la = ivit::LinearArgs{};
+    la.x = w.u; la.w = p->w_fc1; la.bias = p->bias_fc1; la.rq_b = p->fc1_rq_b; la.rq_c = p->fc1_rq_c;
+    la.residual = nullptr; la.gelu = true; la.gelu_p = sp(p->gelu); la.gelu_rq = dy(p->gelu_rq);
+    la.y = w.h; la.M = R; la.N = F; la.K = C;
+    if ((e = ivit::launch_linear(s, la))) return e;
+    if (taps && (e = tap(taps->h, w.h, (size_t)R * F))) return e;
+    // y = Dense(h) + xhat
+    la = ivit::LinearArgs{};
+    la.x = w.h; la.w = p->w_fc2; la.bias = p->bias_fc2; la.rq_b = p->fc2_rq_b; la.rq_c = p->fc2_rq_c;
+    la.residual = w.xhat; la.res_rq = dy(p->res2_rq); la.gelu = false; la.y = y; la.M = R; la.N = C; la.K = F;
+    return ivit::launch_linear(s, la);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ivit_strerror(int status) {
+    switch (status) {
+        case IVIT_OK: return "ok";
+        case IVIT_ERR_NULL: return "a required pointer is NULL";
+        case IVIT_ERR_SHAPE: return "unsupported shape";
+        case IVIT_ERR_PARAM: return "integer parameter out of range";
+        case IVIT_ERR_ALIGN: return "pointer not aligned as required";
+        case IVIT_ERR_WORKSPACE: return "workspace missing or too small";
+        case IVIT_ERR_HIP: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias, const int32_t* rq_b,
+                        const int32_t* rq_c, const int8_t* residual, ivit_dyadic res_rq, const ivit_shift_params* gelu,
+                        ivit_dyadic gelu_rq, int8_t* y, int64_t M, int32_t N, int32_t K) {
+    if (!x || !w || !rq_b || !rq_c || !y) return IVIT_ERR_NULL;
+    if (M < 0 || N < 1 || K < 16 || K > 65536 || (K & 15)) return IVIT_ERR_SHAPE;
+    if ((M + 127) / 128 * (int64_t)((N + 127) / 128) > 0x7fffffffLL) return IVIT_ERR_SHAPE;
+    if (residual && gelu) return IVIT_ERR_PARAM;
+    int st;
+    if (residual && (st = check_dyadic(res_rq)) != IVIT_OK) return st;
+    if (gelu && ((st = check_shift(*gelu)) != IVIT_OK || (st = check_dyadic(gelu_rq)) != IVIT_OK)) return st;
+    if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16) || (residual && !aligned(residual, 16))) return IVIT_ERR_ALIGN;
+    if (!aligned(rq_b, 4) || !aligned(rq_c, 4) || (bias && !aligned(bias, 4))) return IVIT_ERR_ALIGN;
+    ivit::LinearArgs a{};
+    a.x = x; a.w = w; a.bias = bias; a.rq_b = rq_b; a.rq_c = rq_c; a.residual = residual;
+    a.res_rq = residual ? dy(res_rq) : Dyadic{1, 1};
+    a.gelu = gelu != nullptr;
+    if (gelu) { a.gelu_p = sp(*gelu); a.gelu_rq = dy(gelu_rq); }
+    a.y = y; a.M = M; a.N = N; a.K = K;
+    return hip_status(ivit::launch_linear(static_cast<hipStream_t>(stream), a));
+}
+
+int ivit_shiftmax(void* stream, const int8_t* x, const int8_t* bias, int32_t H, int32_t T, int8_t* y, int64_t rows,
+                  int32_t cols, int32_t ld, ivit_shift_params p) {
+    if (!x || !y) return IVIT_ERR_NULL;
+    if (rows < 0 || cols < 1 || cols > 1024 || ld < cols) return IVIT_ERR_SHAPE;
+    if (bias && (H < 1 || T < 1)) return IVIT_ERR_SHAPE;
+    int st = check_shift(p);
+    if (st != IVIT_OK) return st;
+    return hip_status(ivit::launch_shiftmax(static_cast<hipStream_t>(stream), x, bias, bias ? H : 1, bias ? T : 1, y,
+                                            rows, cols, ld, sp(p)));
+}
+
+int ivit_shiftgelu(void* stream, const int8_t* x, int8_t* y, int64_t n, ivit_shift_params p, ivit_dyadic out_rq) {
+    if (!x || !y) return IVIT_ERR_NULL;
+    if (n < 0) return IVIT_ERR_SHAPE;
+    int st;
+    if ((st = check_shift(p)) != IVIT_OK || (st = check_dyadic(out_rq)) != IVIT_OK) return st;
+    return hip_status(ivit::launch_shiftgelu(static_cast<hipStream_t>(stream), x, y, nullptr, n, sp(p), dy(out_rq)));
+}
+
+int ivit_shiftgelu_raw(void* stream, const int8_t* x, int16_t* y16, int64_t n, ivit_shift_params p) {
+    if (!x || !y16) return IVIT_ERR_NULL;
+    if (n < 0) return IVIT_ERR_SHAPE;
+    int st = check_shift(p);
+    if (st != IVIT_OK) return st;
+    if (!aligned(y16, 2)) return IVIT_ERR_ALIGN;
+    return hip_status(ivit::launch_shiftgelu(static_cast<hipStream_t>(stream), x, nullptr, y16, n, sp(p), Dyadic{1, 1}));
+}
+
+int ivit_ilayernorm(void* stream, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q, int8_t* y,
+                    int64_t rows, int32_t C, int32_t f_bits, int32_t c_shift) {
+    if (!x || !gamma_q || !beta_q || !y) return IVIT_ERR_NULL;
+    if (rows < 0) return IVIT_ERR_SHAPE;
+    int st = check_ln(C, f_bits, c_shift);
+    if (st != IVIT_OK) return st;
+    if (!aligned(x, 4) || !aligned(y, 4) || !aligned(gamma_q, 4) || !aligned(beta_q, 4)) return IVIT_ERR_ALIGN;
+    return hip_status(ivit::launch_ilayernorm(static_cast<hipStream_t>(stream), x, gamma_q, beta_q, y, rows, C, f_bits, c_shift));
+}
+
+size_t ivit_workspace_bytes(const ivit_dims* d) {
+    if (check_dims(d) != IVIT_OK) return 0;
+    return carve(d, nullptr, nullptr) + 256;      // never 0 for valid dimensions, even with B == 0
+}
+
+int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8_t* o, const ivit_dims* d,
+                   ivit_dyadic qk_rq, ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores,
+                   int8_t* tap_probs) {
+    if (!qkv || !o || !d) return IVIT_ERR_NULL;
+    int st;
+    if ((st = check_dims(d)) != IVIT_OK) return st;
+    if ((st = check_dyadic(qk_rq)) != IVIT_OK || (st = check_dyadic(pv_rq)) != IVIT_OK ||
+        (st = check_shift(softmax)) != IVIT_OK)
+        return st;
+    if (!aligned(qkv, 16) || !aligned(o, 16)) return IVIT_ERR_ALIGN;
+    ivit::AttentionArgs a{};
+    a.qkv = qkv; a.rel_bias = rel_bias; a.o = o; a.B = d->B; a.T = d->T; a.C = d->C; a.H = d->H;
+    a.qk_rq = dy(qk_rq); a.sm = sp(softmax); a.pv_rq = dy(pv_rq); a.tap_scores = tap_scores; a.tap_probs = tap_probs;
+    return hip_status(ivit::launch_attention(static_cast<hipStream_t>(stream), a));
+}
+
+int ivit_encoder_block(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* p, const ivit_dims* d,
+                       void* workspace, size_t workspace_bytes, const ivit_debug_taps* taps) {
+    if (!x || !y || !p || !d) return IVIT_ERR_NULL;
+    int st;
+    if ((st = check_dims(d)) != IVIT_OK) return st;
+    if ((st = check_block(p, d)) != IVIT_OK) return st;
+    if (!workspace || workspace_bytes < ivit_workspace_bytes(d)) return IVIT_ERR_WORKSPACE;
+    if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(y, 16)) return IVIT_ERR_ALIGN;
+    Workspace w;
+    carve(d, workspace, &w);
+    return hip_status(run_block(static_cast<hipStream_t>(stream), x, y, p, d, w, taps));
+}
+
+int ivit_forward(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* blocks, int32_t n_blocks,
+                 const ivit_final_ln* final_ln, const ivit_dims* d, void* workspace, size_t workspace_bytes) {
+    if (!x || !y || !d || (n_blocks > 0 && !blocks)) return IVIT_ERR_NULL;
+    if (n_blocks < 0) return IVIT_ERR_SHAPE;
+    int st;
+    if ((st = check_dims(d)) != IVIT_OK) return st;
+    for (int l = 0; l < n_blocks; ++l)
+        if ((st = check_block(&blocks[l], d)) != IVIT_OK) return st;
+    if (final_ln) {
+        if (!final_ln->gamma || !final_ln->beta) return IVIT_ERR_NULL;
+        if ((st = check_ln(d->C, final_ln->f_bits, final_ln->c_shift)) != IVIT_OK) return st;
+        if (!aligned(final_ln->gamma, 4) || !aligned(final_ln->beta, 4)) return IVIT_ERR_ALIGN;
+    }
+    if (!workspace || workspace_bytes < ivit_workspace_bytes(d)) return IVIT_ERR_WORKSPACE;
+    if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(y, 16)) return IVIT_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    Workspace w;
+    carve(d, workspace, &w);
+    const size_t n = (size_t)d->B * d->T * d->C;
+    if (n == 0) return IVIT_OK;
+    // block l reads cur and writes into the other ping-pong buffer; the last producer writes y directly
+    const int8_t* cur = x;
+    for (int l = 0; l < n_blocks; ++l) {
+        const bool last = (l == n_blocks - 1) && !final_ln;
+        int8_t* dst = last ? y : (cur == w.act0 ? w.act1 : w.act0);
+        hipError_t e = run_block(s, cur, dst, &blocks[l], d, w, nullptr);
+        if (e != hipSuccess) return IVIT_ERR_HIP;
+        cur = dst;
+    }
+    if (final_ln)
+        return hip_status(ivit::launch_ilayernorm(s, cur, final_ln->gamma, final_ln->beta, y, (int64_t)d->B * d->T, d->C,
+                                                  final_ln->f_bits, final_ln->c_shift));
+    if (n_blocks == 0) return hip_status(hipMemcpyAsync(y, x, n, hipMemcpyDeviceToDevice, s));
+    return IVIT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,205 @@
+// Fused integer multi-head attention for gfx950 (I-ViT, arXiv 2207.01405: Eq. 3-4 with the dyadic
+// pipeline of Sec. 3.2 and Shiftmax of Sec. 3.3 / Algorithm 1):
+//   A = requant(Q K^T) [+ relative-position bias];  P = Shiftmax(rows of A);  O = requant(P V).
+//
+// One workgroup (4 wavefronts) handles one (image-or-window, head) at a time: K and a transposed copy
+// of V live in LDS, and each wavefront takes 16 query tokens at a time.  Scores are produced by
+// v_mfma_i32_16x16x64_i8 (d = 64) or 16x16x32 (d = 32) in the orientation keys x queries, so that a lane
+// holds, for ONE query, four keys of every 16-key tile: the whole score row of a query sits in the
+// registers of four lanes.  Max and sum need an in-lane pass plus two cross-lane steps; ShiftExp is a
+// table lookup on Delta = max - value (at most 510); the packed int8 probabilities are already laid out as
+// the MFMA "B" operand (contraction index = key) of O^T = V^T P^T, so scores and probabilities never
+// leave registers.  The key order inside each 64-key chunk of the V^T rows is permuted when V is
+// written to LDS to match that register layout, and the rows (head features) are permuted so that a
+// lane ends up with d/4 consecutive features of its query: one 16-byte (d = 64) store.
+#include <algorithm>
+
+#include "ivit_kernels.hpp"
+
+namespace ivit {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// position of key k inside a V^T row: 64-key chunk c = k / 64; inside it lane group g = (k % 16) / 4 owns
+// 16 consecutive bytes ordered by tile (k / 16) % 4, then k % 4
+__device__ __forceinline__ int vt_pos(int k) {
+    return (k & ~63) + ((k >> 2) & 3) * 16 + ((k >> 4) & 3) * 4 + (k & 3);
+}
+
+template <int D, int NKT>
+__global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict__ qkv,
+                                                        const int8_t* __restrict__ rel_bias,
+                                                        int8_t* __restrict__ o, int n_items, int T, int C, int H,
+                                                        Dyadic qk, ShiftParams sm, Dyadic pv,
+                                                        int8_t* __restrict__ tap_s, int8_t* __restrict__ tap_p) {
+    constexpr int KROW = D + 16;                  // K row pitch (bytes)
+    constexpr int NKC = (NKT + 3) / 4;            // 64-key chunks of the P V contraction
+    constexpr int VROW = NKC * 64 + 16;           // V^T row pitch (bytes)
+    constexpr int ND = D / 16;                    // 16-feature tiles of the output
+    constexpr int DCH = D / 16;                   // 16-byte chunks per K / V row
+    __shared__ __align__(16) int8_t Ks[NKT * 16 * KROW];
+    __shared__ __align__(16) int8_t Vt[D * VROW];
+    __shared__ uint16_t lut[512];
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int li = lane & 15, lg = lane >> 4;
+    for (int i = tid; i < 512; i += 256) lut[i] = (uint16_t)shiftexp(-i, sm.i0, sm.n_shift);
+    // keys beyond the 16-key tiles but inside the last 64-key chunk multiply probabilities that are zero;
+    // clear them once so that no uninitialised LDS is ever read
+    for (int i = tid; i < D * VROW / 4; i += 256) reinterpret_cast<uint32_t*>(Vt)[i] = 0u;
+
+    const int sh = sm.m_bits - (sm.k_out - 1);
+    const uint32_t top = (1u << (sm.k_out - 1)) - 1u;
+    const int nqt = (T + 15) >> 4;
+    const bool fast_qk = qk.b < 32768 && qk.c >= 16 && qk.c <= 31;
+    const bool fast_pv = pv.b < 32768 && pv.c >= 16 && pv.c <= 31;
+
+    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int b = item / H, h = item % H;
+        const int8_t* base = qkv + (int64_t)b * T * 3 * C + h * D;
+        __syncthreads();                           // table ready / previous item's readers done
+        for (int c = tid; c < NKT * 16 * DCH; c += 256) {
+            const int key = c / DCH, part = c % DCH;
+            v4i kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
+            if (key < T) {
+                kv = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + C + 16 * part);
+                vv = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + 2 * C + 16 * part);
+            }
+            *reinterpret_cast<v4i*>(&Ks[key * KROW + 16 * part]) = kv;
+            const int pos = vt_pos(key);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int dd = 16 * part + e;      // feature; stored in row 16 n + 4 g' + r with dd = g' (D/4) + 4 n + r
+                const int row = ((dd % (D / 4)) >> 2) * 16 + (dd / (D / 4)) * 4 + (dd & 3);
+                Vt[row * VROW + pos] = (int8_t)(vv[e >> 2] >> (8 * (e & 3)));
+            }
+        }
+        __syncthreads();
+
+        for (int qt = wv; qt < nqt; qt += 4) {
+            const int q = qt * 16 + li;            // this lane's query token
+            const int qc = min(q, T - 1);
+            const int8_t* qp = base + (int64_t)qc * 3 * C;
+            int32_t sc[NKT][4];
+            // ---- scores: S^T tile t = K_t (16 keys x D) . Q^T (D x 16 queries)
+            if (D == 64) {
+                const v4i qf = *reinterpret_cast<const v4i*>(qp + 16 * lg);
+#pragma unroll
+                for (int t = 0; t < NKT; ++t) {
+                    const v4i kf = *reinterpret_cast<const v4i*>(&Ks[(16 * t + li) * KROW + 16 * lg]);
+                    const v4i r = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
+                    sc[t][0] = r[0]; sc[t][1] = r[1]; sc[t][2] = r[2]; sc[t][3] = r[3];
+                }
+            } else {
+                const long qf = *reinterpret_cast<const long*>(qp + 8 * lg);
+#pragma unroll
+                for (int t = 0; t < NKT; ++t) {
+                    const long kf = *reinterpret_cast<const long*>(&Ks[(16 * t + li) * KROW + 8 * lg]);
+                    const v4i r = __builtin_amdgcn_mfma_i32_16x16x32_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
+                    sc[t][0] = r[0]; sc[t][1] = r[1]; sc[t][2] = r[2]; sc[t][3] = r[3];
+                }
+            }
+            // ---- requantise, add the bias, row maximum.  Lane (li, lg) holds keys 16 t + 4 lg + r.
+            const int64_t tap_row = ((int64_t)item * T + qc) * T;
+            const int8_t* brow = rel_bias ? rel_bias + ((int64_t)h * T + qc) * T : nullptr;
+            int32_t mx = INT32_MIN;
+#pragma unroll
+            for (int t = 0; t < NKT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int key = 16 * t + 4 * lg + r;
+                    int32_t a = fast_qk ? clamp8(rnd_shift_b15(sc[t][r], qk.b, qk.c)) : requant64(sc[t][r], qk.b, qk.c);
+                    if (key < T) {
+                        if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a;
+                        if (brow) a += brow[key];
+                        mx = max(mx, a);
+                    }
+                    sc[t][r] = a;
+                }
+            mx = max(mx, __shfl_xor(mx, 16, kWave));
+            mx = max(mx, __shfl_xor(mx, 32, kWave));
+            // ---- ShiftExp by table, row sum, IntDiv
+            int32_t sum = 0;
+#pragma unroll
+            for (int t = 0; t < NKT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int key = 16 * t + 4 * lg + r;
+                    const int32_t e = key < T ? (int32_t)lut[mx - sc[t][r]] : 0;
+                    sc[t][r] = e;
+                    sum += e;
+                }
+            sum += __shfl_xor(sum, 16, kWave);
+            sum += __shfl_xor(sum, 32, kWave);
+            const uint32_t inv = (1u << sm.m_bits) / (uint32_t)sum;
+            uint32_t pk[NKC * 4];
+#pragma unroll
+            for (int t = 0; t < NKC * 4; ++t) pk[t] = 0u;
+#pragma unroll
+            for (int t = 0; t < NKT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const uint32_t p = min((inv * (uint32_t)sc[t][r]) >> sh, top);
+                    const int key = 16 * t + 4 * lg + r;
+                    if (tap_p && q < T && key < T) tap_p[tap_row + key] = (int8_t)p;
+                    pk[t] |= p << (8 * r);
+                }
+            // ---- O^T = V^T P^T : "A" = V^T rows (features), "B" = packed probabilities (keys x queries)
+            v4i oacc[ND];
+#pragma unroll
+            for (int n = 0; n < ND; ++n) oacc[n] = v4i{0, 0, 0, 0};
+#pragma unroll
+            for (int c = 0; c < NKC; ++c) {
+                const v4i pf = {(int)pk[4 * c], (int)pk[4 * c + 1], (int)pk[4 * c + 2], (int)pk[4 * c + 3]};
+#pragma unroll
+                for (int n = 0; n < ND; ++n) {
+                    const v4i vf = *reinterpret_cast<const v4i*>(&Vt[(16 * n + li) * VROW + 64 * c + 16 * lg]);
+                    oacc[n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, oacc[n], 0, 0, 0);
+                }
+            }
+            // ---- requantise and store: lane holds features lg (D/4) + 4 n + r of query q
+            uint32_t ow[ND];
+#pragma unroll
+            for (int n = 0; n < ND; ++n) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int32_t v = fast_pv ? clamp8(rnd_shift_b15(oacc[n][r], pv.b, pv.c))
+                                              : requant64(oacc[n][r], pv.b, pv.c);
+                    w |= ((uint32_t)v & 0xffu) << (8 * r);
+                }
+                ow[n] = w;
+            }
+            if (q < T) {
+                int8_t* op = o + ((int64_t)b * T + q) * C + h * D + lg * (D / 4);
+                if (D == 64) *reinterpret_cast<uint4*>(op) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+                else *reinterpret_cast<uint2*>(op) = make_uint2(ow[0], ow[1 % ND]);
+            }
+        }
+    }
+}
+
+template <int D>
+static hipError_t launch_d(hipStream_t s, const AttentionArgs& a, int grid, int nkt) {
+    const int n_items = a.B * a.H;
+#define IVIT_ATT(NKT_)                                                                                          \
+    hipLaunchKernelGGL((attention_kernel<D, NKT_>), dim3(grid), dim3(256), 0, s, a.qkv, a.rel_bias, a.o, n_items, \
+                       a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs)
+    if (nkt <= 4) IVIT_ATT(4);
+    else if (nkt <= 8) IVIT_ATT(8);
+    else if (nkt <= 13) IVIT_ATT(13);
+    else IVIT_ATT(16);
+#undef IVIT_ATT
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
+    const int64_t n_items = (int64_t)a.B * a.H;
+    if (n_items == 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>(n_items, (int64_t)num_cus() * 4);
+    const int nkt = (a.T + 15) / 16;
+    const int d = a.C / a.H;
+    return d == 64 ? launch_d<64>(s, a, grid, nkt) : launch_d<32>(s, a, grid, nkt);
+}
+
+}  // namespace ivit

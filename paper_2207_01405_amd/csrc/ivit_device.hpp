@@ -1,0 +1,106 @@
+// Device-side integer primitives shared by the gfx950 kernels.
+//
+// Everything here is exact integer arithmetic following I-ViT (arXiv 2207.01405):
+// dyadic requantisation (Sec. 3.2, Eq. 8-10), ShiftExp and IntDiv (Sec. 3.3,
+// Eq. 13-16, Algorithm 1), ShiftGELU (Sec. 3.4, Algorithm 2) and the fixed-count
+// integer square root of I-LayerNorm (Sec. 3.5, Eq. 20).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ivit {
+
+struct ShiftParams { int32_t i0, n_shift, m_bits, k_out; };
+struct Dyadic { int32_t b, c; };
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int32_t clamp8(int32_t v) { return min(max(v, -127), 127); }
+
+// round(b * v / 2^c) half up, full 64-bit product (Eq. 8 realised as Eq. 10); any 1 <= c <= 62.
+__device__ __forceinline__ int64_t rnd_shift64(int32_t v, int32_t b, int32_t c) {
+    int64_t p = (int64_t)v * (int64_t)b;
+    return (p + ((int64_t)1 << (c - 1))) >> c;
+}
+
+__device__ __forceinline__ int32_t clamp8_64(int64_t v) {
+    v = v < -127 ? -127 : v;
+    v = v > 127 ? 127 : v;
+    return (int32_t)v;
+}
+
+__device__ __forceinline__ int32_t requant64(int32_t v, int32_t b, int32_t c) {
+    return clamp8_64(rnd_shift64(v, b, c));
+}
+
+// Same value as rnd_shift64 when 0 < b < 2^15, 16 <= c <= 31 and the result fits int32,
+// using only full-rate 24-bit multiplies: with v = hi * 2^16 + lo (0 <= lo < 2^16),
+//   (b v + 2^(c-1)) >> c = (b hi + ((b lo + 2^(c-1)) >> 16)) >> (c - 16),
+// because the 16 bits dropped by the inner shift lie below the final floor.
+__device__ __forceinline__ int32_t rnd_shift_b15(int32_t v, int32_t b, int32_t c) {
+    uint32_t lo = (uint32_t)v & 0xffffu;
+    int32_t hi = v >> 16;
+    uint32_t t = __umul24(lo, (uint32_t)b) + (1u << (c - 1));   // < 2^31 + 2^30
+    int32_t u = __mul24(hi, b) + (int32_t)(t >> 16);
+    return u >> (c - 16);
+}
+
+// floor(a / b) for b > 0 and any sign of a.
+__device__ __forceinline__ int32_t floordiv(int32_t a, int32_t b) {
+    int32_t q = a / b;
+    return q - ((a % b != 0) && (a < 0));
+}
+
+// ShiftExp (Algorithm 1): I <= 0 -> I_exp with (S / 2^N) I_exp ~ exp(S I).  I_b << (N - q) is
+// evaluated as (I_b << N) >> q so that q > N shifts the value out instead of shifting by a negative count.
+__device__ __forceinline__ uint32_t shiftexp(int32_t I, int32_t i0, int32_t n_shift) {
+    int32_t Ip = I + (I >> 1) - (I >> 4);
+    int32_t q = (-Ip) / i0;                   // Ip <= 0: floor(Ip / -i0) = (-Ip) / i0
+    int32_t r = -Ip - q * i0;                 // in [0, i0)
+    int32_t Ib = ((-r) >> 1) + i0;
+    return q > 31 ? 0u : (((uint32_t)Ib << n_shift) >> q);
+}
+
+// IntDiv (Eq. 16) with the reciprocal floor(2^M / sum) already formed; M <= 31 and e <= sum, so the
+// product is at most 2^31 and fits 32 unsigned bits.
+__device__ __forceinline__ uint32_t intdiv_apply(uint32_t inv, uint32_t e, int32_t m_bits, int32_t k_out) {
+    return (inv * e) >> (m_bits - (k_out - 1));
+}
+
+__device__ __forceinline__ uint32_t recip_pow2(uint32_t sum, int32_t m_bits) {
+    return (uint32_t)(((uint64_t)1 << m_bits) / sum);
+}
+
+// ShiftGELU on one int8 value (Algorithm 2, maximum taken per element as max(I_p, 0)):
+// returns I * I_div, |result| <= 127 * 2^(k_out-1).
+__device__ __forceinline__ int32_t shiftgelu_raw(int32_t I, ShiftParams p) {
+    int32_t Ip = I + (I >> 1) + (I >> 3) + (I >> 4);
+    int32_t mx = max(Ip, 0);
+    uint32_t e1 = shiftexp(Ip - mx, p.i0, p.n_shift);
+    uint32_t e2 = shiftexp(-mx, p.i0, p.n_shift);
+    uint32_t dv = intdiv_apply(recip_pow2(e1 + e2, p.m_bits), e1, p.m_bits, p.k_out);
+    return I * (int32_t)dv;
+}
+
+// Tenth iterate of I <- (I + floor(v / I)) >> 1 from I = 2^floor(bitlen(v) / 2) (Eq. 20); 0 for v = 0.
+__device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
+    if (v == 0) return 0;
+    uint32_t x = 1u << ((32 - __clz(v)) >> 1);
+#pragma unroll 1
+    for (int it = 0; it < 10; ++it) x = (x + v / x) >> 1;     // x stays >= 1 for v >= 1
+    return x;
+}
+
+// Butterfly reductions over the 64 lanes of a wavefront.
+__device__ __forceinline__ int32_t wave_max(int32_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ int32_t wave_sum(int32_t v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+}  // namespace ivit

@@ -1,0 +1,39 @@
+// Host-side launchers of the gfx950 kernels (internal to libivit.so; the public surface is include/ivit.h).
+// Each launcher assumes arguments already validated by the C-ABI layer and returns a hipError_t.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ivit_device.hpp"
+
+namespace ivit {
+
+hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
+                             int8_t* y, int64_t rows, int C, int f_bits, int c_shift);
+
+hipError_t launch_shiftmax(hipStream_t s, const int8_t* x, const int8_t* bias, int H, int T, int8_t* y,
+                           int64_t rows, int cols, int ld, ShiftParams p);
+
+hipError_t launch_shiftgelu(hipStream_t s, const int8_t* x, int8_t* y8, int16_t* y16, int64_t n,
+                            ShiftParams p, Dyadic out_rq);
+
+struct LinearArgs {
+    const int8_t* x; const int8_t* w; const int32_t* bias; const int32_t* rq_b; const int32_t* rq_c;
+    const int8_t* residual; Dyadic res_rq;
+    bool gelu; ShiftParams gelu_p; Dyadic gelu_rq;
+    int8_t* y; int64_t M; int N; int K;
+};
+hipError_t launch_linear(hipStream_t s, const LinearArgs& a);
+
+struct AttentionArgs {
+    const int8_t* qkv; const int8_t* rel_bias; int8_t* o;
+    int B, T, C, H;
+    Dyadic qk_rq; ShiftParams sm; Dyadic pv_rq;
+    int8_t* tap_scores; int8_t* tap_probs;
+};
+hipError_t launch_attention(hipStream_t s, const AttentionArgs& a);
+
+// Number of compute units of the current device (cached); used to size persistent grids.
+int num_cus();
+
+}  // namespace ivit

@@ -1,0 +1,223 @@
+// Row-wise integer operators for gfx950: I-LayerNorm (Sec. 3.5, Eq. 19-20), Shiftmax (Sec. 3.3,
+// Algorithm 1) and ShiftGELU (Sec. 3.4, Algorithm 2) of I-ViT (arXiv 2207.01405).
+//
+// All three are bound by HBM traffic (one int8 read and one int8 write per element), so the kernels
+// are organised around coalesced dword / 16-byte accesses and wavefront-wide reductions; the scalar
+// per-row work (integer mean, variance, the ten-step square root, the two reciprocals) is done once per row.
+#include <algorithm>
+
+#include "ivit_kernels.hpp"
+
+namespace ivit {
+
+int num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            return 256;
+    }
+    return n;
+}
+
+// ------------------------------------------------------------------------------------------------
+// I-LayerNorm.  One wavefront per row; lane l owns dwords l, l + 64, ... of the row (4 channels each),
+// so gamma / beta for those channels stay in registers across all rows the wave processes.
+// The sum of squared deviations uses the exact integer identity
+//   sum (x - m)^2 = sum x^2 - 2 m sum x + C m^2,
+// which lets both sums come from one pass with 4-way int8 dot products.
+template <int NT>
+__global__ __launch_bounds__(256) void ilayernorm_kernel(const int8_t* __restrict__ x,
+                                                         const int32_t* __restrict__ gamma_q,
+                                                         const int32_t* __restrict__ beta_q,
+                                                         int8_t* __restrict__ y, int64_t rows, int C,
+                                                         int f_bits, int c_shift) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int ndw = C >> 2;
+    const int32_t half = 1 << (c_shift - 1);
+
+    int32_t g[NT][4], bt[NT][4];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        const int idx = lane + 64 * t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            g[t][e] = idx < ndw ? gamma_q[4 * idx + e] : 0;
+            bt[t][e] = idx < ndw ? (int32_t)((uint32_t)beta_q[4 * idx + e] + (uint32_t)half) : 0;
+        }
+    }
+
+    for (int64_t row = wave; row < rows; row += nwaves) {
+        const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + row * C);
+        uint32_t xv[NT];
+        int32_t s = 0, ss = 0;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int idx = lane + 64 * t;
+            xv[t] = idx < ndw ? xr[idx] : 0u;
+            s = __builtin_amdgcn_sdot4((int)xv[t], 0x01010101, s, false);
+            ss = __builtin_amdgcn_sdot4((int)xv[t], (int)xv[t], ss, false);
+        }
+        s = wave_sum(s);
+        ss = wave_sum(ss);
+        const int32_t mean = floordiv(s + (C >> 1), C);
+        const int32_t sq = ss - 2 * mean * s + C * mean * mean;      // sum of squared deviations, >= 0
+        const uint32_t var = (uint32_t)sq / (uint32_t)C;
+        const uint32_t sd = max(isqrt10(var), 1u);
+        const int32_t f = (int32_t)((1u << f_bits) / sd);
+        uint32_t* yr = reinterpret_cast<uint32_t*>(y + row * C);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int idx = lane + 64 * t;
+            uint32_t out = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t xe = (int32_t)(int8_t)(xv[t] >> (8 * e));
+                const int32_t dg = (xe - mean) * g[t][e];                         // |.| < 2^23
+                const int32_t v = (int32_t)((uint32_t)dg * (uint32_t)f + (uint32_t)bt[t][e]);
+                out |= ((uint32_t)clamp8(v >> c_shift) & 0xffu) << (8 * e);
+            }
+            if (idx < ndw) yr[idx] = out;
+        }
+    }
+}
+
+hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
+                             int8_t* y, int64_t rows, int C, int f_bits, int c_shift) {
+    if (rows == 0) return hipSuccess;
+    const int64_t want = (rows + 3) / 4;
+    const int grid = (int)std::min<int64_t>(want, (int64_t)num_cus() * 16);
+    const int nt = (C / 4 + 63) / 64;
+    switch (nt) {
+        case 1: hipLaunchKernelGGL(ilayernorm_kernel<1>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+        case 2: hipLaunchKernelGGL(ilayernorm_kernel<2>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+        case 3: hipLaunchKernelGGL(ilayernorm_kernel<3>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+        default: hipLaunchKernelGGL(ilayernorm_kernel<4>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Shiftmax.  One wavefront per row, lane l owns columns l, l + 64, ...  ShiftExp only ever sees
+// Delta = value - max in [-508, 0] (int8 input plus int8 bias), so each workgroup tabulates it once in LDS.
+template <int NT>
+__global__ __launch_bounds__(256) void shiftmax_kernel(const int8_t* __restrict__ x, const int8_t* __restrict__ bias,
+                                                       int H, int T, int8_t* __restrict__ y, int64_t rows,
+                                                       int cols, int ld, ShiftParams p) {
+    __shared__ uint16_t lut[512];
+    for (int i = threadIdx.x; i < 512; i += 256) lut[i] = (uint16_t)shiftexp(-i, p.i0, p.n_shift);
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int sh = p.m_bits - (p.k_out - 1);
+    const uint32_t top = (1u << (p.k_out - 1)) - 1u;
+    for (int64_t row = wave; row < rows; row += nwaves) {
+        const int8_t* xr = x + row * ld;
+        const int8_t* br = bias ? bias + (((row / T) % H) * (int64_t)T + (row % T)) * cols : nullptr;
+        int32_t v[NT];
+        int32_t mx = INT32_MIN;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int j = lane + 64 * t;
+            v[t] = INT32_MIN;
+            if (j < cols) {
+                v[t] = xr[j];
+                if (br) v[t] += br[j];
+                mx = max(mx, v[t]);
+            }
+        }
+        mx = wave_max(mx);
+        uint32_t e[NT];
+        int32_t sum = 0;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int j = lane + 64 * t;
+            e[t] = j < cols ? lut[mx - v[t]] : 0u;
+            sum += (int32_t)e[t];
+        }
+        sum = wave_sum(sum);
+        const uint32_t inv = (1u << p.m_bits) / (uint32_t)sum;
+        int8_t* yr = y + row * cols;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int j = lane + 64 * t;
+            if (j < cols) yr[j] = (int8_t)min((inv * e[t]) >> sh, top);
+        }
+    }
+}
+
+hipError_t launch_shiftmax(hipStream_t s, const int8_t* x, const int8_t* bias, int H, int T, int8_t* y,
+                           int64_t rows, int cols, int ld, ShiftParams p) {
+    if (rows == 0) return hipSuccess;
+    const int64_t want = (rows + 3) / 4;
+    const int grid = (int)std::min<int64_t>(want, (int64_t)num_cus() * 16);
+    const int nt = (cols + 63) / 64;
+    if (nt <= 1) hipLaunchKernelGGL(shiftmax_kernel<1>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
+    else if (nt <= 2) hipLaunchKernelGGL(shiftmax_kernel<2>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
+    else if (nt <= 4) hipLaunchKernelGGL(shiftmax_kernel<4>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
+    else if (nt <= 8) hipLaunchKernelGGL(shiftmax_kernel<8>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
+    else hipLaunchKernelGGL(shiftmax_kernel<16>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// ShiftGELU.  A pure function of one int8 value, so each workgroup tabulates all 256 results in LDS
+// (raw int16 product, or the int8 value after the dyadic rescale) and the body is a table lookup.
+template <bool RAW, bool VEC>
+__global__ __launch_bounds__(256) void shiftgelu_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y8,
+                                                        int16_t* __restrict__ y16, int64_t n, ShiftParams p,
+                                                        Dyadic rq) {
+    __shared__ int16_t lut[256];
+    {
+        const int32_t I = (int32_t)(int8_t)threadIdx.x;       // table index = the value's low byte
+        const int32_t g = shiftgelu_raw(I, p);
+        lut[threadIdx.x] = RAW ? (int16_t)g : (int16_t)requant64(g, rq.b, rq.c);
+    }
+    __syncthreads();
+    const int64_t tid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t nthreads = (int64_t)gridDim.x * 256;
+    if (VEC && !RAW) {
+        const int64_t nv = n >> 4;
+        const uint4* xv = reinterpret_cast<const uint4*>(x);
+        uint4* yv = reinterpret_cast<uint4*>(y8);
+        for (int64_t i = tid; i < nv; i += nthreads) {
+            const uint4 a = xv[i];
+            uint32_t in[4] = {a.x, a.y, a.z, a.w}, out[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                uint32_t o = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o |= ((uint32_t)lut[(in[d] >> (8 * e)) & 0xffu] & 0xffu) << (8 * e);
+                out[d] = o;
+            }
+            yv[i] = make_uint4(out[0], out[1], out[2], out[3]);
+        }
+        for (int64_t i = (nv << 4) + tid; i < n; i += nthreads) y8[i] = (int8_t)lut[(uint8_t)x[i]];
+    } else {
+        for (int64_t i = tid; i < n; i += nthreads) {
+            const int16_t v = lut[(uint8_t)x[i]];
+            if (RAW) y16[i] = v; else y8[i] = (int8_t)v;
+        }
+    }
+}
+
+hipError_t launch_shiftgelu(hipStream_t s, const int8_t* x, int8_t* y8, int16_t* y16, int64_t n,
+                            ShiftParams p, Dyadic out_rq) {
+    if (n == 0) return hipSuccess;
+    const bool raw = y16 != nullptr;
+    const bool vec = !raw && (((uintptr_t)x | (uintptr_t)y8) & 15) == 0;
+    const int64_t per_block = vec ? 256 * 16 : 256 * 4;
+    const int grid = (int)std::min<int64_t>((n + per_block - 1) / per_block, (int64_t)num_cus() * 16);
+    if (raw) hipLaunchKernelGGL((shiftgelu_kernel<true, false>), dim3(grid), dim3(256), 0, s, x, y8, y16, n, p, out_rq);
+    else if (vec) hipLaunchKernelGGL((shiftgelu_kernel<false, true>), dim3(grid), dim3(256), 0, s, x, y8, y16, n, p, out_rq);
+    else hipLaunchKernelGGL((shiftgelu_kernel<false, false>), dim3(grid), dim3(256), 0, s, x, y8, y16, n, p, out_rq);
+    return hipGetLastError();
+}
+
+}  // namespace ivit

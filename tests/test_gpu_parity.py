@@ -1,0 +1,302 @@
+"""GPU parity: every C-ABI entry point of libivit.so against the CPU oracle, bit for bit.
+
+All tensors are integers, so the bar is exact equality on every element (and on every intermediate tensor
+of a block, through the debug taps).  Inputs are the seeded synthetic workloads of
+paper_2207_01405_amd.synth.  Sizes span several tiles and ragged tails; the full-size configurations run on
+the GPU in the shape the benchmark times and are checked on sampled images, which the oracle computes one by
+one (images are independent through the encoder).
+"""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+import oracle as orc
+from paper_2207_01405_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def empty(shape, dtype=None):
+    import torch
+    return torch.empty(shape, dtype=dtype or torch.int8, device="cuda")
+
+
+def assert_same(got, want, what):
+    got = np.asarray(got); want = np.asarray(want)
+    assert got.shape == want.shape, (what, got.shape, want.shape)
+    if not np.array_equal(got, want):
+        bad = np.argwhere(got != want)
+        first = tuple(bad[0])
+        raise AssertionError("%s: %d of %d elements differ; first at %s: gpu %d, oracle %d" %
+                             (what, len(bad), got.size, first, got[first], want[first]))
+
+
+# ------------------------------------------------------------------ I-LayerNorm
+@pytest.mark.parametrize("rows,C,dist", [
+    (0, 64, "normal"), (1, 64, "normal"), (65, 64, "normal"), (1001, 96, "normal"), (777, 192, "uniform"),
+    (2049, 384, "normal"), (300, 768, "student_t"), (33, 1024, "normal"), (50, 100, "normal"), (7, 4, "uniform"),
+    (64, 384, "const")])
+def test_ilayernorm(ivit, rows, C, dist):
+    rng = np.random.default_rng(rows + C)
+    x = synth.make_rows(rows + C, rows, C, dist, 30.0)
+    g = np.rint((1.0 + 0.1 * rng.standard_normal(C)) * 256).astype(np.int32)
+    b = np.rint(0.1 * rng.standard_normal(C) * 2 ** 24).astype(np.int32)
+    y = empty((rows, C))
+    ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, 16, 19)
+    assert_same(host(y), orc.ilayernorm(x, g, b, 16, 19), "ilayernorm")
+
+
+def test_ilayernorm_other_shift_counts_and_spike_rows(ivit):
+    C = 768
+    x = np.zeros((16, C), np.int8)
+    x[np.arange(16), np.arange(16) * 40] = 127           # one-hot spikes: the largest normalised values
+    x[8:] = -x[8:]
+    g = np.full(C, 511, np.int32); b = np.full(C, -12345, np.int32)
+    for f_bits, c_shift in ((16, 19), (12, 14), (20, 23), (8, 12)):
+        y = empty((16, C))
+        ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, f_bits, c_shift)
+        assert_same(host(y), orc.ilayernorm(x, g, b, f_bits, c_shift), "ilayernorm f=%d c=%d" % (f_bits, c_shift))
+
+
+# ------------------------------------------------------------------ Shiftmax
+@pytest.mark.parametrize("rows,cols,ld,i0", [
+    (0, 49, 49, 32), (1, 1, 1, 32), (5, 49, 49, 32), (1000, 65, 65, 32), (4099, 197, 197, 32), (333, 197, 208, 12),
+    (100, 256, 256, 64), (17, 1000, 1024, 8), (64, 64, 64, 4), (300, 130, 131, 100)])
+def test_shiftmax(ivit, rows, cols, ld, i0):
+    x = synth.make_rows(rows + cols, rows, ld, "normal", 1.5 * min(i0, 40))
+    p = synth.shift_params(i0)
+    y = empty((rows, cols))
+    ivit.ivit_shiftmax(dev(x), y, p, cols=cols)
+    assert_same(host(y), orc.shiftmax(x, p, cols=cols), "shiftmax")
+
+
+def test_shiftmax_extreme_rows(ivit):
+    p = synth.shift_params(32)
+    x = np.full((6, 197), -128, np.int8)
+    x[0, 5] = 127                      # one dominant element
+    x[1] = 7                           # all equal
+    x[2] = np.arange(197) % 256 - 128  # a ramp
+    x[3, :] = 127
+    x[4, ::2] = 127
+    x[5, 196] = -127
+    y = empty((6, 197))
+    ivit.ivit_shiftmax(dev(x), y, p)
+    assert_same(host(y), orc.shiftmax(x, p), "shiftmax extremes")
+
+
+@pytest.mark.parametrize("n_img,H,T", [(3, 3, 49), (2, 2, 65)])
+def test_shiftmax_with_relative_position_bias(ivit, n_img, H, T):
+    rng = np.random.default_rng(T)
+    x = synth.make_rows(T, n_img * H * T, T, "normal", 40.0)
+    bias = np.clip(np.rint(rng.standard_normal((H, T, T)) * 50), -128, 127).astype(np.int8)
+    p = synth.shift_params(32)
+    y = empty(x.shape)
+    ivit.ivit_shiftmax(dev(x), y, p, bias=dev(bias), H=H, T=T)
+    assert_same(host(y), orc.shiftmax(x, p, bias=bias, H=H, T=T), "shiftmax+bias")
+
+
+# ------------------------------------------------------------------ ShiftGELU
+@pytest.mark.parametrize("n,i0", [(0, 32), (1, 32), (255, 8), (100003, 32), (65536, 12), (4099, 64)])
+def test_shiftgelu(ivit, n, i0):
+    import torch
+    x = np.random.default_rng(n).integers(-128, 128, size=n).astype(np.int8)
+    p = synth.shift_params(i0)
+    rq = (24171, 21)
+    y = empty((n,))
+    ivit.ivit_shiftgelu(dev(x), y, p, rq)
+    assert_same(host(y), orc.shiftgelu(x, p, rq), "shiftgelu")
+    y16 = empty((n,), torch.int16)
+    ivit.ivit_shiftgelu_raw(dev(x), y16, p)
+    assert_same(host(y16).astype(np.int32), orc.shiftgelu_raw(x, p), "shiftgelu_raw")
+    if n > 16:                          # unaligned views take the byte path
+        xd = dev(np.concatenate([np.zeros(1, np.int8), x]))[1:]
+        yb = empty((n + 1,))[1:]
+        ivit.ivit_shiftgelu(xd, yb, p, rq)
+        assert_same(host(yb), orc.shiftgelu(x, p, rq), "shiftgelu unaligned")
+
+
+# ------------------------------------------------------------------ Dense / MatMul + requant
+LIN_SHAPES = [(0, 64, 64), (1, 1, 16), (5, 7, 80), (65, 192, 64), (130, 40, 256), (129, 100, 48), (1000, 384, 384),
+              (197, 1536, 384), (300, 384, 1536), (257, 130, 3072), (64, 256, 16)]
+
+
+@pytest.mark.parametrize("M,N,K", LIN_SHAPES)
+@pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
+def test_linear_requant(ivit, M, N, K, epi):
+    x = synth.make_rows(M + N + K, M, K, "normal", 32.0)
+    w, bias, rq_b, rq_c = synth.make_linear(M * 7 + N, N, K)
+    kw_o, kw_g = {}, {}
+    if epi == "residual":
+        res = synth.make_rows(N + 1, M, N, "uniform")
+        kw_o = dict(residual=res, res_rq=(23456, 15)); kw_g = dict(residual=dev(res), res_rq=(23456, 15))
+    elif epi == "gelu":
+        kw_o = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)); kw_g = dict(kw_o)
+    y = empty((M, N))
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, **kw_g)
+    assert_same(host(y), orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o), "linear %s" % epi)
+
+
+def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit):
+    """Multipliers and shifts outside the 15-bit fast range take the 64-bit path, channel by channel."""
+    rng = np.random.default_rng(42)
+    M, N, K = 200, 96, 128
+    x = synth.make_rows(1, M, K, "uniform")
+    w = synth.make_rows(2, N, K, "uniform")
+    rq_c = rng.integers(1, 47, size=N).astype(np.int32)
+    # keep the product scale around 2^-11 so that outputs stay informative: b ~ 2^(c - 11)
+    rq_b = np.array([int(rng.integers(2 ** max(0, min(29, c - 12)), 2 ** max(1, min(31, c - 10)))) for c in rq_c],
+                    np.int32)
+    rq_b[:8] = 2 ** 31 - 1; rq_c[:8] = 46
+    res = synth.make_rows(3, M, N, "uniform")
+    for kw_o, kw_g in (({}, {}), (dict(residual=res, res_rq=(2 ** 31 - 1, 31)), dict(residual=dev(res), res_rq=(2 ** 31 - 1, 31))),
+                       (dict(residual=res, res_rq=(3, 1)), dict(residual=dev(res), res_rq=(3, 1)))):
+        y = empty((M, N))
+        ivit.ivit_linear_requant(dev(x), dev(w), None, dev(rq_b), dev(rq_c), y, **kw_g)
+        want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
+        assert_same(host(y), want, "linear general")
+        assert np.abs(want.astype(np.int32)).mean() > 2
+
+
+# ------------------------------------------------------------------ fused attention
+ATT_CASES = [("c0_tiny", 2, None), ("c4_swin_t", 5, None), ("c2_deit_s", 2, None), ("c1_deit_t", 1, None),
+             ("c0_tiny", 1, dict(T=1)), ("c2_deit_s", 1, dict(T=256)), ("c4_swin_t", 2, dict(T=16)),
+             ("c2_deit_s", 1, dict(T=130))]
+
+
+@pytest.mark.parametrize("name,B,over", ATT_CASES)
+def test_attention(ivit, name, B, over):
+    cfg = dict(synth.CONFIGS[name], **(over or {}))
+    d = synth.dims_of(cfg, B)
+    blk = synth.make_block(cfg, 0)
+    qkv = synth.make_rows(B + cfg["T"], B * cfg["T"], 3 * cfg["C"], "normal", 32.0)
+    o = empty((B * cfg["T"], cfg["C"]))
+    sc = empty((B, cfg["H"], cfg["T"], cfg["T"])); pr = empty((B, cfg["H"], cfg["T"], cfg["T"]))
+    rb = None if blk["rel_bias"] is None else dev(blk["rel_bias"])
+    ivit.ivit_attention(dev(qkv), o, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], rel_bias=rb, tap_scores=sc, tap_probs=pr)
+    o_ref, sc_ref, pr_ref = orc.attention(qkv, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], blk["rel_bias"], want_taps=True)
+    assert_same(host(sc), sc_ref, "scores")
+    assert_same(host(pr), pr_ref, "probs")
+    assert_same(host(o), o_ref, "attention out")
+    o2 = empty(o.shape)                     # without taps: same result
+    ivit.ivit_attention(dev(qkv), o2, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], rel_bias=rb)
+    assert_same(host(o2), o_ref, "attention out (no taps)")
+
+
+def test_attention_general_dyadic_pairs(ivit):
+    cfg = synth.CONFIGS["c0_tiny"]
+    d = synth.dims_of(cfg, 2)
+    qkv = synth.make_rows(3, 2 * cfg["T"], 3 * cfg["C"], "normal", 32.0)
+    qk, pv, sm = (1200000007, 38), (40000, 15), synth.shift_params(12)
+    o = empty((2 * cfg["T"], cfg["C"]))
+    ivit.ivit_attention(dev(qkv), o, d, qk, sm, pv)
+    assert_same(host(o), orc.attention(qkv, d, qk, sm, pv), "attention general pairs")
+
+
+# ------------------------------------------------------------------ encoder block with every intermediate tensor
+def _gpu_block(ivit, x, p, d, want_taps):
+    import torch
+    R = d["B"] * d["T"]
+    ws = torch.empty(ivit.ivit_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    y = empty((R, d["C"]))
+    taps = None
+    if want_taps:
+        taps = {"u": empty((R, d["C"])), "qkv": empty((R, 3 * d["C"])),
+                "scores": empty((d["B"], d["H"], d["T"], d["T"])), "probs": empty((d["B"], d["H"], d["T"], d["T"])),
+                "o": empty((R, d["C"])), "xhat": empty((R, d["C"])), "v": empty((R, d["C"])), "h": empty((R, d["F"]))}
+    pd = ivit.to_device(p)
+    ivit.ivit_encoder_block(dev(x), y, pd, d, ws, taps=taps)
+    return host(y), (None if taps is None else {k: host(v) for k, v in taps.items()})
+
+
+@pytest.mark.parametrize("name,B,layer", [("c0_tiny", 1, 0), ("c0_tiny", 3, 0), ("c4_swin_t", 8, 0), ("c1_deit_t", 2, 0),
+                                          ("c2_deit_s", 2, 0), ("c2_deit_s", 1, 5), ("c3_vit_b", 1, 0)])
+def test_encoder_block_all_tensors(ivit, name, B, layer):
+    cfg = synth.CONFIGS[name]
+    d = synth.dims_of(cfg, B)
+    p = synth.make_block(cfg, layer)
+    x = synth.make_input(cfg, B)
+    y, taps = _gpu_block(ivit, x, p, d, True)
+    y_ref, t_ref = orc.encoder_block(x, p, d, want_taps=True)
+    for k in orc.TAP_NAMES:
+        assert_same(taps[k], t_ref[k], "%s tap %s" % (name, k))
+    assert_same(y, y_ref, "%s block output" % name)
+    y2, _ = _gpu_block(ivit, x, p, d, False)
+    assert_same(y2, y_ref, "%s block output (no taps)" % name)
+
+
+def test_encoder_block_empty_batch(ivit):
+    import torch
+    cfg = synth.CONFIGS["c0_tiny"]
+    d = synth.dims_of(cfg, 0)
+    ws = torch.empty(ivit.ivit_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    x = empty((16,)); y = empty((16,))
+    ivit.ivit_encoder_block(x, y, ivit.to_device(synth.make_block(cfg, 0)), d, ws)
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ forward
+def _oracle_forward_images(cfg, x, blocks, images, final_ln=None):
+    """Oracle forward of the chosen images, one image per call, images in parallel threads."""
+    T = cfg["T"]
+    d1 = synth.dims_of(cfg, 1)
+
+    def one(i):
+        return orc.forward(x[i * T:(i + 1) * T], blocks, d1, final_ln)
+    with ThreadPoolExecutor(max_workers=8) as ex:
+        return list(ex.map(one, images))
+
+
+def _gpu_forward(ivit, cfg, x, blocks, B, final_ln=None):
+    import torch
+    d = synth.dims_of(cfg, B)
+    ws = torch.empty(ivit.ivit_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    y = empty(x.shape)
+    bl = [ivit.to_device(p) for p in blocks]
+    fl = None if final_ln is None else ivit.to_device(final_ln)
+    ivit.ivit_forward(dev(x), y, bl, d, ws, final_ln=fl)
+    out = host(y)
+    y2 = empty(x.shape)                     # integer kernels must be run-to-run identical
+    ivit.ivit_forward(dev(x), y2, bl, d, ws, final_ln=fl)
+    assert np.array_equal(out, host(y2)), "forward is not deterministic"
+    return out
+
+
+def test_forward_small_stack_with_final_layernorm(ivit):
+    cfg = dict(synth.CONFIGS["c0_tiny"], L=3)
+    B = 5
+    blocks, fin = synth.make_model(cfg), synth.make_final_ln(cfg)
+    x = synth.make_input(cfg, B)
+    got = _gpu_forward(ivit, cfg, x, blocks, B, fin)
+    assert_same(got, orc.forward(x, blocks, synth.dims_of(cfg, B), fin), "forward c0 x3 + LN")
+    got0 = _gpu_forward(ivit, cfg, x, [], B, None)
+    assert_same(got0, x, "forward with no blocks")
+
+
+FULL = [("c1_deit_t", (0, 21, 63)), ("c2_deit_s", (0, 37, 90, 127)), ("c3_vit_b", (5, 255)),
+        ("c4_swin_t", (0, 1, 63, 64, 4095, 8191))]
+
+
+@pytest.mark.parametrize("name,images", FULL)
+def test_forward_full_size_sampled_images(ivit, name, images):
+    """The configuration at its full batch, as the benchmark runs it; sampled images against the oracle."""
+    cfg = synth.CONFIGS[name]
+    blocks = synth.make_model(cfg)
+    x = synth.make_input(cfg)
+    got = _gpu_forward(ivit, cfg, x, blocks, cfg["B"])
+    want = _oracle_forward_images(cfg, x, blocks, images)
+    T = cfg["T"]
+    for i, w in zip(images, want):
+        assert_same(got[i * T:(i + 1) * T], w, "%s image %d" % (name, i))
+    assert np.abs(got.astype(np.int32)).mean() > 3
