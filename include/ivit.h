@@ -19,6 +19,7 @@
  *  - Tensors are row-major and dense unless a leading dimension is given.
  *    Weights are [N_out, K] with K contiguous.  Per-channel parameters are
  *    int32 [N_out] device arrays.
+ *  - A tensor with no elements (M, rows, n or B equal to 0) may be passed as NULL.
  *  - Every function returns IVIT_OK (0) or a negative ivit_status.  Arguments
  *    are validated before anything is launched; a failed call launches nothing.
  *    Nothing throws or aborts.  Input and output may not alias unless stated.
@@ -174,6 +175,19 @@ int ivit_forward(void* stream, const int8_t* x, int8_t* y, const ivit_block_para
 int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8_t* o, const ivit_dims* d,
                    ivit_dyadic qk_rq, ivit_shift_params softmax, ivit_dyadic pv_rq,
                    int8_t* tap_scores, int8_t* tap_probs);
+
+/* Per-launch timing for benchmarks.  Between ivit_trace_begin and ivit_trace_end every kernel launch the
+ * library makes (from any entry point, on any stream) is bracketed by two HIP events recorded on the stream
+ * of the launch.  ivit_trace_end waits for the recorded events, then fills the HOST arrays (each nullable,
+ * `capacity` entries) with, per launch in launch order: elapsed milliseconds, kind (1 I-LayerNorm, 2 Dense,
+ * 3 Dense + residual, 4 Dense + ShiftGELU, 5 attention, 6 Shiftmax, 7 ShiftGELU), algorithmic integer
+ * operations (2 per int8 multiply-accumulate; 0 for row-wise kernels) and algorithmic HBM bytes (each
+ * operand read once, each result written once); *count receives the number of launches seen.
+ * One trace at a time per process, not thread-safe; launches beyond max_launches make ivit_trace_end
+ * return IVIT_ERR_HIP.  Events are host objects: no device memory is allocated.
+ * Errors: SHAPE (max_launches < 1), PARAM (begin while active / end while inactive), HIP. */
+int ivit_trace_begin(int32_t max_launches);
+int ivit_trace_end(float* ms, int32_t* kind, int64_t* ops, int64_t* bytes, int32_t capacity, int32_t* count);
 
 #ifdef __cplusplus
 }

@@ -14,7 +14,11 @@ IVIT_OK = 0
 ERRORS = {"NULL": -1, "SHAPE": -2, "PARAM": -3, "ALIGN": -4, "WORKSPACE": -5, "HIP": -6}
 
 EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftgelu", "ivit_shiftgelu_raw",
-           "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward")
+           "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward",
+           "ivit_trace_begin", "ivit_trace_end")
+
+KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
+              7: "shiftgelu"}
 
 
 class ShiftParams(C.Structure):
@@ -91,8 +95,26 @@ def load():
     lib.ivit_forward.restype = C.c_int
     lib.ivit_forward.argtypes = [_P, _P, _P, C.POINTER(BlockParams), i32, C.POINTER(FinalLN), C.POINTER(Dims), _P,
                                  C.c_size_t]
+    lib.ivit_trace_begin.restype = C.c_int; lib.ivit_trace_begin.argtypes = [i32]
+    lib.ivit_trace_end.restype = C.c_int
+    lib.ivit_trace_end.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64), i32,
+                                   C.POINTER(i32)]
     _lib = lib
     return lib
+
+
+def ivit_trace_begin(max_launches):
+    _check(load().ivit_trace_begin(int(max_launches)), "ivit_trace_begin")
+
+
+def ivit_trace_end(capacity):
+    """Returns a list of (milliseconds, kind, ops, bytes), one per launch since ivit_trace_begin."""
+    ms = (C.c_float * capacity)(); kind = (C.c_int32 * capacity)()
+    ops = (C.c_int64 * capacity)(); nbytes = (C.c_int64 * capacity)()
+    count = C.c_int32(0)
+    _check(load().ivit_trace_end(ms, kind, ops, nbytes, capacity, C.byref(count)), "ivit_trace_end")
+    n = min(capacity, count.value)
+    return [(ms[i], kind[i], ops[i], nbytes[i]) for i in range(n)]
 
 
 def strerror(status):

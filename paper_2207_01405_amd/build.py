@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libivit.so")
-SOURCES = ["api.hip", "rowwise.hip", "gemm_i8.hip", "attention.hip"]
+SOURCES = ["api.hip", "trace.hip", "rowwise.hip", "gemm_i8.hip", "attention.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions are kept out of every code object of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -40,7 +40,7 @@ def _compile(src):
 def build_lib(verbose=False):
     """Compile and link libivit.so; always rebuilds.  Returns the library path."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=min(4, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
         results = list(ex.map(_compile, SOURCES))
     if verbose:
         for _, err in results:

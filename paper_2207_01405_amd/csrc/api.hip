@@ -149,8 +149,9 @@ const char* ivit_strerror(int status) {
 int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias, const int32_t* rq_b,
                         const int32_t* rq_c, const int8_t* residual, ivit_dyadic res_rq, const ivit_shift_params* gelu,
                         ivit_dyadic gelu_rq, int8_t* y, int64_t M, int32_t N, int32_t K) {
-    if (!x || !w || !rq_b || !rq_c || !y) return IVIT_ERR_NULL;
     if (M < 0 || N < 1 || K < 16 || K > 65536 || (K & 15)) return IVIT_ERR_SHAPE;
+    if (M > 0 && (!x || !y)) return IVIT_ERR_NULL;             // an empty tensor may have no storage
+    if (!w || !rq_b || !rq_c) return IVIT_ERR_NULL;
     if ((M + 127) / 128 * (int64_t)((N + 127) / 128) > 0x7fffffffLL) return IVIT_ERR_SHAPE;
     if (residual && gelu) return IVIT_ERR_PARAM;
     int st;
@@ -169,8 +170,8 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
 
 int ivit_shiftmax(void* stream, const int8_t* x, const int8_t* bias, int32_t H, int32_t T, int8_t* y, int64_t rows,
                   int32_t cols, int32_t ld, ivit_shift_params p) {
-    if (!x || !y) return IVIT_ERR_NULL;
     if (rows < 0 || cols < 1 || cols > 1024 || ld < cols) return IVIT_ERR_SHAPE;
+    if (rows > 0 && (!x || !y)) return IVIT_ERR_NULL;
     if (bias && (H < 1 || T < 1)) return IVIT_ERR_SHAPE;
     int st = check_shift(p);
     if (st != IVIT_OK) return st;
@@ -179,16 +180,16 @@ int ivit_shiftmax(void* stream, const int8_t* x, const int8_t* bias, int32_t H, 
 }
 
 int ivit_shiftgelu(void* stream, const int8_t* x, int8_t* y, int64_t n, ivit_shift_params p, ivit_dyadic out_rq) {
-    if (!x || !y) return IVIT_ERR_NULL;
     if (n < 0) return IVIT_ERR_SHAPE;
+    if (n > 0 && (!x || !y)) return IVIT_ERR_NULL;
     int st;
     if ((st = check_shift(p)) != IVIT_OK || (st = check_dyadic(out_rq)) != IVIT_OK) return st;
     return hip_status(ivit::launch_shiftgelu(static_cast<hipStream_t>(stream), x, y, nullptr, n, sp(p), dy(out_rq)));
 }
 
 int ivit_shiftgelu_raw(void* stream, const int8_t* x, int16_t* y16, int64_t n, ivit_shift_params p) {
-    if (!x || !y16) return IVIT_ERR_NULL;
     if (n < 0) return IVIT_ERR_SHAPE;
+    if (n > 0 && (!x || !y16)) return IVIT_ERR_NULL;
     int st = check_shift(p);
     if (st != IVIT_OK) return st;
     if (!aligned(y16, 2)) return IVIT_ERR_ALIGN;
@@ -197,8 +198,8 @@ int ivit_shiftgelu_raw(void* stream, const int8_t* x, int16_t* y16, int64_t n, i
 
 int ivit_ilayernorm(void* stream, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q, int8_t* y,
                     int64_t rows, int32_t C, int32_t f_bits, int32_t c_shift) {
-    if (!x || !gamma_q || !beta_q || !y) return IVIT_ERR_NULL;
     if (rows < 0) return IVIT_ERR_SHAPE;
+    if (!gamma_q || !beta_q || (rows > 0 && (!x || !y))) return IVIT_ERR_NULL;
     int st = check_ln(C, f_bits, c_shift);
     if (st != IVIT_OK) return st;
     if (!aligned(x, 4) || !aligned(y, 4) || !aligned(gamma_q, 4) || !aligned(beta_q, 4)) return IVIT_ERR_ALIGN;
@@ -213,9 +214,10 @@ size_t ivit_workspace_bytes(const ivit_dims* d) {
 int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8_t* o, const ivit_dims* d,
                    ivit_dyadic qk_rq, ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores,
                    int8_t* tap_probs) {
-    if (!qkv || !o || !d) return IVIT_ERR_NULL;
+    if (!d) return IVIT_ERR_NULL;
     int st;
     if ((st = check_dims(d)) != IVIT_OK) return st;
+    if (d->B > 0 && (!qkv || !o)) return IVIT_ERR_NULL;
     if ((st = check_dyadic(qk_rq)) != IVIT_OK || (st = check_dyadic(pv_rq)) != IVIT_OK ||
         (st = check_shift(softmax)) != IVIT_OK)
         return st;
@@ -228,9 +230,10 @@ int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8
 
 int ivit_encoder_block(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* p, const ivit_dims* d,
                        void* workspace, size_t workspace_bytes, const ivit_debug_taps* taps) {
-    if (!x || !y || !p || !d) return IVIT_ERR_NULL;
+    if (!p || !d) return IVIT_ERR_NULL;
     int st;
     if ((st = check_dims(d)) != IVIT_OK) return st;
+    if (d->B > 0 && (!x || !y)) return IVIT_ERR_NULL;
     if ((st = check_block(p, d)) != IVIT_OK) return st;
     if (!workspace || workspace_bytes < ivit_workspace_bytes(d)) return IVIT_ERR_WORKSPACE;
     if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(y, 16)) return IVIT_ERR_ALIGN;
@@ -241,10 +244,11 @@ int ivit_encoder_block(void* stream, const int8_t* x, int8_t* y, const ivit_bloc
 
 int ivit_forward(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* blocks, int32_t n_blocks,
                  const ivit_final_ln* final_ln, const ivit_dims* d, void* workspace, size_t workspace_bytes) {
-    if (!x || !y || !d || (n_blocks > 0 && !blocks)) return IVIT_ERR_NULL;
+    if (!d || (n_blocks > 0 && !blocks)) return IVIT_ERR_NULL;
     if (n_blocks < 0) return IVIT_ERR_SHAPE;
     int st;
     if ((st = check_dims(d)) != IVIT_OK) return st;
+    if (d->B > 0 && (!x || !y)) return IVIT_ERR_NULL;
     for (int l = 0; l < n_blocks; ++l)
         if ((st = check_block(&blocks[l], d)) != IVIT_OK) return st;
     if (final_ln) {

@@ -199,6 +199,8 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     const int grid = (int)std::min<int64_t>(n_items, (int64_t)num_cus() * 4);
     const int nkt = (a.T + 15) / 16;
     const int d = a.C / a.H;
+    const int64_t R = (int64_t)a.B * a.T;
+    TraceScope trace(s, KIND_ATTENTION, 4 * n_items * a.T * a.T * d, 4 * R * a.C + (a.rel_bias ? (int64_t)a.H * a.T * a.T : 0));
     return d == 64 ? launch_d<64>(s, a, grid, nkt) : launch_d<32>(s, a, grid, nkt);
 }
 

@@ -204,6 +204,8 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     const int64_t tiles_m = (a.M + BM - 1) / BM;
     const int64_t grid = tiles_m * P.tiles_n;
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int64_t bytes = a.M * a.K + (int64_t)a.N * a.K + a.M * a.N * (a.residual ? 2 : 1) + 8LL * a.N + (a.bias ? 4LL * a.N : 0);
+    TraceScope trace(s, a.residual ? KIND_GEMM_RESIDUAL : (a.gelu ? KIND_GEMM_GELU : KIND_GEMM), 2 * a.M * a.N * a.K, bytes);
     if (a.residual) hipLaunchKernelGGL(gemm_i8_kernel<EPI_RESIDUAL>, dim3((unsigned)grid), dim3(256), 0, s, P);
     else if (a.gelu) hipLaunchKernelGGL(gemm_i8_kernel<EPI_GELU>, dim3((unsigned)grid), dim3(256), 0, s, P);
     else hipLaunchKernelGGL(gemm_i8_kernel<EPI_PLAIN>, dim3((unsigned)grid), dim3(256), 0, s, P);

@@ -36,4 +36,21 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a);
 // Number of compute units of the current device (cached); used to size persistent grids.
 int num_cus();
 
+// Kinds of launches reported by the trace (ivit_trace_end); values are part of the C ABI.
+enum LaunchKind { KIND_ILAYERNORM = 1, KIND_GEMM = 2, KIND_GEMM_RESIDUAL = 3, KIND_GEMM_GELU = 4,
+                  KIND_ATTENTION = 5, KIND_SHIFTMAX = 6, KIND_SHIFTGELU = 7 };
+
+// Brackets one kernel launch with two HIP events on its stream while a trace is active; otherwise a no-op.
+// ops = algorithmic integer operations (2 per int8 multiply-accumulate), bytes = algorithmic HBM bytes.
+class TraceScope {
+public:
+    TraceScope(hipStream_t s, int kind, int64_t ops, int64_t bytes);
+    ~TraceScope();
+    TraceScope(const TraceScope&) = delete;
+    TraceScope& operator=(const TraceScope&) = delete;
+private:
+    hipStream_t stream_;
+    int slot_;
+};
+
 }  // namespace ivit

@@ -93,6 +93,7 @@ hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamm
     const int64_t want = (rows + 3) / 4;
     const int grid = (int)std::min<int64_t>(want, (int64_t)num_cus() * 16);
     const int nt = (C / 4 + 63) / 64;
+    TraceScope trace(s, KIND_ILAYERNORM, 0, 2 * rows * C + 8LL * C);
     switch (nt) {
         case 1: hipLaunchKernelGGL(ilayernorm_kernel<1>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
         case 2: hipLaunchKernelGGL(ilayernorm_kernel<2>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
@@ -158,6 +159,7 @@ hipError_t launch_shiftmax(hipStream_t s, const int8_t* x, const int8_t* bias, i
     const int64_t want = (rows + 3) / 4;
     const int grid = (int)std::min<int64_t>(want, (int64_t)num_cus() * 16);
     const int nt = (cols + 63) / 64;
+    TraceScope trace(s, KIND_SHIFTMAX, 0, rows * cols * (bias ? 3LL : 2LL));
     if (nt <= 1) hipLaunchKernelGGL(shiftmax_kernel<1>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
     else if (nt <= 2) hipLaunchKernelGGL(shiftmax_kernel<2>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
     else if (nt <= 4) hipLaunchKernelGGL(shiftmax_kernel<4>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
@@ -214,6 +216,7 @@ hipError_t launch_shiftgelu(hipStream_t s, const int8_t* x, int8_t* y8, int16_t*
     const bool vec = !raw && (((uintptr_t)x | (uintptr_t)y8) & 15) == 0;
     const int64_t per_block = vec ? 256 * 16 : 256 * 4;
     const int grid = (int)std::min<int64_t>((n + per_block - 1) / per_block, (int64_t)num_cus() * 16);
+    TraceScope trace(s, KIND_SHIFTGELU, 0, n * (raw ? 3LL : 2LL));
     if (raw) hipLaunchKernelGGL((shiftgelu_kernel<true, false>), dim3(grid), dim3(256), 0, s, x, y8, y16, n, p, out_rq);
     else if (vec) hipLaunchKernelGGL((shiftgelu_kernel<false, true>), dim3(grid), dim3(256), 0, s, x, y8, y16, n, p, out_rq);
     else hipLaunchKernelGGL((shiftgelu_kernel<false, false>), dim3(grid), dim3(256), 0, s, x, y8, y16, n, p, out_rq);

@@ -63,8 +63,9 @@ def test_ilayernorm_other_shift_counts_and_spike_rows(ivit):
     x = np.zeros((16, C), np.int8)
     x[np.arange(16), np.arange(16) * 40] = 127           # one-hot spikes: the largest normalised values
     x[8:] = -x[8:]
-    g = np.full(C, 511, np.int32); b = np.full(C, -12345, np.int32)
-    for f_bits, c_shift in ((16, 19), (12, 14), (20, 23), (8, 12)):
+    b = np.full(C, -12345, np.int32)
+    for f_bits, c_shift, gam in ((16, 19, 511), (12, 14, 511), (20, 23, 15), (8, 12, 32767)):
+        g = np.full(C, gam, np.int32)              # |dev * f * gamma| stays below 2^31, as the ABI requires
         y = empty((16, C))
         ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, f_bits, c_shift)
         assert_same(host(y), orc.ilayernorm(x, g, b, f_bits, c_shift), "ilayernorm f=%d c=%d" % (f_bits, c_shift))
