@@ -12,6 +12,11 @@
 // leave registers.  The key order inside each 64-key chunk of the V^T rows is permuted when V is
 // written to LDS to match that register layout, and the rows (head features) are permuted so that a
 // lane ends up with d/4 consecutive features of its query: one 16-byte (d = 64) store.
+//
+// The kernel is bound by the vector ALU (about a dozen integer operations per score element against
+// 2 d multiply-accumulates on the matrix core), so the per-element path is kept minimal: debug taps, the
+// bias and the 64-bit requantisation are compiled in only when asked for (template flags), and masking
+// of padded keys is done only for key tiles that are not completely valid.
 #include <algorithm>
 
 #include "ivit_kernels.hpp"
@@ -26,7 +31,14 @@ __device__ __forceinline__ int vt_pos(int k) {
     return (k & ~63) + ((k >> 2) & 3) * 16 + ((k >> 4) & 3) * 4 + (k & 3);
 }
 
-template <int D, int NKT>
+template <bool FAST>
+__device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d) {
+    return FAST ? clamp8(rnd_shift_fit32(v, d.b, d.c)) : requant64(v, d.b, d.c);
+}
+
+// FAST: both dyadic pairs are rescales by at most 1 with c <= 31 (32-bit requantisation) and the row sum always
+// exceeds 2^(k_out-1), so that IntDiv is one multiply-high by the pre-shifted reciprocal.
+template <int D, int NKT, bool TAPS, bool BIAS, bool FAST>
 __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
                                                         int8_t* __restrict__ o, int n_items, int T, int C, int H,
@@ -51,8 +63,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
     const int sh = sm.m_bits - (sm.k_out - 1);
     const uint32_t top = (1u << (sm.k_out - 1)) - 1u;
     const int nqt = (T + 15) >> 4;
-    const bool fast_qk = qk.b < 32768 && qk.c >= 16 && qk.c <= 31;
-    const bool fast_pv = pv.b < 32768 && pv.c >= 16 && pv.c <= 31;
+    const int nfull = T >> 4;                      // key tiles whose 16 keys all exist
 
     for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int b = item / H, h = item % H;
@@ -89,6 +100,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
                     const v4i kf = *reinterpret_cast<const v4i*>(&Ks[(16 * t + li) * KROW + 16 * lg]);
                     const v4i r = __builtin_amdgcn_mfma_i32_16x16x64_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
                     sc[t][0] = r[0]; sc[t][1] = r[1]; sc[t][2] = r[2]; sc[t][3] = r[3];
+                    if ((t & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // at most four K fragments in flight
                 }
             } else {
                 const long qf = *reinterpret_cast<const long*>(qp + 8 * lg);
@@ -97,41 +109,69 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
                     const long kf = *reinterpret_cast<const long*>(&Ks[(16 * t + li) * KROW + 8 * lg]);
                     const v4i r = __builtin_amdgcn_mfma_i32_16x16x32_i8(kf, qf, v4i{0, 0, 0, 0}, 0, 0, 0);
                     sc[t][0] = r[0]; sc[t][1] = r[1]; sc[t][2] = r[2]; sc[t][3] = r[3];
+                    if ((t & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 }
             }
             // ---- requantise, add the bias, row maximum.  Lane (li, lg) holds keys 16 t + 4 lg + r.
             const int64_t tap_row = ((int64_t)item * T + qc) * T;
-            const int8_t* brow = rel_bias ? rel_bias + ((int64_t)h * T + qc) * T : nullptr;
+            const int8_t* brow = BIAS ? rel_bias + ((int64_t)h * T + qc) * T : nullptr;
             int32_t mx = INT32_MIN;
 #pragma unroll
-            for (int t = 0; t < NKT; ++t)
+            for (int t = 0; t < NKT; ++t) {
+                if (t < nfull) {                   // uniform: every key of the tile exists
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = 16 * t + 4 * lg + r;
-                    int32_t a = fast_qk ? clamp8(rnd_shift_b15(sc[t][r], qk.b, qk.c)) : requant64(sc[t][r], qk.b, qk.c);
-                    if (key < T) {
-                        if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a;
-                        if (brow) a += brow[key];
+                    for (int r = 0; r < 4; ++r) {
+                        const int key = 16 * t + 4 * lg + r;
+                        int32_t a = requant8<FAST>(sc[t][r], qk);
+                        if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
+                        if (BIAS) a += brow[key];
                         mx = max(mx, a);
+                        sc[t][r] = a;
                     }
-                    sc[t][r] = a;
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int key = 16 * t + 4 * lg + r;
+                        int32_t a = requant8<FAST>(sc[t][r], qk);
+                        if (key < T) {
+                            if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
+                            if (BIAS) a += brow[key];
+                            mx = max(mx, a);
+                        }
+                        sc[t][r] = a;
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);     // keep the 64-bit temporaries of one tile at a time
+            }
             mx = max(mx, __shfl_xor(mx, 16, kWave));
             mx = max(mx, __shfl_xor(mx, 32, kWave));
-            // ---- ShiftExp by table, row sum, IntDiv
+            // ---- ShiftExp by table, row sum
             int32_t sum = 0;
 #pragma unroll
-            for (int t = 0; t < NKT; ++t)
+            for (int t = 0; t < NKT; ++t) {
+                if (t < nfull) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int key = 16 * t + 4 * lg + r;
-                    const int32_t e = key < T ? (int32_t)lut[mx - sc[t][r]] : 0;
-                    sc[t][r] = e;
-                    sum += e;
+                    for (int r = 0; r < 4; ++r) {
+                        const int32_t e = (int32_t)lut[mx - sc[t][r]];
+                        sc[t][r] = e;
+                        sum += e;
+                    }
+                } else {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int key = 16 * t + 4 * lg + r;
+                        const int32_t e = key < T ? (int32_t)lut[mx - sc[t][r]] : 0;
+                        sc[t][r] = e;
+                        sum += e;
+                    }
                 }
+                if (t & 1) __builtin_amdgcn_sched_barrier(0);
+            }
             sum += __shfl_xor(sum, 16, kWave);
             sum += __shfl_xor(sum, 32, kWave);
+            // ---- IntDiv and packing: the four keys of tile t become one word of the "B" operand
             const uint32_t inv = (1u << sm.m_bits) / (uint32_t)sum;
+            const uint32_t inv_hi = FAST ? inv << (32 - sh) : 0u;      // FAST: inv < 2^sh, 1 <= sh <= 31
             uint32_t pk[NKC * 4];
 #pragma unroll
             for (int t = 0; t < NKC * 4; ++t) pk[t] = 0u;
@@ -139,9 +179,12 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
             for (int t = 0; t < NKT; ++t)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint32_t p = min((inv * (uint32_t)sc[t][r]) >> sh, top);
-                    const int key = 16 * t + 4 * lg + r;
-                    if (tap_p && q < T && key < T) tap_p[tap_row + key] = (int8_t)p;
+                    const uint32_t p = FAST ? min(__umulhi(inv_hi, (uint32_t)sc[t][r]), top)
+                                            : min((inv * (uint32_t)sc[t][r]) >> sh, top);
+                    if (TAPS) {
+                        const int key = 16 * t + 4 * lg + r;
+                        if (tap_p && q < T && key < T) tap_p[tap_row + key] = (int8_t)p;
+                    }
                     pk[t] |= p << (8 * r);
                 }
             // ---- O^T = V^T P^T : "A" = V^T rows (features), "B" = packed probabilities (keys x queries)
@@ -156,6 +199,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
                     const v4i vf = *reinterpret_cast<const v4i*>(&Vt[(16 * n + li) * VROW + 64 * c + 16 * lg]);
                     oacc[n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, oacc[n], 0, 0, 0);
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
             // ---- requantise and store: lane holds features lg (D/4) + 4 n + r of query q
             uint32_t ow[ND];
@@ -163,11 +207,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
             for (int n = 0; n < ND; ++n) {
                 uint32_t w = 0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int32_t v = fast_pv ? clamp8(rnd_shift_b15(oacc[n][r], pv.b, pv.c))
-                                              : requant64(oacc[n][r], pv.b, pv.c);
-                    w |= ((uint32_t)v & 0xffu) << (8 * r);
-                }
+                for (int r = 0; r < 4; ++r) w |= ((uint32_t)requant8<FAST>(oacc[n][r], pv) & 0xffu) << (8 * r);
                 ow[n] = w;
             }
             if (q < T) {
@@ -179,19 +219,28 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
     }
 }
 
-template <int D>
-static hipError_t launch_d(hipStream_t s, const AttentionArgs& a, int grid, int nkt) {
+template <int D, int NKT>
+static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, bool taps, bool bias, bool fast) {
     const int n_items = a.B * a.H;
-#define IVIT_ATT(NKT_)                                                                                          \
-    hipLaunchKernelGGL((attention_kernel<D, NKT_>), dim3(grid), dim3(256), 0, s, a.qkv, a.rel_bias, a.o, n_items, \
-                       a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs)
-    if (nkt <= 4) IVIT_ATT(4);
-    else if (nkt <= 8) IVIT_ATT(8);
-    else if (nkt <= 13) IVIT_ATT(13);
-    else IVIT_ATT(16);
+#define IVIT_ATT(TAPS_, BIAS_, FAST_)                                                                              \
+    hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, FAST_>), dim3(grid), dim3(256), 0, s, a.qkv, a.rel_bias, \
+                       a.o, n_items, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs)
+    // the production path is <no taps, fast>; everything else shares one fully general instantiation per bias flag
+    if (!taps && fast) { if (bias) IVIT_ATT(false, true, true); else IVIT_ATT(false, false, true); }
+    else { if (bias) IVIT_ATT(true, true, false); else IVIT_ATT(true, false, false); }
 #undef IVIT_ATT
+}
+
+template <int D>
+static hipError_t launch_d(hipStream_t s, const AttentionArgs& a, int grid, int nkt, bool taps, bool bias, bool fast) {
+    if (nkt <= 4) launch_flags<D, 4>(s, a, grid, taps, bias, fast);
+    else if (nkt <= 8) launch_flags<D, 8>(s, a, grid, taps, bias, fast);
+    else if (nkt <= 13) launch_flags<D, 13>(s, a, grid, taps, bias, fast);
+    else launch_flags<D, 16>(s, a, grid, taps, bias, fast);
     return hipGetLastError();
 }
+
+static bool fits32_host(Dyadic d) { return d.c >= 1 && d.c <= 31 && d.b >= 1 && (uint32_t)d.b <= (1u << d.c); }
 
 hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     const int64_t n_items = (int64_t)a.B * a.H;
@@ -199,9 +248,14 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     const int grid = (int)std::min<int64_t>(n_items, (int64_t)num_cus() * 4);
     const int nkt = (a.T + 15) / 16;
     const int d = a.C / a.H;
+    const int sh = a.sm.m_bits - (a.sm.k_out - 1);
+    const bool fast = fits32_host(a.qk_rq) && fits32_host(a.pv_rq) && sh >= 1 &&
+                      ((int64_t)a.sm.i0 << a.sm.n_shift) > ((int64_t)1 << (a.sm.k_out - 1));
+    const bool taps = a.tap_scores || a.tap_probs;
     const int64_t R = (int64_t)a.B * a.T;
     TraceScope trace(s, KIND_ATTENTION, 4 * n_items * a.T * a.T * d, 4 * R * a.C + (a.rel_bias ? (int64_t)a.H * a.T * a.T : 0));
-    return d == 64 ? launch_d<64>(s, a, grid, nkt) : launch_d<32>(s, a, grid, nkt);
+    return d == 64 ? launch_d<64>(s, a, grid, nkt, taps, a.rel_bias != nullptr, fast)
+                   : launch_d<32>(s, a, grid, nkt, taps, a.rel_bias != nullptr, fast);
 }
 
 }  // namespace ivit

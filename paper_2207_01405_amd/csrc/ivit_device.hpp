@@ -45,6 +45,16 @@ __device__ __forceinline__ int32_t rnd_shift_b15(int32_t v, int32_t b, int32_t c
     return u >> (c - 16);
 }
 
+// round(b v / 2^c) when 1 <= c <= 31 and 1 <= b <= 2^c (a rescale by at most 1, so the result fits 32 bits):
+// one 64-bit multiply-add, then the 32 result bits are cut out of the 64-bit value.
+__device__ __forceinline__ bool dyadic_fits32(int32_t b, int32_t c) {
+    return c >= 1 && c <= 31 && b >= 1 && (uint32_t)b <= (1u << c);
+}
+__device__ __forceinline__ int32_t rnd_shift_fit32(int32_t v, int32_t b, int32_t c) {
+    const int64_t p = (int64_t)v * b + (int64_t)(1u << (c - 1));
+    return (int32_t)__builtin_amdgcn_alignbit((uint32_t)(p >> 32), (uint32_t)p, c);
+}
+
 // floor(a / b) for b > 0 and any sign of a.
 __device__ __forceinline__ int32_t floordiv(int32_t a, int32_t b) {
     int32_t q = a / b;
@@ -68,7 +78,7 @@ __device__ __forceinline__ uint32_t intdiv_apply(uint32_t inv, uint32_t e, int32
 }
 
 __device__ __forceinline__ uint32_t recip_pow2(uint32_t sum, int32_t m_bits) {
-    return (uint32_t)(((uint64_t)1 << m_bits) / sum);
+    return (1u << m_bits) / sum;              // m_bits <= 31
 }
 
 // ShiftGELU on one int8 value (Algorithm 2, maximum taken per element as max(I_p, 0)):

@@ -87,9 +87,108 @@ __global__ __launch_bounds__(256) void ilayernorm_kernel(const int8_t* __restric
     }
 }
 
+// I-LayerNorm, tiled form for C a multiple of 16 with 64 <= C <= 1024.  A workgroup takes R = RP * J
+// consecutive rows, where CPR = C / 16 threads cover one row with 16 bytes each and RP = 256 / CPR rows are
+// covered per pass.  Thread (rgrp, cc) keeps chunk cc of rows rgrp, rgrp + RP, ... in registers, so gamma / beta
+// of its 16 channels are loaded once.  The per-row scalar work (integer mean, variance, ten-step square
+// root, reciprocal) would idle 63 of 64 lanes if done per wavefront, so the 4-way dot-product partial sums
+// go through LDS and every thread then does the scalar work of a DIFFERENT row.
+template <int J>
+__global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __restrict__ x,
+                                                               const int32_t* __restrict__ gamma_q,
+                                                               const int32_t* __restrict__ beta_q,
+                                                               int8_t* __restrict__ y, int64_t rows, int C,
+                                                               int f_bits, int c_shift) {
+    typedef int v4i __attribute__((ext_vector_type(4)));
+    __shared__ int2 part[J * 256];                 // [pass][thread]: (sum x, sum x^2) of one 16-byte chunk
+    __shared__ int2 stat[J * 64];                  // [row in workgroup]: (mean, f)
+    const int tid = threadIdx.x;
+    const int CPR = C >> 4, RP = 256 / CPR, R = RP * J;
+    const bool active = tid < RP * CPR;
+    const int rgrp = tid / CPR, cc = tid - rgrp * CPR;
+    const int64_t row0 = (int64_t)blockIdx.x * R;
+    const int32_t half = 1 << (c_shift - 1);
+
+    v4i xv[J];
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int64_t row = row0 + j * RP + rgrp;
+        xv[j] = v4i{0, 0, 0, 0};
+        if (active && row < rows) xv[j] = *reinterpret_cast<const v4i*>(x + row * C + 16 * cc);
+    }
+    int32_t g[16], bt[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        v4i gv = {0, 0, 0, 0}, bv = {0, 0, 0, 0};
+        if (active) {
+            gv = *reinterpret_cast<const v4i*>(gamma_q + 16 * cc + 4 * q);
+            bv = *reinterpret_cast<const v4i*>(beta_q + 16 * cc + 4 * q);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            g[4 * q + e] = gv[e];
+            bt[4 * q + e] = (int32_t)((uint32_t)bv[e] + (uint32_t)half);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        int32_t s = 0, ss = 0;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            s = __builtin_amdgcn_sdot4(xv[j][d], 0x01010101, s, false);
+            ss = __builtin_amdgcn_sdot4(xv[j][d], xv[j][d], ss, false);
+        }
+        part[j * 256 + tid] = make_int2(s, ss);
+    }
+    __syncthreads();
+    for (int r = tid; r < R; r += 256) {           // one row per thread: r = j * RP + rgrp
+        const int j = r / RP, rg = r - j * RP;
+        const int2* p = &part[j * 256 + rg * CPR];
+        int32_t s = 0, ss = 0;
+        for (int c = 0; c < CPR; ++c) { s += p[c].x; ss += p[c].y; }
+        const int32_t mean = floordiv(s + (C >> 1), C);
+        const int32_t sq = ss - 2 * mean * s + C * mean * mean;      // sum of squared deviations (exact)
+        const uint32_t var = (uint32_t)sq / (uint32_t)C;
+        const uint32_t sd = max(isqrt10(var), 1u);
+        stat[r] = make_int2(mean, (int32_t)((1u << f_bits) / sd));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+        const int64_t row = row0 + j * RP + rgrp;
+        const int2 mf = stat[j * RP + rgrp];
+        uint32_t outw[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t o = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t xe = (int32_t)(int8_t)((uint32_t)xv[j][d] >> (8 * e));
+                const int32_t dg = (xe - mf.x) * g[4 * d + e];                       // |.| < 2^23
+                const int32_t v = (int32_t)((uint32_t)dg * (uint32_t)mf.y + (uint32_t)bt[4 * d + e]);
+                o |= ((uint32_t)clamp8(v >> c_shift) & 0xffu) << (8 * e);
+            }
+            outw[d] = o;
+        }
+        if (active && row < rows)
+            *reinterpret_cast<uint4*>(y + row * C + 16 * cc) = make_uint4(outw[0], outw[1], outw[2], outw[3]);
+    }
+}
+
 hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
                              int8_t* y, int64_t rows, int C, int f_bits, int c_shift) {
     if (rows == 0) return hipSuccess;
+    if ((C & 15) == 0 && C >= 64 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma_q | (uintptr_t)beta_q) & 15) == 0) {
+        constexpr int J = 8;
+        const int R = (256 / (C >> 4)) * J;
+        const int64_t grid = (rows + R - 1) / R;
+        if (grid <= 0x7fffffffLL) {
+            TraceScope trace(s, KIND_ILAYERNORM, 0, 2 * rows * C + 8LL * C);
+            hipLaunchKernelGGL(ilayernorm_tiled_kernel<J>, dim3((unsigned)grid), dim3(256), 0, s, x, gamma_q, beta_q, y,
+                               rows, C, f_bits, c_shift);
+            return hipGetLastError();
+        }
+    }
     const int64_t want = (rows + 3) / 4;
     const int grid = (int)std::min<int64_t>(want, (int64_t)num_cus() * 16);
     const int nt = (C / 4 + 63) / 64;
