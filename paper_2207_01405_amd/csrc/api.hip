@@ -2,6 +2,9 @@
 // one encoder block (I-ViT, arXiv 2207.01405, Eq. 1-5) and of the block stack.  See include/ivit.h.
 #include "../../include/ivit.h"
 
+#include <cstdio>
+#include <cstdlib>
+
 #include "ivit_kernels.hpp"
 
 namespace {
@@ -29,7 +32,11 @@ inline int check_ln(int32_t C, int32_t f_bits, int32_t c_shift) {
 
 inline ShiftParams sp(const ivit_shift_params& p) { return ShiftParams{p.i0, p.n_shift, p.m_bits, p.k_out}; }
 inline Dyadic dy(ivit_dyadic d) { return Dyadic{d.b, d.c}; }
-inline int hip_status(hipError_t e) { return e == hipSuccess ? IVIT_OK : IVIT_ERR_HIP; }
+inline int hip_status(hipError_t e) {
+    if (e == hipSuccess) return IVIT_OK;
+    if (getenv("IVIT_LOG")) fprintf(stderr, "ivit: HIP error %d (%s)\n", (int)e, hipGetErrorString(e));
+    return IVIT_ERR_HIP;
+}
 
 int check_dims(const ivit_dims* d) {
     if (!d) return IVIT_ERR_NULL;
