@@ -24,6 +24,21 @@ PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA peak, TOP/s
 PEAK_HBM_GBS = 8000.0
 
 
+def measured_traffic(workload):
+    """HBM bytes per GEMM launch from the committed hardware-counter summary of this workload (None if there is none).
+
+    Byte counters cannot be read inside this process; the figure is the one the counter runs of this same command gave.
+    """
+    path = os.path.join(ROOT, "profiles", "forward_%s_hbm_traffic.txt" % workload)
+    try:
+        for line in open(path):
+            if "traffic_bytes_per_launch:" in line:
+                return int(line.rsplit(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,6 +47,10 @@ def main():
     ap.add_argument("--workload", default="c2_deit_s")
     ap.add_argument("--trace-steps", type=int, default=10)
     ap.add_argument("--cpu-images", type=int, default=2, help="images the CPU oracle runs for cpu_baseline (0 = skip)")
+    ap.add_argument("--rowwise-gib", type=float, default=1.0,
+                    help="input + output bytes of the stand-alone I-LayerNorm / Shiftmax bandwidth runs (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (reference for hardware byte counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported", file=sys.stderr)
@@ -41,6 +60,14 @@ def main():
     import torch
     from paper_2207_01405_amd import binding, synth
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.calibrate_copy:
+        src = torch.ones(1 << 30, dtype=torch.int8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes_read": 1 << 30, "calibrate_copy_bytes_written": 1 << 30, "launches": 4}))
+        return
     binding.load()
 
     cfg = synth.CONFIGS[args.workload]
@@ -93,9 +120,50 @@ def main():
     achieved = g_ops / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
     roofline = dict(bound="mfma", kernel="gemm_i8_kernel (Dense + requant epilogues: QKV, proj, fc1, fc2)",
                     achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TOP/s",
-                    frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=None,
+                    frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=measured_traffic(args.workload),
                     avg_launch_us=round(g_ms / max(1, g_n) * 1e3, 2), launches_per_step=g_n // max(1, args.trace_steps),
                     ops_per_launch=g_ops // max(1, g_n))
+
+    # ---- stand-alone row-wise kernels on buffers far larger than the caches: the HBM figure of I-LN and Shiftmax
+    rowwise = None
+    if args.rowwise_gib > 0:
+        rowwise = {}
+        half = int(args.rowwise_gib * (1 << 30) / 2)
+        sp = synth.shift_params(32)
+        ln_p = blocks[0]
+
+        def hbm_run(name, cols, launch):
+            rows = half // cols
+            small = torch.from_numpy(synth.make_rows(11, 4096, cols)).cuda()
+            xin = small.repeat((rows + 4095) // 4096, 1)[:rows].contiguous()
+            out = torch.empty_like(xin)
+            for _ in range(2):
+                launch(xin, out)
+            torch.cuda.synchronize()
+            binding.ivit_trace_begin(16)
+            for _ in range(5):
+                launch(xin, out)
+            r = binding.ivit_trace_end(16)
+            avg_ms = sum(t[0] for t in r) / len(r)
+            nbytes = 2 * rows * cols
+            gbs = nbytes / (avg_ms * 1e-3) / 1e9
+            rowwise[name] = dict(rows=rows, cols=cols, algorithmic_bytes=nbytes, avg_us=round(avg_ms * 1e3, 1),
+                                 gbs=round(gbs, 1), frac_of_hbm_peak=round(gbs / PEAK_HBM_GBS, 4))
+            del xin, out
+
+        hbm_run("ilayernorm", C, lambda a, o: binding.ivit_ilayernorm(a, ln_p["ln1_gamma"], ln_p["ln1_beta"], o,
+                                                                       ln_p["ln1_f_bits"], ln_p["ln1_c_shift"], stream=stream))
+        hbm_run("shiftmax", T, lambda a, o: binding.ivit_shiftmax(a, o, sp, stream=stream))
+        src = torch.ones(half, dtype=torch.int8, device="cuda"); dst = torch.empty_like(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src); torch.cuda.synchronize()
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record(); torch.cuda.synchronize()
+        cgbs = 2 * half / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e9
+        rowwise["plain_copy"] = dict(bytes=2 * half, gbs=round(cgbs, 1), frac_of_hbm_peak=round(cgbs / PEAK_HBM_GBS, 4))
+        del src, dst
 
     # ---- the oracle on the host cores, a bounded sample of the same workload
     cpu = None
@@ -116,7 +184,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: %d blocks, dim %d, %d heads, %d tokens, MLP %d, batch %d" % (args.workload, L, C, H, T, F, B)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "rowwise_hbm": rowwise,
         "ms_per_step_traced": round(traced_ms_per_step, 4), "kernels": kernels,
         "int8_tops_whole_step": round((24.0 * B * T * C * C + 4.0 * B * H * T * T * (C // H)) * L / (ms_per_step * 1e-3) / 1e12, 1),
     }
