@@ -252,6 +252,112 @@ __global__ __launch_bounds__(256) void shiftmax_kernel(const int8_t* __restrict_
     }
 }
 
+// Shiftmax without bias for 16 <= cols <= 16 * LPR: LPR (4, 8 or 16) adjacent lanes share a row and every lane owns
+// 16 consecutive bytes of it, read and written as one 16-byte access at byte granularity (rows need no alignment).
+// The last lane of a row is moved back so that it ends at the row's end; the bytes it has in common with its
+// neighbour give the same results and only have to be left out of the row sum.  All arithmetic on the 16 bytes is
+// done on packed words: with the sign bits flipped the bytes order as unsigned numbers, the maximum is taken on
+// 16-bit pairs, and max - value needs no borrow between bytes, so one subtraction yields four table indices.
+// Reductions over the LPR lanes are DPP permutations (quad exchange, then mirrored halves of 8 and 16 lanes).
+typedef uint32_t u32x4_unaligned __attribute__((ext_vector_type(4), aligned(1)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+template <int LPR, class OP>
+__device__ __forceinline__ uint32_t group_allreduce(uint32_t v, OP op) {
+    v = op(v, dpp<0xB1>(v));                         // quad_perm [1,0,3,2]
+    v = op(v, dpp<0x4E>(v));                         // quad_perm [2,3,0,1]
+    if (LPR >= 8) v = op(v, dpp<0x141>(v));          // row_half_mirror: quads 0 <-> 1, 2 <-> 3
+    if (LPR >= 16) v = op(v, dpp<0x140>(v));         // row_mirror: halves of the 16 lanes
+    return v;
+}
+
+template <int LPR, int UNR, bool FAST>
+__global__ __launch_bounds__(256) void shiftmax_vec_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y,
+                                                           int64_t rows, int cols, int ld, ShiftParams p) {
+    __shared__ uint16_t lut[256];                    // ShiftExp(-delta), delta = max - value in [0, 255]
+    lut[threadIdx.x] = (uint16_t)shiftexp(-(int)threadIdx.x, p.i0, p.n_shift);
+    __syncthreads();
+    const int j = threadIdx.x % LPR;                 // lane within the row
+    const int nl = (cols + 15) >> 4;                 // lanes of a row that own bytes
+    const int off = min(16 * j, cols - 16);          // lanes past the end repeat the last one and store nothing
+    const bool owner = j < nl;
+    const bool last = j == nl - 1;
+    const int dup = 16 * (nl - 1) - (cols - 16);     // leading bytes of the last lane that its neighbour owns
+    const int sh = p.m_bits - (p.k_out - 1);
+    const int64_t slot = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
+    const int64_t nslots = (int64_t)gridDim.x * (256 / LPR);
+    auto umax = [](uint32_t a, uint32_t b) { return max(a, b); };
+    auto uadd = [](uint32_t a, uint32_t b) { return a + b; };
+    for (int64_t r0 = slot; r0 < rows; r0 += nslots * UNR) {
+        u32x4_unaligned in[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t r = min(r0 + u * nslots, rows - 1);          // a slot past the end repeats the last row
+            in[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_unaligned*>(x + r * ld + off));
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int64_t r = r0 + u * nslots;
+            uint32_t xf[4];
+            u16x2 m2 = {0, 0};
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                xf[d] = in[u][d] ^ 0x80808080u;
+                const uint32_t lo = xf[d] & 0x00ff00ffu, hi = (xf[d] >> 8) & 0x00ff00ffu;
+                m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(u16x2, lo));
+                m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(u16x2, hi));
+            }
+            const uint32_t mx = group_allreduce<LPR>(max((uint32_t)m2[0], (uint32_t)m2[1]), umax);
+            const uint32_t mrep = mx * 0x01010101u;
+            uint32_t e[16];
+            uint32_t full = 0, tail = 0;
+#pragma unroll
+            for (int k = 0; k < 16; ++k) {
+                const uint32_t delta = mrep - xf[k >> 2];                // bytewise, no borrows: every byte <= max
+                e[k] = lut[(delta >> (8 * (k & 3))) & 0xffu];
+                full += e[k];
+                if (k >= dup) tail += e[k];                              // uniform condition
+            }
+            const uint32_t mine = owner ? (last ? tail : full) : 0u;
+            const uint32_t sum = group_allreduce<LPR>(mine, uadd);
+            const uint32_t inv = (1u << p.m_bits) / sum;
+            uint32_t out[4];
+            const uint32_t invs = FAST ? inv << (32 - sh) : inv;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const uint32_t ek = e[4 * d + b];
+                    const uint32_t q = FAST ? __umulhi(invs, ek) : (inv * ek) >> sh;
+                    w |= q << (8 * b);                                   // q <= 2^(k_out-1) fits a byte
+                }
+                out[d] = w - ((w >> (p.k_out - 1)) & 0x01010101u);       // bytewise min(q, 2^(k_out-1) - 1)
+            }
+            if (owner && r < rows) {
+                u32x4_unaligned o = {out[0], out[1], out[2], out[3]};
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4_unaligned*>(y + r * cols + off));
+            }
+        }
+    }
+}
+
+template <int LPR>
+static void launch_shiftmax_vec(hipStream_t s, const int8_t* x, int8_t* y, int64_t rows, int cols, int ld, ShiftParams p) {
+    constexpr int UNR = 2;
+    const int64_t per_wg = (256 / LPR) * UNR;
+    const int grid = (int)std::min<int64_t>((rows + per_wg - 1) / per_wg, (int64_t)num_cus() * 32);
+    // inv << (32 - sh) must fit 32 bits: inv <= 2^M / (I_0 << N) < 2^sh needs I_0 << N > 2^(k_out - 1); sh >= 1
+    const int sh = p.m_bits - (p.k_out - 1);
+    const bool fast = sh >= 1 && ((int64_t)p.i0 << p.n_shift) > ((int64_t)1 << (p.k_out - 1));
+    if (fast) hipLaunchKernelGGL((shiftmax_vec_kernel<LPR, UNR, true>), dim3(grid), dim3(256), 0, s, x, y, rows, cols, ld, p);
+    else hipLaunchKernelGGL((shiftmax_vec_kernel<LPR, UNR, false>), dim3(grid), dim3(256), 0, s, x, y, rows, cols, ld, p);
+}
+
 hipError_t launch_shiftmax(hipStream_t s, const int8_t* x, const int8_t* bias, int H, int T, int8_t* y,
                            int64_t rows, int cols, int ld, ShiftParams p) {
     if (rows == 0) return hipSuccess;
@@ -259,6 +365,12 @@ hipError_t launch_shiftmax(hipStream_t s, const int8_t* x, const int8_t* bias, i
     const int grid = (int)std::min<int64_t>(want, (int64_t)num_cus() * 16);
     const int nt = (cols + 63) / 64;
     TraceScope trace(s, KIND_SHIFTMAX, 0, rows * cols * (bias ? 3LL : 2LL));
+    if (!bias && cols >= 16 && cols <= 256) {
+        if (cols <= 64) launch_shiftmax_vec<4>(s, x, y, rows, cols, ld, p);
+        else if (cols <= 128) launch_shiftmax_vec<8>(s, x, y, rows, cols, ld, p);
+        else launch_shiftmax_vec<16>(s, x, y, rows, cols, ld, p);
+        return hipGetLastError();
+    }
     if (nt <= 1) hipLaunchKernelGGL(shiftmax_kernel<1>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
     else if (nt <= 2) hipLaunchKernelGGL(shiftmax_kernel<2>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);
     else if (nt <= 4) hipLaunchKernelGGL(shiftmax_kernel<4>, dim3(grid), dim3(256), 0, s, x, bias, H, T, y, rows, cols, ld, p);

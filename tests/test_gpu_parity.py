@@ -74,7 +74,11 @@ def test_ilayernorm_other_shift_counts_and_spike_rows(ivit):
 # ------------------------------------------------------------------ Shiftmax
 @pytest.mark.parametrize("rows,cols,ld,i0", [
     (0, 49, 49, 32), (1, 1, 1, 32), (5, 49, 49, 32), (1000, 65, 65, 32), (4099, 197, 197, 32), (333, 197, 208, 12),
-    (100, 256, 256, 64), (17, 1000, 1024, 8), (64, 64, 64, 4), (300, 130, 131, 100)])
+    (100, 256, 256, 64), (17, 1000, 1024, 8), (64, 64, 64, 4), (300, 130, 131, 100),
+    # 16 <= cols <= 256: lanes own 16 bytes each, the last one overlapping its neighbour; ragged row counts
+    (1, 16, 16, 32), (7, 17, 17, 32), (129, 31, 31, 32), (2000, 32, 40, 16), (1031, 48, 48, 32), (555, 63, 63, 8),
+    (4097, 65, 65, 32), (513, 128, 128, 32), (77, 129, 135, 32), (1001, 255, 255, 32), (9000, 49, 49, 32),
+    (20000, 197, 197, 20), (3, 15, 15, 32)])
 def test_shiftmax(ivit, rows, cols, ld, i0):
     x = synth.make_rows(rows + cols, rows, ld, "normal", 1.5 * min(i0, 40))
     p = synth.shift_params(i0)
@@ -95,6 +99,16 @@ def test_shiftmax_extreme_rows(ivit):
     y = empty((6, 197))
     ivit.ivit_shiftmax(dev(x), y, p)
     assert_same(host(y), orc.shiftmax(x, p), "shiftmax extremes")
+
+
+def test_shiftmax_general_intdiv_parameters(ivit):
+    # I_0 << N not above 2^(k_out - 1), small M, narrow outputs: the reciprocal cannot be pre-shifted
+    x = synth.make_rows(9, 700, 197, "normal", 30.0)
+    for prm in (dict(i0=3, n_shift=2, m_bits=31, k_out=8), dict(i0=32, n_shift=10, m_bits=20, k_out=8),
+                dict(i0=32, n_shift=10, m_bits=31, k_out=4), dict(i0=100, n_shift=0, m_bits=7, k_out=8)):
+        y = empty(x.shape)
+        ivit.ivit_shiftmax(dev(x), y, prm)
+        assert_same(host(y), orc.shiftmax(x, prm), "shiftmax %r" % (prm,))
 
 
 @pytest.mark.parametrize("n_img,H,T", [(3, 3, 49), (2, 2, 65)])
