@@ -13,6 +13,8 @@
 // consecutive channels: they are requantised, packed and stored as two 16-byte writes per token.
 // Workgroup ids are remapped so that each XCD (own L2) works on a contiguous range of tiles.
 #include "ivit_kernels.hpp"
+#include <algorithm>
+#include <type_traits>
 
 namespace ivit {
 
@@ -242,6 +244,300 @@ __global__ __launch_bounds__(256, IVIT_GEMM_WGS_PER_CU) void gemm_i8_kernel(Gemm
     else epilogue<EPI, false>(P, acc, qb_s, qc_s, gelu_lut, m0 + wm + li, n0 + cl, cl);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Weight-stationary kernel for K small enough that a slab of 32 NCB output channels, all of K, stays in LDS.
+//
+// A workgroup (8 wavefronts, two per SIMD) loads its weight slab once; only this prologue has barriers.  Every
+// wavefront then walks over its own groups of 32 tokens, reads their activations straight from global memory into
+// registers in the layout of the MFMA "B" operand (no LDS round trip: nobody else needs them) and multiplies them
+// with the slab, NCB tiles of v_mfma_i32_32x32x32_i8 per 32 bytes of K.  Within a 128-byte chunk of K a lane reads
+// 64 contiguous bytes (lane group g the half g of the chunk) and uses its j-th 16 bytes in the j-th MFMA of the
+// chunk; the weight fragments are read from LDS with the same assignment of K bytes to MFMAs, so the contraction
+// is unchanged.  Activations move in units of UNIT chunks through two register buffers: while one unit is
+// multiplied the loads of the next one (of the next group, at the end of a group) are in flight, which hides the
+// memory latency, and the second wavefront of the SIMD feeds the matrix core while this one requantises.
+// Slab rows are stored in LDS so that the accumulator registers of a lane are 16 NCB consecutive channels of one
+// token (see row_of_channel); results go through a small per-wavefront LDS buffer so that every store instruction
+// writes whole output rows.
+constexpr int WS_THREADS = 512, WS_WAVES = WS_THREADS / 64, WS_CHUNK = 128;
+constexpr int WS_LDS_MAX = 160 * 1024;
+
+struct WsParams {
+    GemmParams g;
+    int slabs, q, nunits, pitch;        // channel slabs, workgroups per slab, units per group, LDS row pitch
+    int64_t groups;                     // groups of 32 tokens
+};
+
+// LDS row (within the slab) of slab-local channel n: lane group g owns channels 16 NCB g .. 16 NCB (g + 1) - 1;
+// channel 16 NCB g + 16 cb + 4 q + r is row 8 q + 4 g + r of MFMA tile cb, i.e. accumulator register 4 q + r.
+template <int NCB>
+__device__ __forceinline__ int row_of_channel(int n) {
+    const int g = n / (16 * NCB), rem = n % (16 * NCB), cb = rem >> 4, v = rem & 15;
+    return 32 * cb + 8 * (v >> 2) + 4 * g + (v & 3);
+}
+
+// UNIT: chunks per unit.  PAD: K is not a whole number of units, the rest reads as zero.  EVEN: the number of
+// units per group is even, so a group can only end after the second unit of the unrolled pair.
+template <int EPI, int NCB, int UNIT, bool PAD, bool EVEN>
+__global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
+    extern __shared__ __align__(16) int8_t lds[];
+    const GemmParams& P = W.g;
+    constexpr int NS = 32 * NCB;                       // channels of a slab
+    constexpr int RB = 32 * NCB, SP = RB + 16;         // bytes of an output row of the slab, pitch of its staging copy
+    constexpr int STG = 32 * SP > 4096 ? 32 * SP : 4096;   // staging bytes per wavefront (the general path needs 4096)
+    const int pitch = W.pitch, nunits = W.nunits;
+    int8_t* Wl = lds;
+    int32_t* qb_s = reinterpret_cast<int32_t*>(lds + (size_t)NS * pitch);
+    int32_t* qc_s = qb_s + NS;
+    int32_t* bias_s = qc_s + NS;
+    int32_t* slow_s = bias_s + NS;
+    int8_t* gelu_lut = reinterpret_cast<int8_t*>(slow_s + 4);
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    int8_t* stage = gelu_lut + 256 + wv * STG;     // this wavefront's 32 token rows, written and read by it alone
+    const int K = P.K, N = P.N;
+    const int64_t M = P.M;
+
+    // workgroups of one XCD (block id modulo 8) get consecutive logical ids: the slabs that share a token range, and
+    // therefore re-read the same activations, sit on the same L2
+    const int G = gridDim.x, xcd = blockIdx.x % NXCD;
+    const int L = xcd * (G / NXCD) + min(xcd, G % NXCD) + blockIdx.x / NXCD;
+    const int slab = L % W.slabs, wi = L / W.slabs;
+    const int n0 = slab * NS;
+
+    const int64_t stride = (int64_t)W.q * WS_WAVES;
+    int64_t cgrp = (int64_t)wi * WS_WAVES + wv;         // group being multiplied
+    int64_t lgrp = cgrp;                                // group and unit of the next load
+    int lu = 0;
+    const bool has_work = cgrp < W.groups;
+
+    // One unit of activations: lane (li, lg) gets bytes 128 c + 64 lg .. + 63 of chunk c of token li of the group.
+    // No branches around the loads (the compiler then counts outstanding loads exactly): past the last group the
+    // last one is loaded again, and with PAD a piece past the end of the row reads the row's last 16 bytes and is
+    // replaced by zero.
+    v4i xa[UNIT][4], xb[UNIT][4];
+    auto issue = [&](v4i (&buf)[UNIT][4]) __attribute__((always_inline)) {
+        const int64_t tok = min<int64_t>(min<int64_t>(lgrp, W.groups - 1) * 32 + li, M - 1);
+        const int8_t* row = P.x + tok * K;
+        const int start = lu * (UNIT * WS_CHUNK) + 64 * lg;
+#pragma unroll
+        for (int c = 0; c < UNIT; ++c)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int off = start + c * WS_CHUNK + 16 * j;
+                if (PAD) {
+                    const v4i v = *reinterpret_cast<const v4i*>(row + min(off, K - 16));
+                    buf[c][j] = off < K ? v : v4i{0, 0, 0, 0};
+                } else {
+                    buf[c][j] = *reinterpret_cast<const v4i*>(row + off);
+                }
+            }
+        if (++lu == nunits) { lu = 0; lgrp += stride; }
+    };
+    if (has_work) issue(xa);                            // in flight during the prologue
+    bool slow_any;
+
+    // ---- prologue: the slab (zero padded to whole units and whole slabs), its parameters, the GELU table; all
+    // global loads are issued before anything waits for one of them
+    {
+        int32_t pb = 1, pc = 1, pbias = 0;
+        if (tid < NS && n0 + tid < N) {
+            pb = P.rq_b[n0 + tid]; pc = P.rq_c[n0 + tid];
+            if (P.bias) pbias = P.bias[n0 + tid];
+        }
+        const int cpr = nunits * UNIT * (WS_CHUNK / 16);   // 16-byte pieces per padded row
+        for (int idx = tid; idx < NS * cpr; idx += WS_THREADS) {
+            const int n = idx / cpr, ck = idx - n * cpr;
+            v4i v = {0, 0, 0, 0};
+            if (n0 + n < N && 16 * ck < K) v = *reinterpret_cast<const v4i*>(P.w + (int64_t)(n0 + n) * K + 16 * ck);
+            *reinterpret_cast<v4i*>(Wl + row_of_channel<NCB>(n) * pitch + 16 * ck) = v;
+        }
+        if (tid < NS) { qb_s[tid] = pb; qc_s[tid] = pc; bias_s[tid] = pbias; }
+        if (EPI == EPI_GELU && tid < 256) {
+            const int32_t I = (int32_t)(int8_t)tid;
+            gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
+        }
+        const bool chan_fast = tid >= NS || dyadic_fits32(pb, pc);
+        slow_any = __syncthreads_and(chan_fast) == 0;
+    }
+#ifndef IVIT_WS_DBG
+#define IVIT_WS_DBG 0
+#endif
+    if (!has_work || (IVIT_WS_DBG & 1)) return;
+    const bool fast = !slow_any && (EPI != EPI_RESIDUAL || dyadic_fits32(P.res_rq.b, P.res_rq.c));
+
+    v16i acc[NCB];
+    auto reset_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const v4i t = *reinterpret_cast<const v4i*>(&bias_s[16 * NCB * lg + 16 * cb + 4 * q]);
+                acc[cb][4 * q] = t[0]; acc[cb][4 * q + 1] = t[1]; acc[cb][4 * q + 2] = t[2]; acc[cb][4 * q + 3] = t[3];
+            }
+    };
+    const int8_t* wl_lane = Wl + li * pitch + 64 * lg;
+    int cu = 0;                                         // unit of the group being multiplied
+
+    // 4 UNIT groups of NCB MFMAs; the weight fragments of a group are read while the previous group is multiplied
+    auto consume = [&](const v4i (&buf)[UNIT][4]) __attribute__((always_inline)) {
+        const int8_t* wp = wl_lane + cu * (UNIT * WS_CHUNK);
+        v4i af[2][NCB];
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) af[0][cb] = *reinterpret_cast<const v4i*>(wp + cb * 32 * pitch);
+#pragma unroll
+        for (int n = 0; n < 4 * UNIT; ++n) {
+            if (n + 1 < 4 * UNIT && !((IVIT_WS_DBG & 8) && n > 0)) {
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+                    af[(n + 1) & 1][cb] = *reinterpret_cast<const v4i*>(wp + cb * 32 * pitch + ((n + 1) >> 2) * WS_CHUNK + 16 * ((n + 1) & 3));
+            }
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb)
+                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[n & 1][cb], buf[n >> 2][n & 3], acc[cb], 0, 0, 0);
+        }
+    };
+
+    // Requantise the 16 NCB channels of this lane's token and store the group's 32 rows.
+    auto finish = [&]() __attribute__((always_inline)) {
+        const int64_t tok = cgrp * 32 + li;
+        const int nl = 16 * NCB * lg;                   // slab-local first channel of the lane
+        if (fast) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                const int nb = n0 + nl + 16 * cb;
+                v4i resv = {0, 0, 0, 0};
+                if (EPI == EPI_RESIDUAL) {              // N % 16 == 0: a 16-channel piece is in or out as a whole
+                    const int64_t rt = min<int64_t>(tok, M - 1);
+                    resv = *reinterpret_cast<const v4i*>(P.residual + rt * N + min(nb, N - 16));
+                }
+                v4i outv;
+#pragma unroll
+                for (int w4 = 0; w4 < 4; ++w4) {
+                    const v4i qb = *reinterpret_cast<const v4i*>(&qb_s[nl + 16 * cb + 4 * w4]);
+                    const v4i qc = *reinterpret_cast<const v4i*>(&qc_s[nl + 16 * cb + 4 * w4]);
+                    uint32_t o[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int32_t v = rnd_shift_fit32(acc[cb][4 * w4 + r], qb[r], qc[r]);
+                        if (EPI == EPI_RESIDUAL) {
+                            const int32_t res = (int32_t)(int8_t)((uint32_t)resv[w4] >> (8 * r));
+                            v += rnd_shift_fit32(res, P.res_rq.b, P.res_rq.c);
+                        }
+                        v = clamp8(v);
+                        if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
+                        o[r] = (uint32_t)v;
+                    }
+                    // low bytes of o[0..3] -> one word (byte selectors 0-3 pick from the second operand, 4-7 from the first)
+                    const uint32_t lo = __builtin_amdgcn_perm(o[1], o[0], 0x0c0c0400u);
+                    const uint32_t hi = __builtin_amdgcn_perm(o[3], o[2], 0x04000c0cu);
+                    outv[w4] = (int)(lo | hi);
+                }
+                *reinterpret_cast<v4i*>(stage + li * SP + nl + 16 * cb) = outv;
+            }
+        } else {
+            // general dyadic pairs (64-bit rounding): one MFMA tile at a time through the staging buffer as int32,
+            // in a rolled loop; this path is rare and kept small rather than fast
+            int32_t* st32 = reinterpret_cast<int32_t*>(stage);              // [32 tokens][32 channels] fits 32 SP bytes
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                const v16i a = acc[cb];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<v4i*>(st32 + li * 32 + 16 * lg + 4 * q) = v4i{a[4 * q], a[4 * q + 1], a[4 * q + 2], a[4 * q + 3]};
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll 1
+                for (int e = lane; e < 32 * 32; e += 64) {
+                    const int t = e >> 5, c = e & 31;   // token row, channel 16 (c / 16) NCB... see below
+                    const int g2 = c >> 4, v2 = c & 15;
+                    const int nloc = 16 * NCB * g2 + 16 * cb + v2;
+                    const int64_t tk = cgrp * 32 + t;
+                    const int n = n0 + nloc;
+                    if (tk < M && n < N) {
+                        const int32_t a32 = st32[t * 32 + c];
+                        int64_t r64 = rnd_shift64(a32, qb_s[nloc], qc_s[nloc]);
+                        int32_t v;
+                        if (EPI == EPI_RESIDUAL) v = clamp8_64(r64 + rnd_shift64(P.residual[tk * N + n], P.res_rq.b, P.res_rq.c));
+                        else v = clamp8_64(r64);
+                        if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
+                        P.y[tk * N + n] = (int8_t)v;
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+            return;
+        }
+        // The lane's 16-byte pieces lie in 32 different rows; written like that every store instruction would touch
+        // 32 memory lines.  Through the staging rows each store instruction writes whole rows instead: 2 NCB
+        // adjacent lanes cover the 32 NCB bytes of one token.
+        __builtin_amdgcn_wave_barrier();
+        constexpr int LPR = 2 * NCB, RPI = 64 / LPR;    // lanes per row, rows per store instruction
+        const int srow = lane / LPR, piece = lane % LPR;
+#pragma unroll
+        for (int t = 0; t < NCB; ++t) {
+            const int row = t * RPI + srow;
+            const v4i v = *reinterpret_cast<const v4i*>(stage + row * SP + 16 * piece);
+            const int64_t tk = cgrp * 32 + row;
+            if (tk < M && n0 + 16 * piece < N) *reinterpret_cast<v4i*>(P.y + tk * N + n0 + 16 * piece) = v;
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
+
+    // true when the wavefront has finished its last group
+    auto end_of_unit = [&]() __attribute__((always_inline)) -> bool {
+        if (++cu < nunits) return false;
+        if (!(IVIT_WS_DBG & 2)) finish();
+        else if (acc[0][0] + acc[1][5] + acc[NCB - 1][7] + acc[NCB - 2][9] == 0x12345678) P.y[0] = 1;
+        cu = 0;
+        cgrp += stride;
+        if (cgrp >= W.groups) return true;
+        reset_acc();
+        return false;
+    };
+
+#ifndef IVIT_WS_STAGGER
+#define IVIT_WS_STAGGER 0
+#endif
+    if (IVIT_WS_STAGGER > 0 && wv >= 4) __builtin_amdgcn_s_sleep(IVIT_WS_STAGGER);
+    reset_acc();
+    for (;;) {
+        if (!(IVIT_WS_DBG & 4)) issue(xb);
+        consume(xa);
+        if (EVEN) ++cu; else if (end_of_unit()) return;
+        if (!(IVIT_WS_DBG & 4)) issue(xa);
+        consume(xb);
+        if (end_of_unit()) return;
+    }
+}
+
+static bool ws_plan(const LinearArgs& a, int& ncb, int& unit, int& nunits, int& pitch, size_t& lds_bytes) {
+    if ((a.N & 15) != 0 || (a.K & 15) != 0) return false;
+    unit = a.K % (3 * WS_CHUNK) == 0 ? 3 : 1;
+    nunits = (a.K + unit * WS_CHUNK - 1) / (unit * WS_CHUNK);
+    const int kp = nunits * unit * WS_CHUNK;
+    pitch = kp + ((kp / 16) % 2 == 0 ? 16 : 32);        // (pitch / 16) odd: 16 lanes x 16 bytes cover all LDS banks
+    for (ncb = 4; ncb >= 2; ncb >>= 1) {
+        lds_bytes = (size_t)32 * ncb * pitch + 3 * 4 * 32 * ncb + 16 + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 4096);
+        if (lds_bytes <= (size_t)WS_LDS_MAX) return true;
+    }
+    return false;
+}
+
+template <int EPI, int NCB>
+static void launch_ws_ncb(hipStream_t s, const WsParams& W, int unit, int grid, size_t lds_bytes) {
+    const dim3 g(grid), b(WS_THREADS);
+    if (unit == 3 && W.nunits % 2 == 0) hipLaunchKernelGGL((gemm_ws_kernel<EPI, NCB, 3, false, true>), g, b, lds_bytes, s, W);
+    else if (unit == 3) hipLaunchKernelGGL((gemm_ws_kernel<EPI, NCB, 3, false, false>), g, b, lds_bytes, s, W);
+    else hipLaunchKernelGGL((gemm_ws_kernel<EPI, NCB, 1, true, false>), g, b, lds_bytes, s, W);
+}
+
+template <int EPI>
+static void launch_ws(hipStream_t s, const WsParams& W, int ncb, int unit, int grid, size_t lds_bytes) {
+    if (ncb == 4) launch_ws_ncb<EPI, 4>(s, W, unit, grid, lds_bytes);
+    else launch_ws_ncb<EPI, 2>(s, W, unit, grid, lds_bytes);
+}
+
 hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     if (a.M == 0) return hipSuccess;
     GemmParams P;
@@ -256,6 +552,21 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int64_t bytes = a.M * a.K + (int64_t)a.N * a.K + a.M * a.N * (a.residual ? 2 : 1) + 8LL * a.N + (a.bias ? 4LL * a.N : 0);
     TraceScope trace(s, a.residual ? KIND_GEMM_RESIDUAL : (a.gelu ? KIND_GEMM_GELU : KIND_GEMM), 2 * a.M * a.N * a.K, bytes);
+    int ncb, unit, nunits, pitch; size_t lds_bytes;
+    // the weight-stationary kernel pays off with 128-channel slabs and enough of them to spread token ranges thinly
+    if (ws_plan(a, ncb, unit, nunits, pitch, lds_bytes) && ncb == 4 && (a.N + 127) / 128 >= 6) {
+        WsParams W;
+        W.g = P; W.pitch = pitch; W.nunits = nunits;
+        W.slabs = (a.N + 32 * ncb - 1) / (32 * ncb);
+        W.groups = (a.M + 31) / 32;
+        const int64_t want = (W.groups + WS_WAVES - 1) / WS_WAVES;        // workgroups per slab that still get a group
+        W.q = (int)std::max<int64_t>(1, std::min<int64_t>(want, num_cus() / W.slabs));
+        const int wgrid = W.q * W.slabs;
+        if (a.residual) launch_ws<EPI_RESIDUAL>(s, W, ncb, unit, wgrid, lds_bytes);
+        else if (a.gelu) launch_ws<EPI_GELU>(s, W, ncb, unit, wgrid, lds_bytes);
+        else launch_ws<EPI_PLAIN>(s, W, ncb, unit, wgrid, lds_bytes);
+        return hipGetLastError();
+    }
     if (a.residual) hipLaunchKernelGGL(gemm_i8_kernel<EPI_RESIDUAL>, dim3((unsigned)grid), dim3(256), 0, s, P);
     else if (a.gelu) hipLaunchKernelGGL(gemm_i8_kernel<EPI_GELU>, dim3((unsigned)grid), dim3(256), 0, s, P);
     else hipLaunchKernelGGL(gemm_i8_kernel<EPI_PLAIN>, dim3((unsigned)grid), dim3(256), 0, s, P);
