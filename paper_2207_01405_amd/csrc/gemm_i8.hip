@@ -306,8 +306,10 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     const int slab = L % W.slabs, wi = L / W.slabs;
     const int n0 = slab * NS;
 
+    // group r + t stride belongs to wavefront r / q of workgroup r % q: when the last round is not full, its groups go
+    // to the low wavefronts (distinct SIMDs) of all workgroups instead of to all wavefronts of a few
     const int64_t stride = (int64_t)W.q * WS_WAVES;
-    int64_t cgrp = (int64_t)wi * WS_WAVES + wv;         // group being multiplied
+    int64_t cgrp = (int64_t)wv * W.q + wi;              // group being multiplied
     int64_t lgrp = cgrp;                                // group and unit of the next load
     int lu = 0;
     const bool has_work = cgrp < W.groups;
@@ -517,7 +519,9 @@ static bool ws_plan(const LinearArgs& a, int& ncb, int& unit, int& nunits, int& 
     nunits = (a.K + unit * WS_CHUNK - 1) / (unit * WS_CHUNK);
     const int kp = nunits * unit * WS_CHUNK;
     pitch = kp + ((kp / 16) % 2 == 0 ? 16 : 32);        // (pitch / 16) odd: 16 lanes x 16 bytes cover all LDS banks
-    for (ncb = 4; ncb >= 2; ncb >>= 1) {
+    // 128-channel slabs halve the activation traffic per MFMA; with fewer than six of them the 64-channel slabs'
+    // finer work items fill the wavefronts more evenly
+    for (ncb = (a.N + 127) / 128 >= 6 ? 4 : 2; ncb >= 2; ncb >>= 1) {
         lds_bytes = (size_t)32 * ncb * pitch + 3 * 4 * 32 * ncb + 16 + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 4096);
         if (lds_bytes <= (size_t)WS_LDS_MAX) return true;
     }
@@ -553,8 +557,7 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     const int64_t bytes = a.M * a.K + (int64_t)a.N * a.K + a.M * a.N * (a.residual ? 2 : 1) + 8LL * a.N + (a.bias ? 4LL * a.N : 0);
     TraceScope trace(s, a.residual ? KIND_GEMM_RESIDUAL : (a.gelu ? KIND_GEMM_GELU : KIND_GEMM), 2 * a.M * a.N * a.K, bytes);
     int ncb, unit, nunits, pitch; size_t lds_bytes;
-    // the weight-stationary kernel pays off with 128-channel slabs and enough of them to spread token ranges thinly
-    if (ws_plan(a, ncb, unit, nunits, pitch, lds_bytes) && ncb == 4 && (a.N + 127) / 128 >= 6) {
+    if (ws_plan(a, ncb, unit, nunits, pitch, lds_bytes)) {
         WsParams W;
         W.g = P; W.pitch = pitch; W.nunits = nunits;
         W.slabs = (a.N + 32 * ncb - 1) / (32 * ncb);

@@ -179,13 +179,22 @@ hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamm
                              int8_t* y, int64_t rows, int C, int f_bits, int c_shift) {
     if (rows == 0) return hipSuccess;
     if ((C & 15) == 0 && C >= 64 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma_q | (uintptr_t)beta_q) & 15) == 0) {
-        constexpr int J = 8;
-        const int R = (256 / (C >> 4)) * J;
-        const int64_t grid = (rows + R - 1) / R;
+        // rows per workgroup = (256 / (C / 16)) * J: fewer passes J for small inputs, so that every CU still holds
+        // several workgroups whose load, statistics and store phases overlap
+        const int rp = 256 / (C >> 4);
+        const int64_t enough = (int64_t)num_cus() * 8;
+        int J = 8;
+        while (J > 1 && (rows + rp * J - 1) / (rp * J) < enough) J >>= 1;
+        const int64_t grid = (rows + rp * J - 1) / (rp * J);
         if (grid <= 0x7fffffffLL) {
             TraceScope trace(s, KIND_ILAYERNORM, 0, 2 * rows * C + 8LL * C);
-            hipLaunchKernelGGL(ilayernorm_tiled_kernel<J>, dim3((unsigned)grid), dim3(256), 0, s, x, gamma_q, beta_q, y,
-                               rows, C, f_bits, c_shift);
+            const dim3 g((unsigned)grid), b(256);
+            switch (J) {
+                case 8: hipLaunchKernelGGL(ilayernorm_tiled_kernel<8>, g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+                case 4: hipLaunchKernelGGL(ilayernorm_tiled_kernel<4>, g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+                case 2: hipLaunchKernelGGL(ilayernorm_tiled_kernel<2>, g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+                default: hipLaunchKernelGGL(ilayernorm_tiled_kernel<1>, g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+            }
             return hipGetLastError();
         }
     }

@@ -144,7 +144,9 @@ def test_shiftgelu(ivit, n, i0):
 
 # ------------------------------------------------------------------ Dense / MatMul + requant
 LIN_SHAPES = [(0, 64, 64), (1, 1, 16), (5, 7, 80), (65, 192, 64), (130, 40, 256), (129, 100, 48), (1000, 384, 384),
-              (197, 1536, 384), (300, 384, 1536), (257, 130, 3072), (64, 256, 16)]
+              (197, 1536, 384), (300, 384, 1536), (257, 130, 3072), (64, 256, 16),
+              # weight-stationary kernel: partial channel slabs, one-chunk K, even / odd unit counts, many groups per wavefront
+              (333, 208, 96), (40, 16, 32), (515, 2304, 768), (30011, 128, 384), (2100, 768, 1152), (77, 1168, 640)]
 
 
 @pytest.mark.parametrize("M,N,K", LIN_SHAPES)
@@ -175,8 +177,9 @@ def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit):
                     np.int32)
     rq_b[:8] = 2 ** 31 - 1; rq_c[:8] = 46
     res = synth.make_rows(3, M, N, "uniform")
+    gl = dict(gelu=synth.shift_params(20), gelu_rq=(2 ** 31 - 1, 38))
     for kw_o, kw_g in (({}, {}), (dict(residual=res, res_rq=(2 ** 31 - 1, 31)), dict(residual=dev(res), res_rq=(2 ** 31 - 1, 31))),
-                       (dict(residual=res, res_rq=(3, 1)), dict(residual=dev(res), res_rq=(3, 1)))):
+                       (dict(residual=res, res_rq=(3, 1)), dict(residual=dev(res), res_rq=(3, 1))), (gl, gl)):
         y = empty((M, N))
         ivit.ivit_linear_requant(dev(x), dev(w), None, dev(rq_b), dev(rq_c), y, **kw_g)
         want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
