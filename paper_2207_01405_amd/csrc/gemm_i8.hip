@@ -284,7 +284,8 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     const GemmParams& P = W.g;
     constexpr int NS = 32 * NCB;                       // channels of a slab
     constexpr int RB = 32 * NCB, SP = RB + 16;         // bytes of an output row of the slab, pitch of its staging copy
-    constexpr int STG = 32 * SP > 4096 ? 32 * SP : 4096;   // staging bytes per wavefront (the general path needs 4096)
+    constexpr int XP = WS_CHUNK + 16;                  // pitch of a staged activation chunk (32 tokens x 128 bytes)
+    constexpr int STG = 32 * SP > 32 * XP ? 32 * SP : 32 * XP;   // staging bytes per wavefront: output rows, or one chunk
     const int pitch = W.pitch, nunits = W.nunits;
     int8_t* Wl = lds;
     int32_t* qb_s = reinterpret_cast<int32_t*>(lds + (size_t)NS * pitch);
@@ -314,27 +315,32 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     int lu = 0;
     const bool has_work = cgrp < W.groups;
 
-    // One unit of activations: lane (li, lg) gets bytes 128 c + 64 lg .. + 63 of chunk c of token li of the group.
+    // One unit of activations.  A load instruction reads whole 128-byte lines (8 lanes per token, 8 tokens per
+    // instruction, 4 instructions per chunk): lane l gets piece l % 8 of chunk c of tokens 8 t + l / 8, t = 0..3.
+    // Scattered 16-byte reads in MFMA layout would cost the texture addresser one cycle per touched line, twice the
+    // time; the chunk is brought into MFMA layout through this wavefront's LDS staging rows right before its use.
     // No branches around the loads (the compiler then counts outstanding loads exactly): past the last group the
     // last one is loaded again, and with PAD a piece past the end of the row reads the row's last 16 bytes and is
     // replaced by zero.
     v4i xa[UNIT][4], xb[UNIT][4];
+    const int l8 = lane >> 3, p8 = lane & 7;
     auto issue = [&](v4i (&buf)[UNIT][4]) __attribute__((always_inline)) {
-        const int64_t tok = min<int64_t>(min<int64_t>(lgrp, W.groups - 1) * 32 + li, M - 1);
-        const int8_t* row = P.x + tok * K;
-        const int start = lu * (UNIT * WS_CHUNK) + 64 * lg;
+        const int64_t g0 = min<int64_t>(lgrp, W.groups - 1) * 32 + l8;
+        const int start = lu * (UNIT * WS_CHUNK) + 16 * p8;
 #pragma unroll
-        for (int c = 0; c < UNIT; ++c)
+        for (int t = 0; t < 4; ++t) {
+            const int8_t* row = P.x + min<int64_t>(g0 + 8 * t, M - 1) * K;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int off = start + c * WS_CHUNK + 16 * j;
+            for (int c = 0; c < UNIT; ++c) {
+                const int off = start + c * WS_CHUNK;
                 if (PAD) {
                     const v4i v = *reinterpret_cast<const v4i*>(row + min(off, K - 16));
-                    buf[c][j] = off < K ? v : v4i{0, 0, 0, 0};
+                    buf[c][t] = off < K ? v : v4i{0, 0, 0, 0};
                 } else {
-                    buf[c][j] = *reinterpret_cast<const v4i*>(row + off);
+                    buf[c][t] = *reinterpret_cast<const v4i*>(row + off);
                 }
             }
+        }
         if (++lu == nunits) { lu = 0; lgrp += stride; }
     };
     if (has_work) issue(xa);                            // in flight during the prologue
@@ -382,14 +388,29 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     const int8_t* wl_lane = Wl + li * pitch + 64 * lg;
     int cu = 0;                                         // unit of the group being multiplied
 
-    // 4 UNIT groups of NCB MFMAs; the weight fragments of a group are read while the previous group is multiplied
+    // A unit: per chunk 4 groups of NCB MFMAs.  The chunk after the one being multiplied goes through the staging
+    // rows meanwhile (LDS executes a wavefront's accesses in order, so the rows can be overwritten as soon as the
+    // reads of the previous chunk have been issued), and the weight fragments of an MFMA group are read while the
+    // previous group is multiplied.
+    int8_t* st_wr = stage + l8 * XP + 16 * p8;          // where this lane's piece of tokens l8 + 8 t goes
+    const int8_t* st_rd = stage + li * XP + 64 * lg;    // MFMA layout: token li, bytes 64 lg + 16 j of the chunk
+    auto stage_chunk = [&](const v4i (&ch)[4], v4i (&bf)[4]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) *reinterpret_cast<v4i*>(st_wr + 8 * t * XP) = ch[t];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bf[j] = *reinterpret_cast<const v4i*>(st_rd + 16 * j);
+        __builtin_amdgcn_wave_barrier();
+    };
     auto consume = [&](const v4i (&buf)[UNIT][4]) __attribute__((always_inline)) {
         const int8_t* wp = wl_lane + cu * (UNIT * WS_CHUNK);
-        v4i af[2][NCB];
+        v4i af[2][NCB], bf[2][4];
+        stage_chunk(buf[0], bf[0]);
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) af[0][cb] = *reinterpret_cast<const v4i*>(wp + cb * 32 * pitch);
 #pragma unroll
         for (int n = 0; n < 4 * UNIT; ++n) {
+            if ((n & 3) == 0 && (n >> 2) + 1 < UNIT) stage_chunk(buf[(n >> 2) + 1], bf[((n >> 2) + 1) & 1]);
             if (n + 1 < 4 * UNIT && !((IVIT_WS_DBG & 8) && n > 0)) {
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb)
@@ -397,7 +418,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             }
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb)
-                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[n & 1][cb], buf[n >> 2][n & 3], acc[cb], 0, 0, 0);
+                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[n & 1][cb], bf[(n >> 2) & 1][n & 3], acc[cb], 0, 0, 0);
         }
     };
 
@@ -522,7 +543,7 @@ static bool ws_plan(const LinearArgs& a, int& ncb, int& unit, int& nunits, int& 
     // 128-channel slabs halve the activation traffic per MFMA; with fewer than six of them the 64-channel slabs'
     // finer work items fill the wavefronts more evenly
     for (ncb = (a.N + 127) / 128 >= 6 ? 4 : 2; ncb >= 2; ncb >>= 1) {
-        lds_bytes = (size_t)32 * ncb * pitch + 3 * 4 * 32 * ncb + 16 + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 4096);
+        lds_bytes = (size_t)32 * ncb * pitch + 3 * 4 * 32 * ncb + 16 + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 32 * (WS_CHUNK + 16));
         if (lds_bytes <= (size_t)WS_LDS_MAX) return true;
     }
     return false;
