@@ -259,6 +259,9 @@ __global__ __launch_bounds__(256, IVIT_GEMM_WGS_PER_CU) void gemm_i8_kernel(Gemm
 // Slab rows are stored in LDS so that the accumulator registers of a lane are 16 NCB consecutive channels of one
 // token (see row_of_channel); results go through a small per-wavefront LDS buffer so that every store instruction
 // writes whole output rows.
+#ifndef IVIT_WS_DBG
+#define IVIT_WS_DBG 0
+#endif
 constexpr int WS_THREADS = 512, WS_WAVES = WS_THREADS / 64, WS_CHUNK = 128;
 constexpr int WS_LDS_MAX = 160 * 1024;
 
@@ -291,8 +294,8 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     int32_t* qb_s = reinterpret_cast<int32_t*>(lds + (size_t)NS * pitch);
     int32_t* qc_s = qb_s + NS;
     int32_t* bias_s = qc_s + NS;
-    int32_t* slow_s = bias_s + NS;
-    int8_t* gelu_lut = reinterpret_cast<int8_t*>(slow_s + 4);
+    int64_t* hb_s = reinterpret_cast<int64_t*>(bias_s + NS);   // bias * b + 2^(c-1): the 64-bit addend of the fast requantisation
+    int8_t* gelu_lut = reinterpret_cast<int8_t*>(hb_s + NS);
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int li = lane & 31, lg = lane >> 5;
@@ -361,7 +364,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             if (n0 + n < N && 16 * ck < K) v = *reinterpret_cast<const v4i*>(P.w + (int64_t)(n0 + n) * K + 16 * ck);
             *reinterpret_cast<v4i*>(Wl + row_of_channel<NCB>(n) * pitch + 16 * ck) = v;
         }
-        if (tid < NS) { qb_s[tid] = pb; qc_s[tid] = pc; bias_s[tid] = pbias; }
+        if (tid < NS) { qb_s[tid] = pb; qc_s[tid] = pc; bias_s[tid] = pbias; hb_s[tid] = (int64_t)pbias * pb + (int64_t)(1u << ((pc - 1) & 31)); }
         if (EPI == EPI_GELU && tid < 256) {
             const int32_t I = (int32_t)(int8_t)tid;
             gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
@@ -369,22 +372,12 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         const bool chan_fast = tid >= NS || dyadic_fits32(pb, pc);
         slow_any = __syncthreads_and(chan_fast) == 0;
     }
-#ifndef IVIT_WS_DBG
-#define IVIT_WS_DBG 0
-#endif
     if (!has_work || (IVIT_WS_DBG & 1)) return;
     const bool fast = !slow_any && (EPI != EPI_RESIDUAL || dyadic_fits32(P.res_rq.b, P.res_rq.c));
 
+    // The accumulators hold the bare dot products: the first MFMA group of a token group takes C = 0, and the bias
+    // enters through the 64-bit addend of the requantisation (general path: added explicitly).
     v16i acc[NCB];
-    auto reset_acc = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int cb = 0; cb < NCB; ++cb)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const v4i t = *reinterpret_cast<const v4i*>(&bias_s[16 * NCB * lg + 16 * cb + 4 * q]);
-                acc[cb][4 * q] = t[0]; acc[cb][4 * q + 1] = t[1]; acc[cb][4 * q + 2] = t[2]; acc[cb][4 * q + 3] = t[3];
-            }
-    };
     const int8_t* wl_lane = Wl + li * pitch + 64 * lg;
     int cu = 0;                                         // unit of the group being multiplied
 
@@ -416,9 +409,16 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
                 for (int cb = 0; cb < NCB; ++cb)
                     af[(n + 1) & 1][cb] = *reinterpret_cast<const v4i*>(wp + cb * 32 * pitch + ((n + 1) >> 2) * WS_CHUNK + 16 * ((n + 1) & 3));
             }
+            if (n == 0 && cu == 0) {
+                const v16i zero = {};
 #pragma unroll
-            for (int cb = 0; cb < NCB; ++cb)
-                acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[n & 1][cb], bf[(n >> 2) & 1][n & 3], acc[cb], 0, 0, 0);
+                for (int cb = 0; cb < NCB; ++cb)
+                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[0][cb], bf[0][0], zero, 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int cb = 0; cb < NCB; ++cb)
+                    acc[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[n & 1][cb], bf[(n >> 2) & 1][n & 3], acc[cb], 0, 0, 0);
+            }
         }
     };
 
@@ -429,21 +429,26 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         if (fast) {
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
-                const int nb = n0 + nl + 16 * cb;
                 v4i resv = {0, 0, 0, 0};
                 if (EPI == EPI_RESIDUAL) {              // N % 16 == 0: a 16-channel piece is in or out as a whole
                     const int64_t rt = min<int64_t>(tok, M - 1);
-                    resv = *reinterpret_cast<const v4i*>(P.residual + rt * N + min(nb, N - 16));
+                    resv = *reinterpret_cast<const v4i*>(P.residual + rt * N + min(n0 + nl + 16 * cb, N - 16));
                 }
                 v4i outv;
 #pragma unroll
                 for (int w4 = 0; w4 < 4; ++w4) {
                     const v4i qb = *reinterpret_cast<const v4i*>(&qb_s[nl + 16 * cb + 4 * w4]);
                     const v4i qc = *reinterpret_cast<const v4i*>(&qc_s[nl + 16 * cb + 4 * w4]);
+                    const v4i h01 = *reinterpret_cast<const v4i*>(&hb_s[nl + 16 * cb + 4 * w4]);
+                    const v4i h23 = *reinterpret_cast<const v4i*>(&hb_s[nl + 16 * cb + 4 * w4 + 2]);
                     uint32_t o[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        int32_t v = rnd_shift_fit32(acc[cb][4 * w4 + r], qb[r], qc[r]);
+                        // (dot + bias) * b + 2^(c-1) in one 64-bit multiply-add, then bits c .. c + 31 (rnd_shift_fit32)
+                        const v4i& hh = r < 2 ? h01 : h23;
+                        const int64_t hb = (int64_t)(((uint64_t)(uint32_t)hh[2 * (r & 1) + 1] << 32) | (uint32_t)hh[2 * (r & 1)]);
+                        const int64_t pr = (int64_t)acc[cb][4 * w4 + r] * qb[r] + hb;
+                        int32_t v = (int32_t)__builtin_amdgcn_alignbit((uint32_t)(pr >> 32), (uint32_t)pr, qc[r]);
                         if (EPI == EPI_RESIDUAL) {
                             const int32_t res = (int32_t)(int8_t)((uint32_t)resv[w4] >> (8 * r));
                             v += rnd_shift_fit32(res, P.res_rq.b, P.res_rq.c);
@@ -478,7 +483,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
                     const int64_t tk = cgrp * 32 + t;
                     const int n = n0 + nloc;
                     if (tk < M && n < N) {
-                        const int32_t a32 = st32[t * 32 + c];
+                        const int32_t a32 = st32[t * 32 + c] + bias_s[nloc];
                         int64_t r64 = rnd_shift64(a32, qb_s[nloc], qc_s[nloc]);
                         int32_t v;
                         if (EPI == EPI_RESIDUAL) v = clamp8_64(r64 + rnd_shift64(P.residual[tk * N + n], P.res_rq.b, P.res_rq.c));
@@ -502,7 +507,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             const int row = t * RPI + srow;
             const v4i v = *reinterpret_cast<const v4i*>(stage + row * SP + 16 * piece);
             const int64_t tk = cgrp * 32 + row;
-            if (tk < M && n0 + 16 * piece < N) *reinterpret_cast<v4i*>(P.y + tk * N + n0 + 16 * piece) = v;
+            if (tk < M && n0 + 16 * piece < N && (!(IVIT_WS_DBG & 16) || v[0] == 0x12345678)) *reinterpret_cast<v4i*>(P.y + tk * N + n0 + 16 * piece) = v;
         }
         __builtin_amdgcn_wave_barrier();
     };
@@ -514,16 +519,13 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         else if (acc[0][0] + acc[1][5] + acc[NCB - 1][7] + acc[NCB - 2][9] == 0x12345678) P.y[0] = 1;
         cu = 0;
         cgrp += stride;
-        if (cgrp >= W.groups) return true;
-        reset_acc();
-        return false;
+        return cgrp >= W.groups;
     };
 
 #ifndef IVIT_WS_STAGGER
 #define IVIT_WS_STAGGER 0
 #endif
     if (IVIT_WS_STAGGER > 0 && wv >= 4) __builtin_amdgcn_s_sleep(IVIT_WS_STAGGER);
-    reset_acc();
     for (;;) {
         if (!(IVIT_WS_DBG & 4)) issue(xb);
         consume(xa);
@@ -543,7 +545,7 @@ static bool ws_plan(const LinearArgs& a, int& ncb, int& unit, int& nunits, int& 
     // 128-channel slabs halve the activation traffic per MFMA; with fewer than six of them the 64-channel slabs'
     // finer work items fill the wavefronts more evenly
     for (ncb = (a.N + 127) / 128 >= 6 ? 4 : 2; ncb >= 2; ncb >>= 1) {
-        lds_bytes = (size_t)32 * ncb * pitch + 3 * 4 * 32 * ncb + 16 + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 32 * (WS_CHUNK + 16));
+        lds_bytes = (size_t)32 * ncb * pitch + 5 * 4 * 32 * ncb + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 32 * (WS_CHUNK + 16));
         if (lds_bytes <= (size_t)WS_LDS_MAX) return true;
     }
     return false;
