@@ -92,12 +92,27 @@ __device__ __forceinline__ int32_t shiftgelu_raw(int32_t I, ShiftParams p) {
     return I * (int32_t)dv;
 }
 
+// floor(v / x) for 1 <= x and v < 2^22: the quotient from a single-precision reciprocal is off by at most one,
+// which one multiply and two compares repair (the general unsigned division does the same with more steps).
+__device__ __forceinline__ uint32_t div_small(uint32_t v, uint32_t x) {
+    uint32_t q = (uint32_t)((float)v * __builtin_amdgcn_rcpf((float)x));
+    const int32_t r = (int32_t)(v - q * x);
+    q += (r >= (int32_t)x);
+    q -= (r < 0);
+    return q;
+}
+
 // Tenth iterate of I <- (I + floor(v / I)) >> 1 from I = 2^floor(bitlen(v) / 2) (Eq. 20); 0 for v = 0.
 __device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
     if (v == 0) return 0;
     uint32_t x = 1u << ((32 - __clz(v)) >> 1);
+    if (v < (1u << 22)) {
 #pragma unroll 1
-    for (int it = 0; it < 10; ++it) x = (x + v / x) >> 1;     // x stays >= 1 for v >= 1
+        for (int it = 0; it < 10; ++it) x = (x + div_small(v, x)) >> 1;
+    } else {
+#pragma unroll 1
+        for (int it = 0; it < 10; ++it) x = (x + v / x) >> 1;  // x stays >= 1 for v >= 1
+    }
     return x;
 }
 

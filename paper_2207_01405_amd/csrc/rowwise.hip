@@ -116,19 +116,12 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
         xv[j] = v4i{0, 0, 0, 0};
         if (active && row < rows) xv[j] = *reinterpret_cast<const v4i*>(x + row * C + 16 * cc);
     }
-    int32_t g[16], bt[16];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        v4i gv = {0, 0, 0, 0}, bv = {0, 0, 0, 0};
-        if (active) {
-            gv = *reinterpret_cast<const v4i*>(gamma_q + 16 * cc + 4 * q);
-            bv = *reinterpret_cast<const v4i*>(beta_q + 16 * cc + 4 * q);
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            g[4 * q + e] = gv[e];
-            bt[4 * q + e] = (int32_t)((uint32_t)bv[e] + (uint32_t)half);
-        }
+    // gamma and beta + 2^(c-1) go through LDS: read once per workgroup with coalesced loads instead of 128 bytes per
+    // thread; each thread picks up its 16 channels after the first barrier
+    __shared__ __align__(16) int32_t gb[2 * 1024];
+    for (int i = tid; i < C; i += 256) {
+        gb[i] = gamma_q[i];
+        gb[1024 + i] = (int32_t)((uint32_t)beta_q[i] + (uint32_t)half);
     }
 #pragma unroll
     for (int j = 0; j < J; ++j) {
@@ -153,6 +146,14 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
         stat[r] = make_int2(mean, (int32_t)((1u << f_bits) / sd));
     }
     __syncthreads();
+    int32_t g[16], bt[16];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const v4i gv = *reinterpret_cast<const v4i*>(&gb[(active ? 16 * cc : 0) + 4 * q]);
+        const v4i bv = *reinterpret_cast<const v4i*>(&gb[1024 + (active ? 16 * cc : 0) + 4 * q]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { g[4 * q + e] = gv[e]; bt[4 * q + e] = bv[e]; }
+    }
 #pragma unroll
     for (int j = 0; j < J; ++j) {
         const int64_t row = row0 + j * RP + rgrp;
