@@ -118,7 +118,7 @@ def main():
     gemm = [k for n, k in kinds.items() if n.startswith("gemm")]
     g_ms = sum(k["ms"] for k in gemm); g_ops = sum(k["ops"] for k in gemm); g_n = sum(k["n"] for k in gemm)
     achieved = g_ops / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
-    roofline = dict(bound="mfma", kernel="gemm_i8_kernel (Dense + requant epilogues: QKV, proj, fc1, fc2)",
+    roofline = dict(bound="mfma", kernel="gemm_ws_kernel (weight-stationary Dense + requant epilogues: QKV, proj, fc1, fc2)",
                     achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TOP/s",
                     frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=measured_traffic(args.workload),
                     avg_launch_us=round(g_ms / max(1, g_n) * 1e3, 2), launches_per_step=g_n // max(1, args.trace_steps),
