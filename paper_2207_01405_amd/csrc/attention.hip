@@ -39,7 +39,7 @@ __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d) {
 // FAST: both dyadic pairs are rescales by at most 1 with c <= 31 (32-bit requantisation) and the row sum always
 // exceeds 2^(k_out-1), so that IntDiv is one multiply-high by the pre-shifted reciprocal.
 template <int D, int NKT, bool TAPS, bool BIAS, bool FAST>
-__global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
                                                         int8_t* __restrict__ o, int n_items, int T, int C, int H,
                                                         Dyadic qk, ShiftParams sm, Dyadic pv,
@@ -65,17 +65,37 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
     const int nqt = (T + 15) >> 4;
     const int nfull = T >> 4;                      // key tiles whose 16 keys all exist
 
-    for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    // workgroups of one XCD (block id modulo 8) take consecutive items: the heads of an image share 128-byte lines of
+    // qkv (two 64-byte head slices per line), which then meet in one L2
+    const int G = gridDim.x, xcd = blockIdx.x % 8;
+    const int first = xcd * (G / 8) + min(xcd, G % 8) + blockIdx.x / 8;
+    for (int item = first; item < n_items; item += G) {
         const int b = item / H, h = item % H;
         const int8_t* base = qkv + (int64_t)b * T * 3 * C + h * D;
         __syncthreads();                           // table ready / previous item's readers done
-        for (int c = tid; c < NKT * 16 * DCH; c += 256) {
+        // the query fragment of a tile is requested one tile ahead, the first one together with K and V
+        auto load_q64 = [&](int qt) { return *reinterpret_cast<const v4i*>(base + (int64_t)min(qt * 16 + li, T - 1) * 3 * C + 16 * lg); };
+        auto load_q32 = [&](int qt) { return *reinterpret_cast<const long*>(base + (int64_t)min(qt * 16 + li, T - 1) * 3 * C + 8 * lg); };
+        v4i qn64 = {0, 0, 0, 0};
+        long qn32 = 0;
+        if (D == 64) qn64 = load_q64(wv); else qn32 = load_q32(wv);
+        // all of this thread's K and V pieces are requested before the first one is used: one memory latency per item
+        constexpr int NPC = (NKT * 16 * DCH + 255) / 256;     // 16-byte pieces per thread and operand
+        v4i kreg[NPC], vreg[NPC];
+#pragma unroll
+        for (int it = 0; it < NPC; ++it) {
+            const int c = tid + 256 * it;
+            const int key = min(c / DCH, T - 1), part = c % DCH;
+            kreg[it] = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + C + 16 * part);
+            vreg[it] = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + 2 * C + 16 * part);
+        }
+#pragma unroll
+        for (int it = 0; it < NPC; ++it) {
+            const int c = tid + 256 * it;
+            if (c >= NKT * 16 * DCH) break;
             const int key = c / DCH, part = c % DCH;
-            v4i kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-            if (key < T) {
-                kv = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + C + 16 * part);
-                vv = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + 2 * C + 16 * part);
-            }
+            const v4i kv = key < T ? kreg[it] : v4i{0, 0, 0, 0};
+            const v4i vv = key < T ? vreg[it] : v4i{0, 0, 0, 0};
             *reinterpret_cast<v4i*>(&Ks[key * KROW + 16 * part]) = kv;
             const int pos = vt_pos(key);
 #pragma unroll
@@ -90,11 +110,11 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
         for (int qt = wv; qt < nqt; qt += 4) {
             const int q = qt * 16 + li;            // this lane's query token
             const int qc = min(q, T - 1);
-            const int8_t* qp = base + (int64_t)qc * 3 * C;
             int32_t sc[NKT][4];
             // ---- scores: S^T tile t = K_t (16 keys x D) . Q^T (D x 16 queries)
             if (D == 64) {
-                const v4i qf = *reinterpret_cast<const v4i*>(qp + 16 * lg);
+                const v4i qf = qn64;
+                qn64 = load_q64(qt + 4);
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) {
                     const v4i kf = *reinterpret_cast<const v4i*>(&Ks[(16 * t + li) * KROW + 16 * lg]);
@@ -103,7 +123,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const int8_t* __restrict
                     if ((t & 3) == 3) __builtin_amdgcn_sched_barrier(0);   // at most four K fragments in flight
                 }
             } else {
-                const long qf = *reinterpret_cast<const long*>(qp + 8 * lg);
+                const long qf = qn32;
+                qn32 = load_q32(qt + 4);
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) {
                     const long kf = *reinterpret_cast<const long*>(&Ks[(16 * t + li) * KROW + 8 * lg]);
