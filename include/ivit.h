@@ -189,6 +189,28 @@ int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8
 int ivit_trace_begin(int32_t max_launches);
 int ivit_trace_end(float* ms, int32_t* kind, int64_t* ops, int64_t* bytes, int32_t capacity, int32_t* count);
 
+/* ---- Host helpers: the floating-point side of a quantised model -> the integers this library takes. --------
+ * Pure host code on HOST pointers; nothing is launched.  They realise Sec. 3.1 Eq. 6 (symmetric uniform
+ * quantisation), the dyadic number of Sec. 3.2 and the I_0 of Algorithm 1, with the readings the kernels use
+ * (symmetric integer range, round to nearest with ties away from zero on the host). */
+
+/* q[i] = clamp(round(r[i] / S), -(2^(k-1) - 1), 2^(k-1) - 1) with S = m / (2^(k-1) - 1) (Eq. 6 with the
+ * symmetric range); *scale (nullable) receives S.  n >= 0, m > 0 and finite, 2 <= k <= 8.  NaN inputs give 0.
+ * Errors: NULL, SHAPE (n < 0), PARAM (m, k). */
+int ivit_quantize_symmetric(const float* r, int64_t n, float m, int32_t k, int8_t* q, float* scale);
+
+/* b / 2^c ~ x with 2^(bits-1) <= b < 2^bits where the shift allows it (Sec. 3.2): c = bits - 1 - floor(log2 x),
+ * b = round(x 2^c); c is limited to [1, 46], b to [1, 2^31 - 1].  |b / 2^c - x| <= 2^-(c+1) unless a limit is
+ * hit.  x > 0 and finite, 2 <= bits <= 31.  Errors: NULL, PARAM (x, bits, or x so large that c < 1 would be needed
+ * with b beyond 2^31 - 1). */
+int ivit_dyadic_from_float(double x, int32_t bits, ivit_dyadic* out);
+
+/* ShiftExp / IntDiv parameters for an input scale S (Algorithm 1): i0 = round(1 / S) (at least 1),
+ * n_shift = width - bitlen(i0) so that ShiftExp values stay below 2^width (width <= 16), m_bits and k_out as
+ * given.  Errors: NULL, PARAM (S <= 0 or not finite, width outside [2, 16], i0 needing more than `width` bits,
+ * k_out outside [2, 8], m_bits outside [k_out - 1, 31]). */
+int ivit_shift_params_from_scale(double s, int32_t width, int32_t m_bits, int32_t k_out, ivit_shift_params* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,7 @@ __all__ = [
     "shiftgelu_raw", "shiftgelu", "shiftmax", "ilayernorm", "linear_requant",
     "attention", "encoder_block", "forward", "ShiftParams", "Dyadic",
     "requant_vec", "rnd_shift_vec", "isqrt10_vec", "shiftexp_vec", "TAP_NAMES",
+    "quantize_symmetric", "dyadic_from_float", "shift_params_from_scale",
 ]
 
 
@@ -281,3 +282,48 @@ def forward(x, blocks, dims, final_ln=None):
         fb, cs = int(final_ln["f_bits"]), int(final_ln["c_shift"])
     _L().orc_forward(_ptr(x), _ptr(y), arr, len(blocks), _ptr(g), _ptr(b), fb, cs, _dims(dims))
     return y
+
+
+# ---- host-side conversions (Sec. 3.1 Eq. 6, the dyadic number of Sec. 3.2, I_0 of Algorithm 1), exact rationals
+def quantize_symmetric(r, m, k=8):
+    """clamp(round(r / S)), S = m / (2^(k-1) - 1), ties away from zero; every float is taken as the exact rational it is."""
+    from fractions import Fraction
+    import math
+    qmax = (1 << (k - 1)) - 1
+    S = Fraction(float(np.float32(m))) / qmax
+    out = np.empty(np.shape(r), np.int8)
+    flat = out.reshape(-1)
+    for i, v in enumerate(np.asarray(r, np.float32).reshape(-1)):
+        if not math.isfinite(float(v)):
+            flat[i] = 0 if math.isnan(float(v)) else (qmax if v > 0 else -qmax)
+            continue
+        t = Fraction(float(v)) / S
+        n = math.floor(abs(t) + Fraction(1, 2))
+        flat[i] = max(-qmax, min(qmax, n if t >= 0 else -n))
+    return out, float(S)
+
+
+def dyadic_from_float(x, bits=15):
+    """(b, c) with b = round(x 2^c), c = bits - 1 - floor(log2 x) limited to [1, 46]; a carry into bit `bits` lowers c."""
+    from fractions import Fraction
+    import math
+    X = Fraction(float(x))
+    fl = math.floor(math.log2(X)) if X > 0 else None
+    while Fraction(2) ** fl > X:
+        fl -= 1
+    while Fraction(2) ** (fl + 1) <= X:
+        fl += 1
+    c = max(1, min(46, bits - 1 - fl))
+    rnd = lambda t: math.floor(t + Fraction(1, 2))
+    b = rnd(X * 2 ** c)
+    if b >= 2 ** bits and c > 1:
+        c -= 1
+        b = rnd(X * 2 ** c)
+    return max(1, b), c
+
+
+def shift_params_from_scale(s, width=16, m_bits=31, k_out=8):
+    from fractions import Fraction
+    import math
+    i0 = max(1, math.floor(1 / Fraction(float(s)) + Fraction(1, 2)))
+    return dict(i0=i0, n_shift=width - i0.bit_length(), m_bits=m_bits, k_out=k_out)

@@ -11,11 +11,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libivit.so")
 
 IVIT_OK = 0
+IVIT_ERR_NULL, IVIT_ERR_SHAPE, IVIT_ERR_PARAM, IVIT_ERR_ALIGN, IVIT_ERR_WORKSPACE, IVIT_ERR_HIP = -1, -2, -3, -4, -5, -6
 ERRORS = {"NULL": -1, "SHAPE": -2, "PARAM": -3, "ALIGN": -4, "WORKSPACE": -5, "HIP": -6}
 
 EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftgelu", "ivit_shiftgelu_raw",
            "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward",
-           "ivit_trace_begin", "ivit_trace_end")
+           "ivit_trace_begin", "ivit_trace_end", "ivit_quantize_symmetric", "ivit_dyadic_from_float",
+           "ivit_shift_params_from_scale")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
               7: "shiftgelu"}
@@ -95,6 +97,12 @@ def load():
     lib.ivit_forward.restype = C.c_int
     lib.ivit_forward.argtypes = [_P, _P, _P, C.POINTER(BlockParams), i32, C.POINTER(FinalLN), C.POINTER(Dims), _P,
                                  C.c_size_t]
+    lib.ivit_quantize_symmetric.restype = C.c_int
+    lib.ivit_quantize_symmetric.argtypes = [_P, i64, C.c_float, i32, _P, C.POINTER(C.c_float)]
+    lib.ivit_dyadic_from_float.restype = C.c_int
+    lib.ivit_dyadic_from_float.argtypes = [C.c_double, i32, C.POINTER(Dyadic)]
+    lib.ivit_shift_params_from_scale.restype = C.c_int
+    lib.ivit_shift_params_from_scale.argtypes = [C.c_double, i32, i32, i32, C.POINTER(ShiftParams)]
     lib.ivit_trace_begin.restype = C.c_int; lib.ivit_trace_begin.argtypes = [i32]
     lib.ivit_trace_end.restype = C.c_int
     lib.ivit_trace_end.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), C.POINTER(i64), C.POINTER(i64), i32,
@@ -115,6 +123,32 @@ def ivit_trace_end(capacity):
     _check(load().ivit_trace_end(ms, kind, ops, nbytes, capacity, C.byref(count)), "ivit_trace_end")
     n = min(capacity, count.value)
     return [(ms[i], kind[i], ops[i], nbytes[i]) for i in range(n)]
+
+
+def ivit_quantize_symmetric(r, m, k=8):
+    """Host helper: numpy float32 array -> (int8 array, scale)."""
+    import numpy as np
+    r = np.ascontiguousarray(r, np.float32)
+    q = np.empty(r.shape, np.int8)
+    scale = C.c_float(0)
+    _check(load().ivit_quantize_symmetric(r.ctypes.data, r.size, float(m), int(k), q.ctypes.data, C.byref(scale)),
+           "ivit_quantize_symmetric")
+    return q, scale.value
+
+
+def ivit_dyadic_from_float(x, bits=15):
+    """Host helper: positive real multiplier -> (b, c)."""
+    d = Dyadic(0, 0)
+    _check(load().ivit_dyadic_from_float(float(x), int(bits), C.byref(d)), "ivit_dyadic_from_float")
+    return d.b, d.c
+
+
+def ivit_shift_params_from_scale(s, width=16, m_bits=31, k_out=8):
+    """Host helper: input scale of Shiftmax / ShiftGELU -> dict(i0, n_shift, m_bits, k_out)."""
+    p = ShiftParams(0, 0, 0, 0)
+    _check(load().ivit_shift_params_from_scale(float(s), int(width), int(m_bits), int(k_out), C.byref(p)),
+           "ivit_shift_params_from_scale")
+    return dict(i0=p.i0, n_shift=p.n_shift, m_bits=p.m_bits, k_out=p.k_out)
 
 
 def strerror(status):

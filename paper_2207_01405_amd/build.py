@@ -15,7 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libivit.so")
-SOURCES = ["api.hip", "trace.hip", "rowwise.hip", "gemm_i8.hip", "attention.hip"]
+SOURCES = ["api.hip", "trace.hip", "rowwise.hip", "gemm_i8.hip", "attention.hip", "host_helpers.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions are kept out of every code object of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
