@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--cpu-images", type=int, default=2, help="images the CPU oracle runs for cpu_baseline (0 = skip)")
     ap.add_argument("--rowwise-gib", type=float, default=1.0,
                     help="input + output bytes of the stand-alone I-LayerNorm / Shiftmax bandwidth runs (0 = skip)")
+    ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes to time as well (same weights), e.g. 1,8,16,32,64,128")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for hardware byte counters) and exit")
     args = ap.parse_args()
@@ -95,6 +96,26 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     images_per_s = B * args.steps / dt
+
+    # ---- optional: the same model at other batch sizes (Fig. 5 of the paper sweeps the batch)
+    sweep = None
+    if args.batch_sweep:
+        sweep = []
+        for bs in [int(v) for v in args.batch_sweep.split(",")]:
+            ds = synth.dims_of(cfg, bs)
+            xs = x[: bs * T] if bs <= B else x.repeat((bs + B - 1) // B, 1)[: bs * T].contiguous()
+            ys = torch.empty_like(xs)
+            wss = torch.empty(binding.ivit_workspace_bytes(ds), dtype=torch.uint8, device="cuda")
+            for _ in range(3):
+                binding.ivit_forward(xs, ys, blk_structs, ds, wss, stream=stream)
+            torch.cuda.synchronize()
+            n = max(10, args.steps // 2)
+            ts = time.perf_counter()
+            for _ in range(n):
+                binding.ivit_forward(xs, ys, blk_structs, ds, wss, stream=stream)
+            torch.cuda.synchronize()
+            el = (time.perf_counter() - ts) / n
+            sweep.append(dict(batch=bs, ms_per_step=round(el * 1e3, 4), images_per_s=round(bs / el, 1)))
 
     # ---- per-kernel durations with HIP events, same workload, same process
     launches_per_step = 7 * L
@@ -184,7 +205,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: %d blocks, dim %d, %d heads, %d tokens, MLP %d, batch %d" % (args.workload, L, C, H, T, F, B)},
-        "roofline": roofline, "cpu_baseline": cpu, "rowwise_hbm": rowwise,
+        "roofline": roofline, "cpu_baseline": cpu, "rowwise_hbm": rowwise, "batch_sweep": sweep,
         "ms_per_step_traced": round(traced_ms_per_step, 4), "kernels": kernels,
         "int8_tops_whole_step": round((24.0 * B * T * C * C + 4.0 * B * H * T * T * (C // H)) * L / (ms_per_step * 1e-3) / 1e12, 1),
     }

@@ -180,7 +180,7 @@ int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8
  * library makes (from any entry point, on any stream) is bracketed by two HIP events recorded on the stream
  * of the launch.  ivit_trace_end waits for the recorded events, then fills the HOST arrays (each nullable,
  * `capacity` entries) with, per launch in launch order: elapsed milliseconds, kind (1 I-LayerNorm, 2 Dense,
- * 3 Dense + residual, 4 Dense + ShiftGELU, 5 attention, 6 Shiftmax, 7 ShiftGELU), algorithmic integer
+ * 3 Dense + residual, 4 Dense + ShiftGELU, 5 attention, 6 Shiftmax, 7 ShiftGELU, 8 token assembly), algorithmic integer
  * operations (2 per int8 multiply-accumulate; 0 for row-wise kernels) and algorithmic HBM bytes (each
  * operand read once, each result written once); *count receives the number of launches seen.
  * One trace at a time per process, not thread-safe; launches beyond max_launches make ivit_trace_end
@@ -188,6 +188,52 @@ int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8
  * Errors: SHAPE (max_launches < 1), PARAM (begin while active / end while inactive), HIP. */
 int ivit_trace_begin(int32_t max_launches);
 int ivit_trace_end(float* ms, int32_t* kind, int64_t* ops, int64_t* bytes, int32_t capacity, int32_t* count);
+
+/* ---- Embedding layer and classifier head around the encoder (Sec. 3.1; Sec. 3.2 states that the embedding
+ * layer's Conv follows the same dyadic pipeline as Dense).  A 16 x 16 stride-16 Conv on an image is a Dense
+ * layer on flattened patches; cutting the image into patches is a permutation and is left to the caller. ------ */
+
+/* Token assembly: for image b, tokens[b, 0, :] comes from the class token, tokens[b, 1 + p, :] from
+ * patch_tok[b, p, :] (the output of the patch Dense, ivit_linear_requant); each is rescaled by tok_rq and the
+ * position embedding pos[t, :] rescaled by pos_rq is added (the two-scale addition rule of the residuals):
+ *   tokens = clamp8(round(src * b_t, c_t) + round(pos * b_p, c_p)).
+ * patch_tok int8 [B * P, C], cls int8 [C], pos int8 [P + 1, C], tokens int8 [B * (P + 1), C]; all 16-byte
+ * aligned; C % 16 == 0, P >= 0, B >= 0.  Errors: NULL, SHAPE, PARAM (dyadic pairs), ALIGN, HIP. */
+int ivit_embed_tokens(void* stream, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos,
+                      ivit_dyadic tok_rq, ivit_dyadic pos_rq, int8_t* tokens, int32_t B, int32_t P, int32_t C);
+
+/* Classifier head: logits[b, :] = requant(tokens[b * T, :] . w^T + bias; rq_b, rq_c), a Dense layer on the class
+ * token (row 0) of every image.  tokens int8 [B * T, C], w int8 [N, C], bias int32 [N] (nullable), rq int32 [N],
+ * logits int8 [B, N]; C % 16 == 0; tokens, w, logits 16-byte aligned.  Errors as ivit_linear_requant. */
+int ivit_classifier_head(void* stream, const int8_t* tokens, int32_t T, const int8_t* w, const int32_t* bias,
+                         const int32_t* rq_b, const int32_t* rq_c, int8_t* logits, int32_t B, int32_t N, int32_t C);
+
+/* Parameters of the embedding layer and the head (host struct, device pointers). */
+typedef struct {
+    const int8_t* w_patch;        /* [C, patch_dim]                                                 */
+    const int32_t* bias_patch;    /* [C], nullable                                                  */
+    const int32_t* patch_rq_b;    /* [C]                                                            */
+    const int32_t* patch_rq_c;    /* [C]                                                            */
+    int32_t patch_dim;            /* bytes of a flattened patch, multiple of 16                     */
+    const int8_t* cls;            /* [C]                                                            */
+    const int8_t* pos;            /* [T, C]                                                         */
+    ivit_dyadic tok_rq, pos_rq;
+    const int8_t* w_head;         /* [n_classes, C]                                                 */
+    const int32_t* bias_head;     /* [n_classes], nullable                                          */
+    const int32_t* head_rq_b;     /* [n_classes]                                                    */
+    const int32_t* head_rq_c;     /* [n_classes]                                                    */
+    int32_t n_classes;
+} ivit_image_params;
+
+/* Workspace of ivit_forward_image: that of ivit_forward plus the patch tokens and two token buffers. */
+size_t ivit_image_workspace_bytes(const ivit_dims* d);
+
+/* Patches in, logits out: patch Dense, token assembly, the block stack, the final I-LayerNorm (required here) and
+ * the head.  patches int8 [B * (T - 1), patch_dim], logits int8 [B, n_classes]; d->T counts the class token.
+ * Errors: those of the parts; WORKSPACE if smaller than ivit_image_workspace_bytes(d). */
+int ivit_forward_image(void* stream, const int8_t* patches, int8_t* logits, const ivit_image_params* ip,
+                       const ivit_block_params* blocks, int32_t n_blocks, const ivit_final_ln* final_ln,
+                       const ivit_dims* d, void* workspace, size_t workspace_bytes);
 
 /* ---- Host helpers: the floating-point side of a quantised model -> the integers this library takes. --------
  * Pure host code on HOST pointers; nothing is launched.  They realise Sec. 3.1 Eq. 6 (symmetric uniform

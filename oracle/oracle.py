@@ -20,6 +20,7 @@ __all__ = [
     "attention", "encoder_block", "forward", "ShiftParams", "Dyadic",
     "requant_vec", "rnd_shift_vec", "isqrt10_vec", "shiftexp_vec", "TAP_NAMES",
     "quantize_symmetric", "dyadic_from_float", "shift_params_from_scale",
+    "embed_tokens", "classifier_head", "forward_image",
 ]
 
 
@@ -327,3 +328,34 @@ def shift_params_from_scale(s, width=16, m_bits=31, k_out=8):
     import math
     i0 = max(1, math.floor(1 / Fraction(float(s)) + Fraction(1, 2)))
     return dict(i0=i0, n_shift=width - i0.bit_length(), m_bits=m_bits, k_out=k_out)
+
+
+# ---- embedding layer and classifier head (Sec. 3.1; Sec. 3.2: the embedding Conv follows the dyadic pipeline)
+def embed_tokens(patch_tok, cls, pos, tok_rq, pos_rq, B):
+    """tokens[b, 0] from the class token, tokens[b, 1 + p] from patch_tok[b, p]; each rescaled by tok_rq, plus the
+    position embedding rescaled by pos_rq, clamped to int8 (the two-scale addition of the residuals)."""
+    patch_tok = _arr(patch_tok, np.int8); cls = _arr(cls, np.int8); pos = _arr(pos, np.int8)
+    T, Cc = pos.shape
+    P = T - 1
+    src = np.empty((B, T, Cc), np.int64)
+    src[:, 0, :] = cls.astype(np.int64)
+    src[:, 1:, :] = patch_tok.reshape(B, P, Cc).astype(np.int64)
+    bt, ct = tok_rq
+    bp, cp = pos_rq
+    a = (src * int(bt) + (1 << (int(ct) - 1))) >> int(ct)                      # numpy >> on int64 is arithmetic
+    q = (pos.astype(np.int64)[None] * int(bp) + (1 << (int(cp) - 1))) >> int(cp)
+    return np.clip(a + q, -127, 127).astype(np.int8).reshape(B * T, Cc)
+
+
+def classifier_head(tokens, T, w, bias, rq_b, rq_c):
+    """Dense + requant on row 0 of every image."""
+    tokens = _arr(tokens, np.int8)
+    return linear_requant(np.ascontiguousarray(tokens[::T]), w, bias, rq_b, rq_c)
+
+
+def forward_image(patches, image, blocks, d, final_ln):
+    B, T = d["B"], d["T"]
+    tok = linear_requant(patches, image["w_patch"], image["bias_patch"], image["patch_rq_b"], image["patch_rq_c"])
+    x = embed_tokens(tok, image["cls"], image["pos"], image["tok_rq"], image["pos_rq"], B)
+    y = forward(x, blocks, d, final_ln=final_ln)
+    return classifier_head(y, T, image["w_head"], image["bias_head"], image["head_rq_b"], image["head_rq_c"])

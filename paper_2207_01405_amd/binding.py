@@ -17,10 +17,11 @@ ERRORS = {"NULL": -1, "SHAPE": -2, "PARAM": -3, "ALIGN": -4, "WORKSPACE": -5, "H
 EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftgelu", "ivit_shiftgelu_raw",
            "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward",
            "ivit_trace_begin", "ivit_trace_end", "ivit_quantize_symmetric", "ivit_dyadic_from_float",
-           "ivit_shift_params_from_scale")
+           "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
+           "ivit_forward_image")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
-              7: "shiftgelu"}
+              7: "shiftgelu", 8: "embed_tokens"}
 
 
 class ShiftParams(C.Structure):
@@ -56,6 +57,12 @@ TAP_NAMES = ("u", "qkv", "scores", "probs", "o", "xhat", "v", "h")
 
 class DebugTaps(C.Structure):
     _fields_ = [(n, _P) for n in TAP_NAMES]
+
+
+class ImageParams(C.Structure):
+    _fields_ = [("w_patch", _P), ("bias_patch", _P), ("patch_rq_b", _P), ("patch_rq_c", _P), ("patch_dim", C.c_int32),
+                ("cls", _P), ("pos", _P), ("tok_rq", Dyadic), ("pos_rq", Dyadic),
+                ("w_head", _P), ("bias_head", _P), ("head_rq_b", _P), ("head_rq_c", _P), ("n_classes", C.c_int32)]
 
 
 class FinalLN(C.Structure):
@@ -97,6 +104,14 @@ def load():
     lib.ivit_forward.restype = C.c_int
     lib.ivit_forward.argtypes = [_P, _P, _P, C.POINTER(BlockParams), i32, C.POINTER(FinalLN), C.POINTER(Dims), _P,
                                  C.c_size_t]
+    lib.ivit_embed_tokens.restype = C.c_int
+    lib.ivit_embed_tokens.argtypes = [_P, _P, _P, _P, Dyadic, Dyadic, _P, i32, i32, i32]
+    lib.ivit_classifier_head.restype = C.c_int
+    lib.ivit_classifier_head.argtypes = [_P, _P, i32, _P, _P, _P, _P, _P, i32, i32, i32]
+    lib.ivit_image_workspace_bytes.restype = C.c_size_t; lib.ivit_image_workspace_bytes.argtypes = [C.POINTER(Dims)]
+    lib.ivit_forward_image.restype = C.c_int
+    lib.ivit_forward_image.argtypes = [_P, _P, _P, C.POINTER(ImageParams), C.POINTER(BlockParams), i32, C.POINTER(FinalLN),
+                                       C.POINTER(Dims), _P, C.c_size_t]
     lib.ivit_quantize_symmetric.restype = C.c_int
     lib.ivit_quantize_symmetric.argtypes = [_P, i64, C.c_float, i32, _P, C.POINTER(C.c_float)]
     lib.ivit_dyadic_from_float.restype = C.c_int
@@ -288,3 +303,41 @@ def ivit_forward(x, y, blocks, d, workspace, final_ln=None, stream=None):
                              _ptr(workspace), workspace.numel() * workspace.element_size())
     _check(st, "ivit_forward")
     return y
+
+
+def ivit_embed_tokens(patch_tok, cls, pos, tok_rq, pos_rq, tokens, B, P, stream=None):
+    Cc = tokens.shape[-1]
+    _check(load().ivit_embed_tokens(_stream(stream), _ptr(patch_tok), _ptr(cls), _ptr(pos), dyadic(tok_rq), dyadic(pos_rq),
+                                    _ptr(tokens), int(B), int(P), int(Cc)), "ivit_embed_tokens")
+    return tokens
+
+
+def ivit_classifier_head(tokens, T, w, bias, rq_b, rq_c, logits, stream=None):
+    B, N = logits.shape
+    _check(load().ivit_classifier_head(_stream(stream), _ptr(tokens), int(T), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c),
+                                       _ptr(logits), int(B), int(N), int(w.shape[1])), "ivit_classifier_head")
+    return logits
+
+
+def ivit_image_workspace_bytes(d):
+    return load().ivit_image_workspace_bytes(C.byref(dims(d)))
+
+
+def image_params(p):
+    """ImageParams struct from a dict whose tensor entries are torch CUDA tensors (kept alive by the caller)."""
+    ip = ImageParams()
+    for k in ("w_patch", "bias_patch", "patch_rq_b", "patch_rq_c", "cls", "pos", "w_head", "bias_head", "head_rq_b", "head_rq_c"):
+        setattr(ip, k, _ptr(p.get(k)))
+    ip.patch_dim = int(p["w_patch"].shape[1]); ip.n_classes = int(p["w_head"].shape[0])
+    ip.tok_rq = dyadic(p["tok_rq"]); ip.pos_rq = dyadic(p["pos_rq"])
+    return ip
+
+
+def ivit_forward_image(patches, logits, image, blocks, d, workspace, final_ln, stream=None):
+    arr = (BlockParams * max(1, len(blocks)))(*[block_params(p) for p in blocks])
+    fl = FinalLN(_ptr(final_ln["gamma"]), _ptr(final_ln["beta"]), int(final_ln["f_bits"]), int(final_ln["c_shift"]))
+    ip = image if isinstance(image, ImageParams) else image_params(image)
+    st = load().ivit_forward_image(_stream(stream), _ptr(patches), _ptr(logits), C.byref(ip), arr, len(blocks), C.byref(fl),
+                                   C.byref(dims(d)), _ptr(workspace), workspace.numel() * workspace.element_size())
+    _check(st, "ivit_forward_image")
+    return logits

@@ -286,4 +286,61 @@ int ivit_forward(void* stream, const int8_t* x, int8_t* y, const ivit_block_para
     return IVIT_OK;
 }
 
+int ivit_embed_tokens(void* stream, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos,
+                      ivit_dyadic tok_rq, ivit_dyadic pos_rq, int8_t* tokens, int32_t B, int32_t P, int32_t C) {
+    if (B < 0 || P < 0 || C < 16 || (C & 15)) return IVIT_ERR_SHAPE;
+    if (B > 0 && (!cls || !pos || !tokens || (P > 0 && !patch_tok))) return IVIT_ERR_NULL;
+    int st;
+    if ((st = check_dyadic(tok_rq)) != IVIT_OK || (st = check_dyadic(pos_rq)) != IVIT_OK) return st;
+    if (!aligned(patch_tok, 16) || !aligned(cls, 16) || !aligned(pos, 16) || !aligned(tokens, 16)) return IVIT_ERR_ALIGN;
+    return hip_status(ivit::launch_embed_tokens(static_cast<hipStream_t>(stream), patch_tok, cls, pos, dy(tok_rq),
+                                                dy(pos_rq), tokens, B, P, C));
+}
+
+int ivit_classifier_head(void* stream, const int8_t* tokens, int32_t T, const int8_t* w, const int32_t* bias,
+                         const int32_t* rq_b, const int32_t* rq_c, int8_t* logits, int32_t B, int32_t N, int32_t C) {
+    if (B < 0 || T < 1 || N < 1 || C < 16 || C > 65536 || (C & 15)) return IVIT_ERR_SHAPE;
+    if (B > 0 && (!tokens || !logits)) return IVIT_ERR_NULL;
+    if (!w || !rq_b || !rq_c) return IVIT_ERR_NULL;
+    if (!aligned(tokens, 16) || !aligned(w, 16) || !aligned(logits, 16)) return IVIT_ERR_ALIGN;
+    if (!aligned(rq_b, 4) || !aligned(rq_c, 4) || (bias && !aligned(bias, 4))) return IVIT_ERR_ALIGN;
+    ivit::LinearArgs a{};
+    a.x = tokens; a.w = w; a.bias = bias; a.rq_b = rq_b; a.rq_c = rq_c; a.residual = nullptr;
+    a.res_rq = Dyadic{1, 1}; a.gelu = false;
+    a.y = logits; a.M = B; a.N = N; a.K = C; a.ldx = (int64_t)T * C;
+    return hip_status(ivit::launch_linear(static_cast<hipStream_t>(stream), a));
+}
+
+size_t ivit_image_workspace_bytes(const ivit_dims* d) {
+    if (!d || check_dims(d) != IVIT_OK) return 0;
+    const size_t act = ((size_t)d->B * d->T * d->C + 255) / 256 * 256;
+    return ivit_workspace_bytes(d) + 3 * act;
+}
+
+int ivit_forward_image(void* stream, const int8_t* patches, int8_t* logits, const ivit_image_params* ip,
+                       const ivit_block_params* blocks, int32_t n_blocks, const ivit_final_ln* final_ln,
+                       const ivit_dims* d, void* workspace, size_t workspace_bytes) {
+    if (!ip || !d || !final_ln) return IVIT_ERR_NULL;
+    int st;
+    if ((st = check_dims(d)) != IVIT_OK) return st;
+    if (ip->patch_dim < 16 || (ip->patch_dim & 15) || ip->n_classes < 1) return IVIT_ERR_SHAPE;
+    if (d->B > 0 && (!patches || !logits)) return IVIT_ERR_NULL;
+    if (!workspace || workspace_bytes < ivit_image_workspace_bytes(d)) return IVIT_ERR_WORKSPACE;
+    if (!aligned(workspace, 256)) return IVIT_ERR_ALIGN;
+    const size_t act = ((size_t)d->B * d->T * d->C + 255) / 256 * 256;
+    int8_t* base = static_cast<int8_t*>(workspace);
+    int8_t* patch_tok = base;
+    int8_t* tok_in = base + act;
+    int8_t* tok_out = base + 2 * act;
+    void* inner = base + 3 * act;
+    const int P = d->T - 1;
+    st = ivit_linear_requant(stream, patches, ip->w_patch, ip->bias_patch, ip->patch_rq_b, ip->patch_rq_c, nullptr,
+                             ivit_dyadic{1, 1}, nullptr, ivit_dyadic{1, 1}, patch_tok, (int64_t)d->B * P, d->C, ip->patch_dim);
+    if (st != IVIT_OK && !(P == 0 && st == IVIT_ERR_SHAPE)) return st;
+    if ((st = ivit_embed_tokens(stream, patch_tok, ip->cls, ip->pos, ip->tok_rq, ip->pos_rq, tok_in, d->B, P, d->C)) != IVIT_OK) return st;
+    if ((st = ivit_forward(stream, tok_in, tok_out, blocks, n_blocks, final_ln, d, inner, workspace_bytes - 3 * act)) != IVIT_OK) return st;
+    return ivit_classifier_head(stream, tok_out, d->T, ip->w_head, ip->bias_head, ip->head_rq_b, ip->head_rq_c, logits,
+                                d->B, ip->n_classes, d->C);
+}
+
 }  // extern "C"

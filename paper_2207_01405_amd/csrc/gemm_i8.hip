@@ -40,6 +40,7 @@ struct GemmParams {
     const int8_t* x; const int8_t* w; const int32_t* bias; const int32_t* rq_b; const int32_t* rq_c;
     const int8_t* residual; Dyadic res_rq; ShiftParams gelu_p; Dyadic gelu_rq;
     int8_t* y; int64_t M; int N; int K; int tiles_n; int64_t tiles; int64_t per_xcd;
+    int64_t ldx;                         // bytes between rows of x
 };
 
 // LDS row (0..63) of channel offset n (0..63) inside a wavefront's 64-channel slab.  MFMA tile ct, row
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(256, IVIT_GEMM_WGS_PER_CU) void gemm_i8_kernel(Gemm
         const int r = ld_row + RPP * p;
         const int64_t xm = min<int64_t>(m0 + r, M - 1);
         const int wnn = min(n0 + r, N - 1);
-        xg[p] = P.x + xm * K + ld_k;
+        xg[p] = P.x + xm * P.ldx + ld_k;
         wg[p] = P.w + (int64_t)wnn * K + ld_k;
         xs_off[p] = r * LROW + ld_k;
         ws_off[p] = ((r & 64) + slab_row(r & 63)) * LROW + ld_k;
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         const int start = lu * (UNIT * WS_CHUNK) + 16 * p8;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int8_t* row = P.x + min<int64_t>(g0 + 8 * t, M - 1) * K;
+            const int8_t* row = P.x + min<int64_t>(g0 + 8 * t, M - 1) * P.ldx;
 #pragma unroll
             for (int c = 0; c < UNIT; ++c) {
                 const int off = start + c * WS_CHUNK;
@@ -570,7 +571,7 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     GemmParams P;
     P.x = a.x; P.w = a.w; P.bias = a.bias; P.rq_b = a.rq_b; P.rq_c = a.rq_c;
     P.residual = a.residual; P.res_rq = a.res_rq; P.gelu_p = a.gelu_p; P.gelu_rq = a.gelu_rq;
-    P.y = a.y; P.M = a.M; P.N = a.N; P.K = a.K;
+    P.y = a.y; P.M = a.M; P.N = a.N; P.K = a.K; P.ldx = a.ldx ? a.ldx : a.K;
     P.tiles_n = (a.N + BN - 1) / BN;
     const int64_t tiles_m = (a.M + BM - 1) / BM;
     P.tiles = tiles_m * P.tiles_n;

@@ -22,8 +22,11 @@ struct LinearArgs {
     const int8_t* residual; Dyadic res_rq;
     bool gelu; ShiftParams gelu_p; Dyadic gelu_rq;
     int8_t* y; int64_t M; int N; int K;
+    int64_t ldx;                         // bytes between rows of x; 0 means K (dense rows)
 };
 hipError_t launch_linear(hipStream_t s, const LinearArgs& a);
+hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos, Dyadic tok_rq,
+                               Dyadic pos_rq, int8_t* tokens, int B, int P, int C);
 
 struct AttentionArgs {
     const int8_t* qkv; const int8_t* rel_bias; int8_t* o;
@@ -38,7 +41,7 @@ int num_cus();
 
 // Kinds of launches reported by the trace (ivit_trace_end); values are part of the C ABI.
 enum LaunchKind { KIND_ILAYERNORM = 1, KIND_GEMM = 2, KIND_GEMM_RESIDUAL = 3, KIND_GEMM_GELU = 4,
-                  KIND_ATTENTION = 5, KIND_SHIFTMAX = 6, KIND_SHIFTGELU = 7 };
+                  KIND_ATTENTION = 5, KIND_SHIFTMAX = 6, KIND_SHIFTGELU = 7, KIND_EMBED = 8 };
 
 // Brackets one kernel launch with two HIP events on its stream while a trace is active; otherwise a no-op.
 // ops = algorithmic integer operations (2 per int8 multiply-accumulate), bytes = algorithmic HBM bytes.

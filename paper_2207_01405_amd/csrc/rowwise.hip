@@ -444,4 +444,54 @@ hipError_t launch_shiftgelu(hipStream_t s, const int8_t* x, int8_t* y8, int16_t*
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------------------------------------
+// Token assembly of the embedding layer: class token, patch tokens and position embedding, each int8 at its own
+// scale, brought to the token scale by two dyadic rescales and added (the residual-add rule of Eq. 1-2 applied to
+// the embedding sum).  One thread per 16 bytes of an output row; C % 16 == 0.
+template <bool FAST>
+__global__ __launch_bounds__(256) void embed_tokens_kernel(const int8_t* __restrict__ patch_tok, const int8_t* __restrict__ cls,
+                                                           const int8_t* __restrict__ pos, Dyadic tq, Dyadic pq,
+                                                           int8_t* __restrict__ tokens, int64_t n_pieces, int P, int C) {
+    typedef int v4i __attribute__((ext_vector_type(4)));
+    const int cpr = C >> 4, T = P + 1;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_pieces; i += (int64_t)gridDim.x * 256) {
+        const int64_t row = i / cpr;
+        const int cc = (int)(i - row * cpr);
+        const int64_t b = row / T;
+        const int t = (int)(row - b * T);
+        const int8_t* src = t == 0 ? cls + 16 * cc : patch_tok + ((b * P + (t - 1)) * C + 16 * cc);
+        const v4i sv = *reinterpret_cast<const v4i*>(src);
+        const v4i pv = *reinterpret_cast<const v4i*>(pos + (int64_t)t * C + 16 * cc);
+        v4i ov;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int32_t a = (int32_t)(int8_t)((uint32_t)sv[d] >> (8 * e));
+                const int32_t q = (int32_t)(int8_t)((uint32_t)pv[d] >> (8 * e));
+                const int32_t v = FAST ? clamp8(rnd_shift_fit32(a, tq.b, tq.c) + rnd_shift_fit32(q, pq.b, pq.c))
+                                       : clamp8_64(rnd_shift64(a, tq.b, tq.c) + rnd_shift64(q, pq.b, pq.c));
+                w |= ((uint32_t)v & 0xffu) << (8 * e);
+            }
+            ov[d] = (int)w;
+        }
+        *reinterpret_cast<v4i*>(tokens + row * C + 16 * cc) = ov;
+    }
+}
+
+hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos, Dyadic tok_rq,
+                               Dyadic pos_rq, int8_t* tokens, int B, int P, int C) {
+    const int64_t n_pieces = (int64_t)B * (P + 1) * (C >> 4);
+    if (n_pieces == 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((n_pieces + 255) / 256, (int64_t)num_cus() * 32);
+    auto fits = [](Dyadic d) { return d.c >= 1 && d.c <= 31 && d.b >= 1 && (uint32_t)d.b <= (1u << d.c); };
+    TraceScope trace(s, KIND_EMBED, 0, (int64_t)B * (2 * P + 1) * C + (int64_t)(P + 2) * C);
+    if (fits(tok_rq) && fits(pos_rq))
+        hipLaunchKernelGGL(embed_tokens_kernel<true>, dim3(grid), dim3(256), 0, s, patch_tok, cls, pos, tok_rq, pos_rq, tokens, n_pieces, P, C);
+    else
+        hipLaunchKernelGGL(embed_tokens_kernel<false>, dim3(grid), dim3(256), 0, s, patch_tok, cls, pos, tok_rq, pos_rq, tokens, n_pieces, P, C);
+    return hipGetLastError();
+}
+
 }  // namespace ivit

@@ -24,6 +24,9 @@ CONFIGS = {
     "c4_swin_t": dict(B=8192, T=49,  C=96,  H=3,  F=384,  L=1,  seed=4, act="normal",   i0="fixed", rel_bias=True),
 }
 
+for _name, _cfg in CONFIGS.items():
+    _cfg["name"] = _name
+
 K_OUT = 8        # output bit width of Shiftmax / ShiftGELU's IntDiv
 ACC_BITS = 16    # "16-bit accumulation width": I_0 << N stays below 2^16
 M_BITS = 31      # M of IntDiv
@@ -144,6 +147,33 @@ def make_final_ln(cfg):
     rng = np.random.default_rng([cfg["seed"], 3000])
     g, b = _ln(rng, cfg["C"])
     return dict(gamma=g, beta=b, f_bits=LN_F_BITS, c_shift=LN_C_SHIFT)
+
+
+PATCH_DIM = {"c0_tiny": 48, "c1_deit_t": 768, "c2_deit_s": 768, "c3_vit_b": 768}     # 4x4x3 for the tiny case, else 16x16x3
+N_CLASSES = {"c0_tiny": 10, "c1_deit_t": 1000, "c2_deit_s": 1000, "c3_vit_b": 1000}
+
+
+def make_image_params(cfg):
+    """Embedding layer (patch Dense, class token, position embedding) and classifier head of the workload `cfg`."""
+    rng = np.random.default_rng([cfg["seed"], 6000])
+    T, C = cfg["T"], cfg["C"]
+    kp, ncls = PATCH_DIM[cfg["name"]], N_CLASSES[cfg["name"]]
+    p = {}
+    (p["w_patch"], p["bias_patch"], p["patch_rq_b"], p["patch_rq_c"]), _ = _dense(rng, C, kp, 32.0, 32.0, LN_OUT_SCALE)
+    p["cls"] = np.clip(np.rint(rng.standard_normal(C) * 32.0), -127, 127).astype(np.int8)
+    p["pos"] = np.clip(np.rint(rng.standard_normal((T, C)) * 24.0), -127, 127).astype(np.int8)
+    p["tok_rq"] = (int(rng.integers(2 ** 14, 2 ** 15)), 15)
+    p["pos_rq"] = (int(rng.integers(2 ** 13, 2 ** 14)), 15)
+    (p["w_head"], p["bias_head"], p["head_rq_b"], p["head_rq_c"]), _ = _dense(rng, ncls, C, 1.0 / LN_OUT_SCALE, 32.0, LN_OUT_SCALE)
+    return p
+
+
+def make_patches(cfg, n_images=None):
+    """int8 [B * (T - 1), patch_dim]: flattened image patches (cutting an image into patches is a permutation)."""
+    rng = np.random.default_rng([cfg["seed"], 7000])
+    B = cfg["B"] if n_images is None else n_images
+    z = rng.standard_normal((max(B, cfg["B"]) * (cfg["T"] - 1), PATCH_DIM[cfg["name"]])) * 32.0
+    return np.clip(np.rint(z), -127, 127).astype(np.int8)[: B * (cfg["T"] - 1)]
 
 
 def make_model(cfg, n_blocks=None):

@@ -1,0 +1,71 @@
+"""Writes tests/golden/forward_checksums.json: SHA-256 (first 64 bits) of the oracle's final int8 output of every image of
+the full-size synthetic configurations c1-c4 (the whole block stack of each), from oracle/ and the seeded generators
+only.  The GPU parity tests hash the library's output of the full batch the same way and compare.
+
+    python tests/golden/make_checksums.py [--configs c1_deit_t,c2_deit_s,c3_vit_b,c4_swin_t] [--workers 8]
+
+Images are independent through the encoder, so each worker runs the oracle on a slice of the batch.
+"""
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+from multiprocessing import Pool
+
+ROOT = os.path.dirname(os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+sys.path.insert(0, ROOT)
+OUT = os.path.join(os.path.dirname(os.path.abspath(__file__)), "forward_checksums.json")
+
+
+GROUP = {"c4_swin_t": 64}       # windows per digest: the 64 windows of one image; other configurations: one image
+
+
+def digest_rows(y, T, group=1):
+    """One digest (first 64 bits of SHA-256, hex) per `group` consecutive images: y is int8 [n * T, C]."""
+    import numpy as np
+    y = np.ascontiguousarray(y)
+    step = T * group
+    return [hashlib.sha256(y[i:i + step].tobytes()).hexdigest()[:16] for i in range(0, y.shape[0], step)]
+
+
+def work(job):
+    name, lo, hi = job
+    import oracle
+    from paper_2207_01405_amd import synth
+    cfg = synth.CONFIGS[name]
+    blocks = synth.make_model(cfg)
+    x = synth.make_input(cfg)
+    T = cfg["T"]
+    y = oracle.forward(x[lo * T:hi * T], blocks, synth.dims_of(cfg, hi - lo))
+    return name, lo, digest_rows(y, T, GROUP.get(name, 1))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="c1_deit_t,c2_deit_s,c3_vit_b,c4_swin_t")
+    ap.add_argument("--workers", type=int, default=8)
+    args = ap.parse_args()
+    import oracle
+    from paper_2207_01405_amd import synth
+    oracle.build()
+    res = json.load(open(OUT)) if os.path.exists(OUT) else {}
+    for name in args.configs.split(","):
+        cfg = synth.CONFIGS[name]
+        B = cfg["B"]
+        g = GROUP.get(name, 1)
+        per = g * max(1, min(64, B // g // (4 * args.workers)))
+        jobs = [(name, lo, min(B, lo + per)) for lo in range(0, B, per)]
+        t0 = time.time()
+        dig = [None] * (B // g)
+        with Pool(args.workers) as pool:
+            for _, lo, d in pool.imap_unordered(work, jobs):
+                dig[lo // g:lo // g + len(d)] = d
+        res[name] = dict(images=B, tokens=cfg["T"], dim=cfg["C"], blocks=cfg["L"], images_per_digest=g, sha256_64=dig)
+        print("%s: %d images in %.0f s" % (name, B, time.time() - t0), flush=True)
+        json.dump(res, open(OUT, "w"), indent=0)
+
+
+if __name__ == "__main__":
+    main()

@@ -318,3 +318,62 @@ def test_forward_full_size_sampled_images(ivit, name, images):
     for i, w in zip(images, want):
         assert_same(got[i * T:(i + 1) * T], w, "%s image %d" % (name, i))
     assert np.abs(got.astype(np.int32)).mean() > 3
+
+
+@pytest.mark.parametrize("name", ["c1_deit_t", "c2_deit_s", "c3_vit_b", "c4_swin_t"])
+def test_forward_full_size_every_image_against_stored_oracle_digests(ivit, name):
+    """Every image of the full batch: digests of the oracle's outputs, written by tests/golden/make_checksums.py
+    (which calls only the oracle and the seeded generators), against digests of the library's output."""
+    import hashlib
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "forward_checksums.json")
+    ref = json.load(open(path))[name]
+    cfg = synth.CONFIGS[name]
+    assert (ref["images"], ref["tokens"], ref["dim"], ref["blocks"]) == (cfg["B"], cfg["T"], cfg["C"], cfg["L"])
+    got = np.ascontiguousarray(_gpu_forward(ivit, cfg, synth.make_input(cfg), synth.make_model(cfg), cfg["B"]))
+    step = cfg["T"] * ref["images_per_digest"]
+    dig = [hashlib.sha256(got[i:i + step].tobytes()).hexdigest()[:16] for i in range(0, got.shape[0], step)]
+    bad = [i for i, (a, b) in enumerate(zip(dig, ref["sha256_64"])) if a != b]
+    assert len(dig) == len(ref["sha256_64"]) and not bad, "%s: %d of %d digests differ, first %s" % (name, len(bad), len(dig), bad[:5])
+
+
+# ------------------------------------------------------------------ embedding layer, head, patches -> logits
+@pytest.mark.parametrize("B,P,C,tq,pq", [(0, 4, 64, (2 ** 14, 14), (2 ** 13, 14)), (3, 0, 16, (23457, 15), (9001, 15)),
+                                         (5, 196, 384, (23457, 15), (9001, 15)), (2, 64, 64, (2 ** 31 - 1, 33), (7, 1)),
+                                         (129, 48, 96, (30000, 15), (3, 2))])
+def test_embed_tokens(ivit, B, P, C, tq, pq):
+    rng = np.random.default_rng(B + P + C)
+    tok = rng.integers(-127, 128, size=(B * P, C)).astype(np.int8)
+    cls = rng.integers(-127, 128, size=C).astype(np.int8)
+    pos = rng.integers(-127, 128, size=(P + 1, C)).astype(np.int8)
+    out = empty((B * (P + 1), C))
+    ivit.ivit_embed_tokens(dev(tok), dev(cls), dev(pos), tq, pq, out, B, P)
+    assert_same(host(out), orc.embed_tokens(tok, cls, pos, tq, pq, B), "embed_tokens")
+
+
+@pytest.mark.parametrize("B,T,C,N", [(1, 1, 16, 1), (7, 65, 64, 10), (128, 197, 384, 1000), (33, 197, 768, 1000), (256, 5, 192, 21)])
+def test_classifier_head(ivit, B, T, C, N):
+    x = synth.make_rows(B + N, B * T, C, "normal", 32.0)
+    w, bias, rq_b, rq_c = synth.make_linear(N + 3, N, C)
+    out = empty((B, N))
+    ivit.ivit_classifier_head(dev(x), T, dev(w), dev(bias), dev(rq_b), dev(rq_c), out)
+    assert_same(host(out), orc.classifier_head(x, T, w, bias, rq_b, rq_c), "classifier head")
+
+
+@pytest.mark.parametrize("name,B,L", [("c0_tiny", 1, 1), ("c0_tiny", 5, 1), ("c1_deit_t", 3, 2), ("c2_deit_s", 2, 12)])
+def test_forward_image_patches_to_logits(ivit, name, B, L):
+    import torch
+    cfg = synth.CONFIGS[name]
+    d = synth.dims_of(cfg, B)
+    blocks = synth.make_model(cfg, L)
+    image = synth.make_image_params(cfg)
+    fl = synth.make_final_ln(cfg)
+    patches = synth.make_patches(cfg, B)
+    want = orc.forward_image(patches, image, blocks, d, fl)
+    ws = torch.empty(ivit.ivit_image_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    logits = empty(want.shape)
+    img_d = ivit.to_device(image); fl_d = ivit.to_device(fl); blk_d = [ivit.to_device(p) for p in blocks]
+    ivit.ivit_forward_image(dev(patches), logits, img_d, blk_d, d, ws, fl_d)
+    assert_same(host(logits), want, "logits %s" % name)
+    assert np.abs(want.astype(np.int32)).mean() > 2 and len(np.unique(want.argmax(axis=1))) >= min(B, 2) - 1

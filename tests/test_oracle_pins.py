@@ -474,3 +474,45 @@ def test_synthetic_workloads_are_not_degenerate():
             t = taps[k].astype(np.int64)
             assert t.std() > 4.0 and (np.abs(t) == 127).mean() < 0.08, (name, k)
         assert taps["probs"].max() > 8
+
+
+# ------------------------------------------------------------------ embedding layer and head
+def test_embed_tokens_special_cases():
+    """With the identity rescale (2^14, 14) and a zero position embedding the tokens are the sources; a zero source
+    leaves the rescaled position embedding; sums saturate symmetrically."""
+    rng = np.random.default_rng(11)
+    B, P, C = 3, 5, 16
+    tok = rng.integers(-127, 128, size=(B * P, C)).astype(np.int8)
+    cls = rng.integers(-127, 128, size=C).astype(np.int8)
+    pos = rng.integers(-127, 128, size=(P + 1, C)).astype(np.int8)
+    ident = (2 ** 14, 14)
+    out = orc.embed_tokens(tok, cls, np.zeros_like(pos), ident, ident, B).reshape(B, P + 1, C)
+    assert np.array_equal(out[:, 0], np.broadcast_to(cls, (B, C))) and np.array_equal(out[:, 1:].reshape(B * P, C), tok)
+    half = (2 ** 13, 14)                                  # x 0.5, ties up
+    out = orc.embed_tokens(np.zeros_like(tok), np.zeros_like(cls), pos, ident, half, B).reshape(B, P + 1, C)
+    want = np.floor(pos.astype(np.float64) / 2 + 0.5).astype(np.int8)
+    assert np.array_equal(out[1], want)
+    big = orc.embed_tokens(np.full_like(tok, 127), np.full_like(cls, -127), np.sign(pos + 0.5).astype(np.int8) * 127, ident, ident, B)
+    assert big.max() == 127 and big.min() == -127
+    # brute force with exact rationals on a few entries
+    from fractions import Fraction
+    import math
+    tq, pq = (23457, 15), (9001, 15)
+    out = orc.embed_tokens(tok, cls, pos, tq, pq, B).reshape(B, P + 1, C)
+    for (b, t, c) in ((0, 0, 0), (1, 3, 7), (2, 5, 15), (2, 0, 9)):
+        s = int(cls[c]) if t == 0 else int(tok[b * P + t - 1, c])
+        v = math.floor(Fraction(s * tq[0], 2 ** tq[1]) + Fraction(1, 2)) + math.floor(Fraction(int(pos[t, c]) * pq[0], 2 ** pq[1]) + Fraction(1, 2))
+        assert out[b, t, c] == max(-127, min(127, v))
+
+
+def test_classifier_head_is_dense_on_class_rows():
+    rng = np.random.default_rng(12)
+    B, T, C, N = 4, 7, 32, 10
+    x = rng.integers(-127, 128, size=(B * T, C)).astype(np.int8)
+    w = rng.integers(-127, 128, size=(N, C)).astype(np.int8)
+    bias = rng.integers(-1000, 1000, size=N).astype(np.int32)
+    rq_b = rng.integers(2 ** 14, 2 ** 15, size=N).astype(np.int32); rq_c = np.full(N, 22, np.int32)
+    got = orc.classifier_head(x, T, w, bias, rq_b, rq_c)
+    acc = x[::T].astype(np.int64) @ w.astype(np.int64).T + bias
+    want = np.clip((acc * rq_b + (1 << 21)) >> 22, -127, 127).astype(np.int8)
+    assert np.array_equal(got, want)
