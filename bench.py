@@ -50,6 +50,7 @@ def main():
     ap.add_argument("--rowwise-gib", type=float, default=1.0,
                     help="input + output bytes of the stand-alone I-LayerNorm / Shiftmax bandwidth runs (0 = skip)")
     ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes to time as well (same weights), e.g. 1,8,16,32,64,128")
+    ap.add_argument("--no-image-path", action="store_true", help="skip the patches-to-logits timing (embedding + blocks + head)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for hardware byte counters) and exit")
     args = ap.parse_args()
@@ -116,6 +117,27 @@ def main():
             torch.cuda.synchronize()
             el = (time.perf_counter() - ts) / n
             sweep.append(dict(batch=bs, ms_per_step=round(el * 1e3, 4), images_per_s=round(bs / el, 1)))
+
+    # ---- patches in, logits out (embedding layer + block stack + final I-LayerNorm + head): the end-to-end figure
+    image_path = None
+    if not args.no_image_path and cfg["name"] in synth.PATCH_DIM:
+        img = binding.to_device(synth.make_image_params(cfg)); fl = binding.to_device(synth.make_final_ln(cfg))
+        patches = torch.from_numpy(synth.make_patches(cfg)).cuda()
+        logits = torch.empty((B, synth.N_CLASSES[cfg["name"]]), dtype=torch.int8, device="cuda")
+        wsi = torch.empty(binding.ivit_image_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+        ip = binding.image_params(img)
+        for _ in range(3):
+            binding.ivit_forward_image(patches, logits, ip, blk_structs, d, wsi, fl, stream=stream)
+        torch.cuda.synchronize()
+        n = max(10, args.steps // 2)
+        ts = time.perf_counter()
+        for _ in range(n):
+            binding.ivit_forward_image(patches, logits, ip, blk_structs, d, wsi, fl, stream=stream)
+        torch.cuda.synchronize()
+        el = (time.perf_counter() - ts) / n
+        image_path = dict(ms_per_step=round(el * 1e3, 4), images_per_s=round(B / el, 1), patch_dim=synth.PATCH_DIM[cfg["name"]],
+                          n_classes=synth.N_CLASSES[cfg["name"]])
+        del patches, logits, wsi
 
     # ---- per-kernel durations with HIP events, same workload, same process
     launches_per_step = 7 * L
@@ -205,7 +227,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8", "data": "synthetic",
         "config": {"workload": "%s: %d blocks, dim %d, %d heads, %d tokens, MLP %d, batch %d" % (args.workload, L, C, H, T, F, B)},
-        "roofline": roofline, "cpu_baseline": cpu, "rowwise_hbm": rowwise, "batch_sweep": sweep,
+        "roofline": roofline, "cpu_baseline": cpu, "rowwise_hbm": rowwise, "batch_sweep": sweep, "image_path": image_path,
         "ms_per_step_traced": round(traced_ms_per_step, 4), "kernels": kernels,
         "int8_tops_whole_step": round((24.0 * B * T * C * C + 4.0 * B * H * T * T * (C // H)) * L / (ms_per_step * 1e-3) / 1e12, 1),
     }

@@ -377,3 +377,34 @@ def test_forward_image_patches_to_logits(ivit, name, B, L):
     ivit.ivit_forward_image(dev(patches), logits, img_d, blk_d, d, ws, fl_d)
     assert_same(host(logits), want, "logits %s" % name)
     assert np.abs(want.astype(np.int32)).mean() > 2 and len(np.unique(want.argmax(axis=1))) >= min(B, 2) - 1
+
+
+def test_forward_under_hip_graph_capture_replays_identically(ivit):
+    """ivit_forward allocates nothing and records no memset, so it can be captured; every replay, with eager work
+    and synchronisations in between, must reproduce the eager (oracle-checked) result."""
+    import torch
+    cfg = synth.CONFIGS["c1_deit_t"]
+    B = 4
+    d = synth.dims_of(cfg, B)
+    blocks = synth.make_model(cfg, 3)
+    x = synth.make_input(cfg)[: B * cfg["T"]]
+    want = orc.forward(x, blocks, d)
+    blk_d = [ivit.to_device(p) for p in blocks]
+    structs = [ivit.block_params(p) for p in blk_d]
+    xd = dev(x); y_eager = empty(x.shape); y_graph = empty(x.shape)
+    ws = torch.empty(ivit.ivit_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        ivit.ivit_forward(xd, y_eager, structs, d, ws, stream=s.cuda_stream)
+    torch.cuda.synchronize()
+    assert_same(host(y_eager), want, "eager forward")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=s):
+        ivit.ivit_forward(xd, y_graph, structs, d, ws, stream=torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        y_graph.zero_()
+        ws.random_(0, 255)                           # eager work between replays; the workspace holds no state
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert_same(host(y_graph), want, "graph replay %d" % rep)
