@@ -25,6 +25,11 @@ namespace ivit {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
+#ifndef IVIT_ATT_WAVES
+#define IVIT_ATT_WAVES 4
+#endif
+constexpr int ATT_WAVES = IVIT_ATT_WAVES, ATT_THREADS = 64 * ATT_WAVES;   // wavefronts per workgroup
+
 // position of key k inside a V^T row: 64-key chunk c = k / 64; inside it lane group g = (k % 16) / 4 owns
 // 16 consecutive bytes ordered by tile (k / 16) % 4, then k % 4
 __device__ __forceinline__ int vt_pos(int k) {
@@ -39,7 +44,7 @@ __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d) {
 // FAST: both dyadic pairs are rescales by at most 1 with c <= 31 (32-bit requantisation) and the row sum always
 // exceeds 2^(k_out-1), so that IntDiv is one multiply-high by the pre-shifted reciprocal.
 template <int D, int NKT, bool TAPS, bool BIAS, bool FAST>
-__global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restrict__ qkv,
+__global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
                                                         int8_t* __restrict__ o, int n_items, int T, int C, int H,
                                                         Dyadic qk, ShiftParams sm, Dyadic pv,
@@ -55,10 +60,10 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restr
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
-    for (int i = tid; i < 512; i += 256) lut[i] = (uint16_t)shiftexp(-i, sm.i0, sm.n_shift);
+    for (int i = tid; i < 512; i += ATT_THREADS) lut[i] = (uint16_t)shiftexp(-i, sm.i0, sm.n_shift);
     // keys beyond the 16-key tiles but inside the last 64-key chunk multiply probabilities that are zero;
     // clear them once so that no uninitialised LDS is ever read
-    for (int i = tid; i < D * VROW / 4; i += 256) reinterpret_cast<uint32_t*>(Vt)[i] = 0u;
+    for (int i = tid; i < D * VROW / 4; i += ATT_THREADS) reinterpret_cast<uint32_t*>(Vt)[i] = 0u;
 
     const int sh = sm.m_bits - (sm.k_out - 1);
     const uint32_t top = (1u << (sm.k_out - 1)) - 1u;
@@ -80,18 +85,18 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restr
         long qn32 = 0;
         if (D == 64) qn64 = load_q64(wv); else qn32 = load_q32(wv);
         // all of this thread's K and V pieces are requested before the first one is used: one memory latency per item
-        constexpr int NPC = (NKT * 16 * DCH + 255) / 256;     // 16-byte pieces per thread and operand
+        constexpr int NPC = (NKT * 16 * DCH + ATT_THREADS - 1) / ATT_THREADS;     // 16-byte pieces per thread and operand
         v4i kreg[NPC], vreg[NPC];
 #pragma unroll
         for (int it = 0; it < NPC; ++it) {
-            const int c = tid + 256 * it;
+            const int c = tid + ATT_THREADS * it;
             const int key = min(c / DCH, T - 1), part = c % DCH;
             kreg[it] = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + C + 16 * part);
             vreg[it] = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + 2 * C + 16 * part);
         }
 #pragma unroll
         for (int it = 0; it < NPC; ++it) {
-            const int c = tid + 256 * it;
+            const int c = tid + ATT_THREADS * it;
             if (c >= NKT * 16 * DCH) break;
             const int key = c / DCH, part = c % DCH;
             const v4i kv = key < T ? kreg[it] : v4i{0, 0, 0, 0};
@@ -107,14 +112,14 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restr
         }
         __syncthreads();
 
-        for (int qt = wv; qt < nqt; qt += 4) {
+        for (int qt = wv; qt < nqt; qt += ATT_WAVES) {
             const int q = qt * 16 + li;            // this lane's query token
             const int qc = min(q, T - 1);
             int32_t sc[NKT][4];
             // ---- scores: S^T tile t = K_t (16 keys x D) . Q^T (D x 16 queries)
             if (D == 64) {
                 const v4i qf = qn64;
-                qn64 = load_q64(qt + 4);
+                qn64 = load_q64(qt + ATT_WAVES);
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) {
                     const v4i kf = *reinterpret_cast<const v4i*>(&Ks[(16 * t + li) * KROW + 16 * lg]);
@@ -124,7 +129,7 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restr
                 }
             } else {
                 const long qf = qn32;
-                qn32 = load_q32(qt + 4);
+                qn32 = load_q32(qt + ATT_WAVES);
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) {
                     const long kf = *reinterpret_cast<const long*>(&Ks[(16 * t + li) * KROW + 8 * lg]);
@@ -146,9 +151,10 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restr
                         int32_t a = requant8<FAST>(sc[t][r], qk);
                         if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
                         if (BIAS) a += brow[key];
-                        mx = max(mx, a);
                         sc[t][r] = a;
                     }
+                    mx = max(mx, max(sc[t][0], sc[t][1]));       // two three-operand maxima per tile
+                    mx = max(mx, max(sc[t][2], sc[t][3]));
                 } else {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
@@ -166,14 +172,16 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restr
             }
             mx = max(mx, __shfl_xor(mx, 16, kWave));
             mx = max(mx, __shfl_xor(mx, 32, kWave));
-            // ---- ShiftExp by table, row sum
+            // ---- ShiftExp by table, row sum.  The byte offset 2 (max - a) of the table entry is one 24-bit multiply-add.
             int32_t sum = 0;
+            const int32_t mx2 = 2 * mx;
+            const char* lut_b = reinterpret_cast<const char*>(lut);
 #pragma unroll
             for (int t = 0; t < NKT; ++t) {
                 if (t < nfull) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int32_t e = (int32_t)lut[mx - sc[t][r]];
+                        const int32_t e = (int32_t)*reinterpret_cast<const uint16_t*>(lut_b + (__mul24(sc[t][r], -2) + mx2));
                         sc[t][r] = e;
                         sum += e;
                     }
@@ -200,14 +208,22 @@ __global__ __launch_bounds__(256, 3) void attention_kernel(const int8_t* __restr
             for (int t = 0; t < NKT; ++t)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const uint32_t p = FAST ? min(__umulhi(inv_hi, (uint32_t)sc[t][r]), top)
-                                            : min((inv * (uint32_t)sc[t][r]) >> sh, top);
                     if (TAPS) {
+                        const uint32_t p = FAST ? min(__umulhi(inv_hi, (uint32_t)sc[t][r]), top)
+                                                : min((inv * (uint32_t)sc[t][r]) >> sh, top);
                         const int key = 16 * t + 4 * lg + r;
                         if (tap_p && q < T && key < T) tap_p[tap_row + key] = (int8_t)p;
+                        pk[t] |= p << (8 * r);
+                    } else {
+                        // IntDiv gives at most 2^(k_out-1), which fits a byte: clamp the four of a word together below
+                        const uint32_t p = FAST ? __umulhi(inv_hi, (uint32_t)sc[t][r]) : (inv * (uint32_t)sc[t][r]) >> sh;
+                        pk[t] |= p << (8 * r);
                     }
-                    pk[t] |= p << (8 * r);
                 }
+            if (!TAPS) {
+#pragma unroll
+                for (int t = 0; t < NKT; ++t) pk[t] -= (pk[t] >> (sm.k_out - 1)) & 0x01010101u;   // bytewise min(p, 2^(k_out-1) - 1)
+            }
             // ---- O^T = V^T P^T : "A" = V^T rows (features), "B" = packed probabilities (keys x queries)
             v4i oacc[ND];
 #pragma unroll
@@ -244,7 +260,7 @@ template <int D, int NKT>
 static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, bool taps, bool bias, bool fast) {
     const int n_items = a.B * a.H;
 #define IVIT_ATT(TAPS_, BIAS_, FAST_)                                                                              \
-    hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, FAST_>), dim3(grid), dim3(256), 0, s, a.qkv, a.rel_bias, \
+    hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, FAST_>), dim3(grid), dim3(ATT_THREADS), 0, s, a.qkv, a.rel_bias, \
                        a.o, n_items, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs)
     // the production path is <no taps, fast>; everything else shares one fully general instantiation per bias flag
     if (!taps && fast) { if (bias) IVIT_ATT(false, true, true); else IVIT_ATT(false, false, true); }

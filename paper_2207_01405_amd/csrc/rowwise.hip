@@ -180,12 +180,12 @@ hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamm
                              int8_t* y, int64_t rows, int C, int f_bits, int c_shift) {
     if (rows == 0) return hipSuccess;
     if ((C & 15) == 0 && C >= 64 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma_q | (uintptr_t)beta_q) & 15) == 0) {
-        // rows per workgroup = (256 / (C / 16)) * J: fewer passes J for small inputs, so that every CU still holds
-        // several workgroups whose load, statistics and store phases overlap
+        // rows per workgroup = (256 / (C / 16)) * J
         const int rp = 256 / (C >> 4);
-        const int64_t enough = (int64_t)num_cus() * 8;
-        int J = 8;
-        while (J > 1 && (rows + rp * J - 1) / (rp * J) < enough) J >>= 1;
+        // the smallest J whose workgroups are all resident at once (8 per CU): one round of the three dependent phases
+        const int64_t resident = (int64_t)num_cus() * 8;
+        int J = 1;
+        while (J < 8 && (rows + rp * J - 1) / (rp * J) > resident) J <<= 1;
         const int64_t grid = (rows + rp * J - 1) / (rp * J);
         if (grid <= 0x7fffffffLL) {
             TraceScope trace(s, KIND_ILAYERNORM, 0, 2 * rows * C + 8LL * C);
