@@ -260,9 +260,6 @@ __global__ __launch_bounds__(256, IVIT_GEMM_WGS_PER_CU) void gemm_i8_kernel(Gemm
 // Slab rows are stored in LDS so that the accumulator registers of a lane are 16 NCB consecutive channels of one
 // token (see row_of_channel); results go through a small per-wavefront LDS buffer so that every store instruction
 // writes whole output rows.
-#ifndef IVIT_WS_DBG
-#define IVIT_WS_DBG 0
-#endif
 constexpr int WS_THREADS = 512, WS_WAVES = WS_THREADS / 64, WS_CHUNK = 128;
 constexpr int WS_LDS_MAX = 160 * 1024;
 
@@ -359,12 +356,12 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             if (P.bias) pbias = P.bias[n0 + tid];
         }
         const int cpr = nunits * UNIT * (WS_CHUNK / 16);   // 16-byte pieces per padded row
-        for (int idx = tid; idx < NS * cpr; idx += WS_THREADS) {
-            const int n = idx / cpr, ck = idx - n * cpr;
-            v4i v = {0, 0, 0, 0};
-            if (n0 + n < N && 16 * ck < K) v = *reinterpret_cast<const v4i*>(P.w + (int64_t)(n0 + n) * K + 16 * ck);
-            *reinterpret_cast<v4i*>(Wl + row_of_channel<NCB>(n) * pitch + 16 * ck) = v;
-        }
+        for (int n = tid >> 3; n < NS; n += WS_THREADS / 8)            // 8 lanes read a 128-byte line of a weight row
+            for (int ck = tid & 7; ck < cpr; ck += 8) {
+                v4i v = {0, 0, 0, 0};
+                if (n0 + n < N && 16 * ck < K) v = *reinterpret_cast<const v4i*>(P.w + (int64_t)(n0 + n) * K + 16 * ck);
+                *reinterpret_cast<v4i*>(Wl + row_of_channel<NCB>(n) * pitch + 16 * ck) = v;
+            }
         if (tid < NS) { qb_s[tid] = pb; qc_s[tid] = pc; bias_s[tid] = pbias; hb_s[tid] = (int64_t)pbias * pb + (int64_t)(1u << ((pc - 1) & 31)); }
         if (EPI == EPI_GELU && tid < 256) {
             const int32_t I = (int32_t)(int8_t)tid;
@@ -373,7 +370,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         const bool chan_fast = tid >= NS || dyadic_fits32(pb, pc);
         slow_any = __syncthreads_and(chan_fast) == 0;
     }
-    if (!has_work || (IVIT_WS_DBG & 1)) return;
+    if (!has_work) return;
     const bool fast = !slow_any && (EPI != EPI_RESIDUAL || dyadic_fits32(P.res_rq.b, P.res_rq.c));
 
     // The accumulators hold the bare dot products: the first MFMA group of a token group takes C = 0, and the bias
@@ -405,7 +402,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
 #pragma unroll
         for (int n = 0; n < 4 * UNIT; ++n) {
             if ((n & 3) == 0 && (n >> 2) + 1 < UNIT) stage_chunk(buf[(n >> 2) + 1], bf[((n >> 2) + 1) & 1]);
-            if (n + 1 < 4 * UNIT && !((IVIT_WS_DBG & 8) && n > 0)) {
+            if (n + 1 < 4 * UNIT) {
 #pragma unroll
                 for (int cb = 0; cb < NCB; ++cb)
                     af[(n + 1) & 1][cb] = *reinterpret_cast<const v4i*>(wp + cb * 32 * pitch + ((n + 1) >> 2) * WS_CHUNK + 16 * ((n + 1) & 3));
@@ -508,7 +505,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             const int row = t * RPI + srow;
             const v4i v = *reinterpret_cast<const v4i*>(stage + row * SP + 16 * piece);
             const int64_t tk = cgrp * 32 + row;
-            if (tk < M && n0 + 16 * piece < N && (!(IVIT_WS_DBG & 16) || v[0] == 0x12345678)) *reinterpret_cast<v4i*>(P.y + tk * N + n0 + 16 * piece) = v;
+            if (tk < M && n0 + 16 * piece < N) *reinterpret_cast<v4i*>(P.y + tk * N + n0 + 16 * piece) = v;
         }
         __builtin_amdgcn_wave_barrier();
     };
@@ -516,22 +513,17 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     // true when the wavefront has finished its last group
     auto end_of_unit = [&]() __attribute__((always_inline)) -> bool {
         if (++cu < nunits) return false;
-        if (!(IVIT_WS_DBG & 2)) finish();
-        else if (acc[0][0] + acc[1][5] + acc[NCB - 1][7] + acc[NCB - 2][9] == 0x12345678) P.y[0] = 1;
+        finish();
         cu = 0;
         cgrp += stride;
         return cgrp >= W.groups;
     };
 
-#ifndef IVIT_WS_STAGGER
-#define IVIT_WS_STAGGER 0
-#endif
-    if (IVIT_WS_STAGGER > 0 && wv >= 4) __builtin_amdgcn_s_sleep(IVIT_WS_STAGGER);
     for (;;) {
-        if (!(IVIT_WS_DBG & 4)) issue(xb);
+        issue(xb);
         consume(xa);
         if (EVEN) ++cu; else if (end_of_unit()) return;
-        if (!(IVIT_WS_DBG & 4)) issue(xa);
+        issue(xa);
         consume(xb);
         if (end_of_unit()) return;
     }
