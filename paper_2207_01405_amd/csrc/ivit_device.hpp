@@ -81,6 +81,19 @@ __device__ __forceinline__ uint32_t recip_pow2(uint32_t sum, int32_t m_bits) {
     return (1u << m_bits) / sum;              // m_bits <= 31
 }
 
+// The same value for 2^9 <= sum < 2^24 (a row sum of ShiftExp values: the maximum's term alone is I_0 << N): the
+// quotient is below 2^23, a single-precision estimate of it is off by at most one, and the remainder
+// 2^M - q sum, exact in 32-bit wrap-around arithmetic, repairs it.  Other sums take the general division.
+__device__ __forceinline__ uint32_t recip_pow2_small(uint32_t sum, int32_t m_bits) {
+    if (sum < (1u << 9) || sum >= (1u << 24)) return (1u << m_bits) / sum;
+    const uint32_t num = 1u << m_bits;
+    uint32_t q = (uint32_t)((float)num * __builtin_amdgcn_rcpf((float)sum));
+    const int32_t r = (int32_t)(num - q * sum);
+    q += (r >= (int32_t)sum);
+    q -= (r < 0);
+    return q;
+}
+
 // ShiftGELU on one int8 value (Algorithm 2, maximum taken per element as max(I_p, 0)):
 // returns I * I_div, |result| <= 127 * 2^(k_out-1).
 __device__ __forceinline__ int32_t shiftgelu_raw(int32_t I, ShiftParams p) {

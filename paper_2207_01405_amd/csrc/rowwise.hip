@@ -285,7 +285,9 @@ __device__ __forceinline__ uint32_t group_allreduce(uint32_t v, OP op) {
     return v;
 }
 
-template <int LPR, int UNR, bool FAST>
+// DUP: the number of leading bytes of a row's last lane that belong to its neighbour, 16 ceil(cols / 16) - cols,
+// when it is one of the instantiated values (0; 11 for 197 columns; 15 for 49 and 65), else -1 = taken at run time.
+template <int LPR, int UNR, bool FAST, int DUP>
 __global__ __launch_bounds__(256) void shiftmax_vec_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y,
                                                            int64_t rows, int cols, int ld, ShiftParams p) {
     __shared__ uint16_t lut[256];                    // ShiftExp(-delta), delta = max - value in [0, 255]
@@ -296,7 +298,7 @@ __global__ __launch_bounds__(256) void shiftmax_vec_kernel(const int8_t* __restr
     const int off = min(16 * j, cols - 16);          // lanes past the end repeat the last one and store nothing
     const bool owner = j < nl;
     const bool last = j == nl - 1;
-    const int dup = 16 * (nl - 1) - (cols - 16);     // leading bytes of the last lane that its neighbour owns
+    const int dup = DUP >= 0 ? DUP : 16 * (nl - 1) - (cols - 16);   // leading bytes of the last lane that its neighbour owns
     const int sh = p.m_bits - (p.k_out - 1);
     const int64_t slot = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
     const int64_t nslots = (int64_t)gridDim.x * (256 / LPR);
@@ -330,11 +332,11 @@ __global__ __launch_bounds__(256) void shiftmax_vec_kernel(const int8_t* __restr
                 const uint32_t delta = mrep - xf[k >> 2];                // bytewise, no borrows: every byte <= max
                 e[k] = lut[(delta >> (8 * (k & 3))) & 0xffu];
                 full += e[k];
-                if (k >= dup) tail += e[k];                              // uniform condition
+                if (k >= dup) tail += e[k];                              // known at compile time when DUP >= 0
             }
             const uint32_t mine = owner ? (last ? tail : full) : 0u;
             const uint32_t sum = group_allreduce<LPR>(mine, uadd);
-            const uint32_t inv = (1u << p.m_bits) / sum;
+            const uint32_t inv = recip_pow2_small(sum, p.m_bits);
             uint32_t out[4];
             const uint32_t invs = FAST ? inv << (32 - sh) : inv;
 #pragma unroll
@@ -364,8 +366,15 @@ static void launch_shiftmax_vec(hipStream_t s, const int8_t* x, int8_t* y, int64
     // inv << (32 - sh) must fit 32 bits: inv <= 2^M / (I_0 << N) < 2^sh needs I_0 << N > 2^(k_out - 1); sh >= 1
     const int sh = p.m_bits - (p.k_out - 1);
     const bool fast = sh >= 1 && ((int64_t)p.i0 << p.n_shift) > ((int64_t)1 << (p.k_out - 1));
-    if (fast) hipLaunchKernelGGL((shiftmax_vec_kernel<LPR, UNR, true>), dim3(grid), dim3(256), 0, s, x, y, rows, cols, ld, p);
-    else hipLaunchKernelGGL((shiftmax_vec_kernel<LPR, UNR, false>), dim3(grid), dim3(256), 0, s, x, y, rows, cols, ld, p);
+    const int dup = 16 * ((cols + 15) / 16) - cols;
+    const dim3 g(grid), b(256);
+#define IVIT_SM(FAST_, DUP_) hipLaunchKernelGGL((shiftmax_vec_kernel<LPR, UNR, FAST_, DUP_>), g, b, 0, s, x, y, rows, cols, ld, p)
+    if (fast) {
+        if (dup == 0) IVIT_SM(true, 0); else if (dup == 11) IVIT_SM(true, 11); else if (dup == 15) IVIT_SM(true, 15); else IVIT_SM(true, -1);
+    } else {
+        IVIT_SM(false, -1);
+    }
+#undef IVIT_SM
 }
 
 hipError_t launch_shiftmax(hipStream_t s, const int8_t* x, const int8_t* bias, int H, int T, int8_t* y,
