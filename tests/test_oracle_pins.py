@@ -516,3 +516,17 @@ def test_classifier_head_is_dense_on_class_rows():
     acc = x[::T].astype(np.int64) @ w.astype(np.int64).T + bias
     want = np.clip((acc * rq_b + (1 << 21)) >> 22, -127, 127).astype(np.int8)
     assert np.array_equal(got, want)
+
+
+def test_oracle_runs_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The oracle's no-overflow and shift-range claims, checked by running it (saturated operands, K = 3072, 31-bit
+    multipliers, shifts up to 46, one-hot rows) in a build where signed overflow, bad shifts and bad accesses abort."""
+    import os
+    import subprocess
+    src = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "oracle", "sanitize_check.c")
+    exe = str(tmp_path / "orc_check")
+    subprocess.run(["gcc", "-O1", "-g", "-std=c11", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", src, "-o", exe],
+                   check=True, capture_output=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0")
+    r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
+    assert r.returncode == 0 and "sanitize_check: ok" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
