@@ -81,6 +81,9 @@ typedef struct {
     ivit_shift_params gelu;  ivit_dyadic gelu_rq;                            /* ShiftGELU and its int8 rescale */
     const int8_t  *w_fc2;   const int32_t *bias_fc2 /*nullable*/, *fc2_rq_b, *fc2_rq_c;      /* [C, F], [C] */
     ivit_dyadic    res2_rq;               /* rescale of the residual Xhat before the second add (Eq. 2)  */
+    const int8_t  *attn_mask;             /* nullable, [n_mask, T, T]: mask of shifted-window attention, see
+                                             ivit_attention_masked                                       */
+    int32_t        n_mask;                /* window b uses attn_mask[b % n_mask]; ignored without a mask  */
 } ivit_block_params;
 
 /* Optional device buffers that receive every intermediate int8 tensor of a block
@@ -175,6 +178,17 @@ int ivit_forward(void* stream, const int8_t* x, int8_t* y, const ivit_block_para
 int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8_t* o, const ivit_dims* d,
                    ivit_dyadic qk_rq, ivit_shift_params softmax, ivit_dyadic pv_rq,
                    int8_t* tap_scores, int8_t* tap_probs);
+
+/* The same with the additive mask of shifted-window attention (the windowed models of Table 1 add -100 to the
+ * logits of token pairs that the cyclic shift brought together): where mask[b % n_mask][i][j] != 0 the score
+ * of query i and key j of window b gets -100 * I_0 (that is -100 at the integer scale of the logits, I_0 being
+ * softmax.i0) after the rescale and the bias and before the row maximum; ShiftExp of such a value is 0 unless
+ * I_0 is tiny, so those keys drop out of the row.  mask int8 [n_mask, T, T], shared by the heads, nullable
+ * (then n_mask is ignored); the windows of an image are consecutive values of b.  Errors as ivit_attention,
+ * SHAPE if a mask is given with n_mask < 1. */
+int ivit_attention_masked(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
+                          int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq, ivit_shift_params softmax,
+                          ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs);
 
 /* Per-launch timing for benchmarks.  Between ivit_trace_begin and ivit_trace_end every kernel launch the
  * library makes (from any entry point, on any stream) is bracketed by two HIP events recorded on the stream

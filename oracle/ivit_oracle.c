@@ -122,24 +122,33 @@ void orc_shiftgelu(const int8_t* x, int8_t* y, int64_t n, orc_shift_params p, or
  * bias[(r / T) % H][r % T][:] before the maximum is subtracted.  The result is
  * limited to 2^(k_out-1)-1 so that it is a signed k_out-bit value (Eq. 16 can
  * reach 2^(k_out-1) exactly when one element carries the whole row). */
+/* The additive mask of shifted-window attention: where mask_row[j] != 0 the logit gets -100 (in real units, the
+ * value the windowed models add), i.e. -100 * I_0 at the integer scale, before the maximum is taken.  ShiftExp of
+ * such a value is 0 unless I_0 is tiny, so masked keys drop out of the row; nothing else is special-cased. */
+#define ORC_MASK_LOGIT 100
+
+static void shiftmax_row(const int8_t* xr, const int8_t* br, const int8_t* mr, int8_t* yr, int32_t cols,
+                         orc_shift_params p, int64_t* e) {
+    int64_t top = ((int64_t)1 << (p.k_out - 1)) - 1;
+    int64_t mx = INT64_MIN;
+    for (int32_t j = 0; j < cols; ++j) {
+        e[j] = (int64_t)xr[j] + (br ? br[j] : 0) - ((mr && mr[j]) ? (int64_t)ORC_MASK_LOGIT * p.i0 : 0);
+        if (e[j] > mx) mx = e[j];
+    }
+    int64_t sum = 0;
+    for (int32_t j = 0; j < cols; ++j) { e[j] = orc_shiftexp(e[j] - mx, p.i0, p.n_shift); sum += e[j]; }
+    for (int32_t j = 0; j < cols; ++j) {
+        int64_t o = orc_intdiv(e[j], sum, p.k_out, p.m_bits);
+        yr[j] = (int8_t)(o > top ? top : o);
+    }
+}
+
 void orc_shiftmax(const int8_t* x, const int8_t* bias, int32_t H, int32_t T, int8_t* y,
                   int64_t rows, int32_t cols, int32_t ld, orc_shift_params p) {
     int64_t* e = (int64_t*)malloc(sizeof(int64_t) * (size_t)(cols > 0 ? cols : 1));
-    int64_t top = ((int64_t)1 << (p.k_out - 1)) - 1;
     for (int64_t r = 0; r < rows; ++r) {
-        const int8_t* xr = x + r * (int64_t)ld;
         const int8_t* br = bias ? bias + (((r / T) % H) * (int64_t)T + (r % T)) * cols : NULL;
-        int64_t mx = INT64_MIN;
-        for (int32_t j = 0; j < cols; ++j) {
-            e[j] = (int64_t)xr[j] + (br ? br[j] : 0);
-            if (e[j] > mx) mx = e[j];
-        }
-        int64_t sum = 0;
-        for (int32_t j = 0; j < cols; ++j) { e[j] = orc_shiftexp(e[j] - mx, p.i0, p.n_shift); sum += e[j]; }
-        for (int32_t j = 0; j < cols; ++j) {
-            int64_t o = orc_intdiv(e[j], sum, p.k_out, p.m_bits);
-            y[r * (int64_t)cols + j] = (int8_t)(o > top ? top : o);
-        }
+        shiftmax_row(x + r * (int64_t)ld, br, NULL, y + r * (int64_t)cols, cols, p, e);
     }
     free(e);
 }
@@ -218,6 +227,7 @@ typedef struct {
     const int8_t* w_fc1; const int32_t *bias_fc1, *fc1_rq_b, *fc1_rq_c;
     orc_shift_params gelu; orc_dyadic gelu_rq;
     const int8_t* w_fc2; const int32_t *bias_fc2, *fc2_rq_b, *fc2_rq_c; orc_dyadic res2_rq;
+    const int8_t* attn_mask; int32_t n_mask;          /* [n_mask, T, T], NULL: none (shifted-window attention) */
 } orc_block_params;
 
 /* Optional taps: every intermediate int tensor of a block (any may be NULL). */
@@ -229,12 +239,13 @@ typedef struct { int8_t *u, *qkv, *scores, *probs, *o, *xhat, *v, *h; } orc_taps
  * of the dyadic pair, by the homogeneity argument of Sec. 3.1), an optional
  * int8 relative-position bias [H,T,T] is added, P = Shiftmax(rows of A),
  * O = requant(P V; pv_rq), heads concatenated into o [B*T, C]. */
-void orc_attention(const int8_t* qkv, const int8_t* rel_bias, int8_t* o,
-                   orc_dims d, orc_dyadic qk_rq, orc_shift_params sm, orc_dyadic pv_rq,
-                   int8_t* tap_scores, int8_t* tap_probs) {
+void orc_attention_masked(const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask, int8_t* o,
+                          orc_dims d, orc_dyadic qk_rq, orc_shift_params sm, orc_dyadic pv_rq,
+                          int8_t* tap_scores, int8_t* tap_probs) {
     int32_t T = d.T, C = d.C, H = d.H, hd = d.C / d.H;
     int8_t* a = (int8_t*)malloc((size_t)T * T);
     int8_t* p = (int8_t*)malloc((size_t)T * T);
+    int64_t* erow = (int64_t*)malloc(sizeof(int64_t) * (size_t)T);
     for (int32_t b = 0; b < d.B; ++b)
         for (int32_t h = 0; h < H; ++h) {
             const int8_t* base = qkv + (int64_t)b * T * 3 * C + h * hd;
@@ -245,8 +256,10 @@ void orc_attention(const int8_t* qkv, const int8_t* rel_bias, int8_t* o,
                         acc += (int64_t)base[(int64_t)i * 3 * C + k] * base[(int64_t)j * 3 * C + C + k];
                     a[i * T + j] = (int8_t)orc_requant(acc, qk_rq.b, qk_rq.c);
                 }
-            /* rows of this (image, head) are rows 0..T-1 of head h for the bias lookup */
-            orc_shiftmax(a, rel_bias ? rel_bias + (int64_t)h * T * T : NULL, 1, T, p, T, T, T, sm);
+            /* window b uses mask[b % n_mask] ([T, T], shared by the heads): the windows of an image are consecutive */
+            for (int32_t i = 0; i < T; ++i)
+                shiftmax_row(a + i * T, rel_bias ? rel_bias + ((int64_t)h * T + i) * T : NULL,
+                             mask ? mask + ((int64_t)(b % n_mask) * T + i) * T : NULL, p + i * T, T, sm, erow);
             for (int32_t i = 0; i < T; ++i)
                 for (int32_t k = 0; k < hd; ++k) {
                     int64_t acc = 0;
@@ -258,7 +271,13 @@ void orc_attention(const int8_t* qkv, const int8_t* rel_bias, int8_t* o,
             if (tap_scores) memcpy(tap_scores + off, a, (size_t)T * T);
             if (tap_probs) memcpy(tap_probs + off, p, (size_t)T * T);
         }
-    free(a); free(p);
+    free(a); free(p); free(erow);
+}
+
+void orc_attention(const int8_t* qkv, const int8_t* rel_bias, int8_t* o,
+                   orc_dims d, orc_dyadic qk_rq, orc_shift_params sm, orc_dyadic pv_rq,
+                   int8_t* tap_scores, int8_t* tap_probs) {
+    orc_attention_masked(qkv, rel_bias, NULL, 1, o, d, qk_rq, sm, pv_rq, tap_scores, tap_probs);
 }
 
 /* One encoder block (Eq. 1-2): Xhat = MSA(LN(X)) + X ; Y = MLP(LN(Xhat)) + Xhat. */
@@ -274,8 +293,8 @@ void orc_encoder_block(const int8_t* x, int8_t* y, const orc_block_params* p, or
     int8_t* h    = (int8_t*)malloc((size_t)R * F);
     orc_ilayernorm(x, p->ln1_gamma, p->ln1_beta, u, R, C, p->ln1_f_bits, p->ln1_c_shift);
     orc_linear_requant(u, p->w_qkv, p->bias_qkv, p->qkv_rq_b, p->qkv_rq_c, NULL, none, NULL, none, qkv, R, 3 * C, C);
-    orc_attention(qkv, p->rel_bias, o, d, p->qk_rq, p->softmax, p->pv_rq,
-                  taps ? taps->scores : NULL, taps ? taps->probs : NULL);
+    orc_attention_masked(qkv, p->rel_bias, p->attn_mask, p->attn_mask ? p->n_mask : 1, o, d, p->qk_rq, p->softmax, p->pv_rq,
+                         taps ? taps->scores : NULL, taps ? taps->probs : NULL);
     orc_linear_requant(o, p->w_proj, p->bias_proj, p->proj_rq_b, p->proj_rq_c, x, p->res1_rq, NULL, none, xhat, R, C, C);
     orc_ilayernorm(xhat, p->ln2_gamma, p->ln2_beta, v, R, C, p->ln2_f_bits, p->ln2_c_shift);
     orc_linear_requant(v, p->w_fc1, p->bias_fc1, p->fc1_rq_b, p->fc1_rq_c, NULL, none, &p->gelu, p->gelu_rq, h, R, F, C);

@@ -49,6 +49,7 @@ class _BlockParams(C.Structure):
         ("w_fc1", _P), ("bias_fc1", _P), ("fc1_rq_b", _P), ("fc1_rq_c", _P),
         ("gelu", ShiftParams), ("gelu_rq", Dyadic),
         ("w_fc2", _P), ("bias_fc2", _P), ("fc2_rq_b", _P), ("fc2_rq_c", _P), ("res2_rq", Dyadic),
+        ("attn_mask", _P), ("n_mask", C.c_int32),
     ]
 
 
@@ -87,8 +88,8 @@ def _L():
         lib.orc_linear_requant.restype = None
         lib.orc_linear_requant.argtypes = [_P, _P, _P, _P, _P, _P, Dyadic, C.POINTER(ShiftParams), Dyadic,
                                            _P, i64, i32, i32]
-        lib.orc_attention.restype = None
-        lib.orc_attention.argtypes = [_P, _P, _P, _Dims, Dyadic, ShiftParams, Dyadic, _P, _P]
+        lib.orc_attention_masked.restype = None
+        lib.orc_attention_masked.argtypes = [_P, _P, _P, C.c_int32, _P, _Dims, Dyadic, ShiftParams, Dyadic, _P, _P]
         lib.orc_encoder_block.restype = None
         lib.orc_encoder_block.argtypes = [_P, _P, C.POINTER(_BlockParams), _Dims, C.POINTER(_Taps)]
         lib.orc_forward.restype = None
@@ -201,7 +202,8 @@ def _dims(d):
     return _Dims(int(d["B"]), int(d["T"]), int(d["C"]), int(d["H"]), int(d["F"]))
 
 
-def attention(qkv, dims, qk_rq, softmax, pv_rq, rel_bias=None, want_taps=False):
+def attention(qkv, dims, qk_rq, softmax, pv_rq, rel_bias=None, want_taps=False, mask=None):
+    """mask: None or int8 [n_mask, T, T]; window b uses mask[b % n_mask]; nonzero entries add -100 (real units)."""
     qkv = _arr(qkv, np.int8)
     B, T, Cc, H = dims["B"], dims["T"], dims["C"], dims["H"]
     assert qkv.shape == (B * T, 3 * Cc)
@@ -209,8 +211,9 @@ def attention(qkv, dims, qk_rq, softmax, pv_rq, rel_bias=None, want_taps=False):
     o = np.empty((B * T, Cc), np.int8)
     sc = np.empty((B, H, T, T), np.int8) if want_taps else None
     pr = np.empty((B, H, T, T), np.int8) if want_taps else None
-    _L().orc_attention(_ptr(qkv), _ptr(rel_bias), _ptr(o), _dims(dims), _dy(qk_rq), _sp(softmax), _dy(pv_rq),
-                       _ptr(sc), _ptr(pr))
+    mask = None if mask is None else _arr(mask, np.int8)
+    _L().orc_attention_masked(_ptr(qkv), _ptr(rel_bias), _ptr(mask), 1 if mask is None else int(mask.shape[0]), _ptr(o),
+                              _dims(dims), _dy(qk_rq), _sp(softmax), _dy(pv_rq), _ptr(sc), _ptr(pr))
     return (o, sc, pr) if want_taps else o
 
 
@@ -219,7 +222,7 @@ _PTR_FIELDS = {
     "qkv_rq_c": np.int32, "rel_bias": np.int8, "w_proj": np.int8, "bias_proj": np.int32, "proj_rq_b": np.int32,
     "proj_rq_c": np.int32, "ln2_gamma": np.int32, "ln2_beta": np.int32, "w_fc1": np.int8, "bias_fc1": np.int32,
     "fc1_rq_b": np.int32, "fc1_rq_c": np.int32, "w_fc2": np.int8, "bias_fc2": np.int32, "fc2_rq_b": np.int32,
-    "fc2_rq_c": np.int32,
+    "fc2_rq_c": np.int32, "attn_mask": np.int8,
 }
 _INT_FIELDS = ("ln1_f_bits", "ln1_c_shift", "ln2_f_bits", "ln2_c_shift")
 _DY_FIELDS = ("qk_rq", "pv_rq", "res1_rq", "gelu_rq", "res2_rq")
@@ -242,6 +245,8 @@ def _block(p, keep):
         setattr(bp, name, _dy(p[name]))
     for name in _SP_FIELDS:
         setattr(bp, name, _sp(p[name]))
+    m = p.get("attn_mask")
+    bp.n_mask = 1 if m is None else int(np.shape(m)[0])
     return bp
 
 

@@ -18,7 +18,7 @@ EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftg
            "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward",
            "ivit_trace_begin", "ivit_trace_end", "ivit_quantize_symmetric", "ivit_dyadic_from_float",
            "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
-           "ivit_forward_image")
+           "ivit_forward_image", "ivit_attention_masked")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
               7: "shiftgelu", 8: "embed_tokens"}
@@ -49,6 +49,7 @@ class BlockParams(C.Structure):
         ("w_fc1", _P), ("bias_fc1", _P), ("fc1_rq_b", _P), ("fc1_rq_c", _P),
         ("gelu", ShiftParams), ("gelu_rq", Dyadic),
         ("w_fc2", _P), ("bias_fc2", _P), ("fc2_rq_b", _P), ("fc2_rq_c", _P), ("res2_rq", Dyadic),
+        ("attn_mask", _P), ("n_mask", C.c_int32),
     ]
 
 
@@ -98,6 +99,8 @@ def load():
     lib.ivit_workspace_bytes.restype = C.c_size_t; lib.ivit_workspace_bytes.argtypes = [C.POINTER(Dims)]
     lib.ivit_attention.restype = C.c_int
     lib.ivit_attention.argtypes = [_P, _P, _P, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
+    lib.ivit_attention_masked.restype = C.c_int
+    lib.ivit_attention_masked.argtypes = [_P, _P, _P, _P, i32, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
     lib.ivit_encoder_block.restype = C.c_int
     lib.ivit_encoder_block.argtypes = [_P, _P, _P, C.POINTER(BlockParams), C.POINTER(Dims), _P, C.c_size_t,
                                        C.POINTER(DebugTaps)]
@@ -243,9 +246,14 @@ def ivit_workspace_bytes(d):
     return int(load().ivit_workspace_bytes(C.byref(dims(d))))
 
 
-def ivit_attention(qkv, o, d, qk_rq, softmax, pv_rq, rel_bias=None, tap_scores=None, tap_probs=None, stream=None):
-    st = load().ivit_attention(_stream(stream), _ptr(qkv), _ptr(rel_bias), _ptr(o), C.byref(dims(d)), dyadic(qk_rq),
-                               shift_params(softmax), dyadic(pv_rq), _ptr(tap_scores), _ptr(tap_probs))
+def ivit_attention(qkv, o, d, qk_rq, softmax, pv_rq, rel_bias=None, tap_scores=None, tap_probs=None, stream=None, mask=None):
+    if mask is None:
+        st = load().ivit_attention(_stream(stream), _ptr(qkv), _ptr(rel_bias), _ptr(o), C.byref(dims(d)), dyadic(qk_rq),
+                                   shift_params(softmax), dyadic(pv_rq), _ptr(tap_scores), _ptr(tap_probs))
+    else:
+        st = load().ivit_attention_masked(_stream(stream), _ptr(qkv), _ptr(rel_bias), _ptr(mask), int(mask.shape[0]), _ptr(o),
+                                          C.byref(dims(d)), dyadic(qk_rq), shift_params(softmax), dyadic(pv_rq),
+                                          _ptr(tap_scores), _ptr(tap_probs))
     _check(st, "ivit_attention")
     return o
 
@@ -271,6 +279,9 @@ def block_params(p):
         setattr(bp, k, dyadic(p[k]))
     for k in _SP_FIELDS:
         setattr(bp, k, shift_params(p[k]))
+    m = p.get("attn_mask")
+    bp.attn_mask = _ptr(m)
+    bp.n_mask = 1 if m is None else int(m.shape[0])
     return bp
 
 

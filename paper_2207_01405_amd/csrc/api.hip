@@ -77,6 +77,7 @@ int check_block(const ivit_block_params* p, const ivit_dims* d) {
         (st = check_dyadic(p->gelu_rq)) != IVIT_OK)
         return st;
     if ((st = check_shift(p->softmax)) != IVIT_OK || (st = check_shift(p->gelu)) != IVIT_OK) return st;
+    if (p->attn_mask && p->n_mask < 1) return IVIT_ERR_SHAPE;
     if (!aligned(p->w_qkv, 16) || !aligned(p->w_proj, 16) || !aligned(p->w_fc1, 16) || !aligned(p->w_fc2, 16))
         return IVIT_ERR_ALIGN;
     const void* i32s[] = {p->ln1_gamma, p->ln1_beta, p->bias_qkv, p->qkv_rq_b, p->qkv_rq_c, p->bias_proj, p->proj_rq_b,
@@ -109,6 +110,7 @@ hipError_t run_block(hipStream_t s, const int8_t* x, int8_t* y, const ivit_block
     // o = attention(qkv)
     ivit::AttentionArgs aa{};
     aa.qkv = w.qkv; aa.rel_bias = p->rel_bias; aa.o = w.o; aa.B = d->B; aa.T = d->T; aa.C = C; aa.H = d->H;
+    aa.mask = p->attn_mask; aa.n_mask = p->attn_mask ? p->n_mask : 1;
     aa.qk_rq = dy(p->qk_rq); aa.sm = sp(p->softmax); aa.pv_rq = dy(p->pv_rq);
     aa.tap_scores = taps ? taps->scores : nullptr; aa.tap_probs = taps ? taps->probs : nullptr;
     if ((e = ivit::launch_attention(s, aa))) return e;
@@ -221,7 +223,14 @@ size_t ivit_workspace_bytes(const ivit_dims* d) {
 int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8_t* o, const ivit_dims* d,
                    ivit_dyadic qk_rq, ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores,
                    int8_t* tap_probs) {
+    return ivit_attention_masked(stream, qkv, rel_bias, nullptr, 1, o, d, qk_rq, softmax, pv_rq, tap_scores, tap_probs);
+}
+
+int ivit_attention_masked(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
+                          int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq, ivit_shift_params softmax,
+                          ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs) {
     if (!d) return IVIT_ERR_NULL;
+    if (mask && n_mask < 1) return IVIT_ERR_SHAPE;
     int st;
     if ((st = check_dims(d)) != IVIT_OK) return st;
     if (d->B > 0 && (!qkv || !o)) return IVIT_ERR_NULL;
@@ -231,6 +240,7 @@ int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8
     if (!aligned(qkv, 16) || !aligned(o, 16)) return IVIT_ERR_ALIGN;
     ivit::AttentionArgs a{};
     a.qkv = qkv; a.rel_bias = rel_bias; a.o = o; a.B = d->B; a.T = d->T; a.C = d->C; a.H = d->H;
+    a.mask = mask; a.n_mask = mask ? n_mask : 1;
     a.qk_rq = dy(qk_rq); a.sm = sp(softmax); a.pv_rq = dy(pv_rq); a.tap_scores = tap_scores; a.tap_probs = tap_probs;
     return hip_status(ivit::launch_attention(static_cast<hipStream_t>(stream), a));
 }

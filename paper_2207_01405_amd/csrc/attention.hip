@@ -43,9 +43,10 @@ __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d) {
 
 // FAST: both dyadic pairs are rescales by at most 1 with c <= 31 (32-bit requantisation) and the row sum always
 // exceeds 2^(k_out-1), so that IntDiv is one multiply-high by the pre-shifted reciprocal.
-template <int D, int NKT, bool TAPS, bool BIAS, bool FAST>
+template <int D, int NKT, bool TAPS, bool BIAS, bool MASK, bool FAST>
 __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
+                                                        const int8_t* __restrict__ mask, int n_mask,
                                                         int8_t* __restrict__ o, int n_items, int T, int C, int H,
                                                         Dyadic qk, ShiftParams sm, Dyadic pv,
                                                         int8_t* __restrict__ tap_s, int8_t* __restrict__ tap_p) {
@@ -56,11 +57,14 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
     constexpr int DCH = D / 16;                   // 16-byte chunks per K / V row
     __shared__ __align__(16) int8_t Ks[NKT * 16 * KROW];
     __shared__ __align__(16) int8_t Vt[D * VROW];
-    __shared__ uint16_t lut[512];
+    // table of ShiftExp(-delta): int8 scores give delta <= 254; with a bias and the mask the exact range is wider,
+    // and beyond the table the value is 0 whenever it can occur (see the mask comment below)
+    constexpr int NLUT = MASK ? 1024 : (BIAS ? 512 : 256);
+    __shared__ uint16_t lut[NLUT];
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
-    for (int i = tid; i < 512; i += ATT_THREADS) lut[i] = (uint16_t)shiftexp(-i, sm.i0, sm.n_shift);
+    for (int i = tid; i < NLUT; i += ATT_THREADS) lut[i] = (uint16_t)shiftexp(-i, sm.i0, sm.n_shift);
     // keys beyond the 16-key tiles but inside the last 64-key chunk multiply probabilities that are zero;
     // clear them once so that no uninitialised LDS is ever read
     for (int i = tid; i < D * VROW / 4; i += ATT_THREADS) reinterpret_cast<uint32_t*>(Vt)[i] = 0u;
@@ -140,7 +144,14 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             }
             // ---- requantise, add the bias, row maximum.  Lane (li, lg) holds keys 16 t + 4 lg + r.
             const int64_t tap_row = ((int64_t)item * T + qc) * T;
-            const int8_t* brow = BIAS ? rel_bias + ((int64_t)h * T + qc) * T : nullptr;
+            // BIAS: a relative-position bias and / or the shifted-window mask.  A masked key gets -100 I_0 (the -100
+            // the windowed models add, at the integer scale of the logits).  All of this is exact int32 arithmetic;
+            // only the table is finite: an unmasked key is at most 508 below the row maximum, and for a masked key
+            // ShiftExp(-delta) is 0 for every delta >= 1024 it can reach (delta >= 100 I_0 - 508, and a non-zero
+            // value needs delta < 23 I_0), so entries past the table read as 0.
+            const int8_t* brow = (BIAS && rel_bias) ? rel_bias + ((int64_t)h * T + qc) * T : nullptr;
+            const int8_t* mrow = MASK ? mask + ((int64_t)(b % n_mask) * T + qc) * T : nullptr;
+            const int32_t mask_add = -100 * sm.i0;
             int32_t mx = INT32_MIN;
 #pragma unroll
             for (int t = 0; t < NKT; ++t) {
@@ -150,7 +161,8 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                         const int key = 16 * t + 4 * lg + r;
                         int32_t a = requant8<FAST>(sc[t][r], qk);
                         if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
-                        if (BIAS) a += brow[key];
+                        if (BIAS) { if (!MASK || brow) a += brow[key]; }
+                        if (MASK) { if (mrow[key]) a += mask_add; }
                         sc[t][r] = a;
                     }
                     mx = max(mx, max(sc[t][0], sc[t][1]));       // two three-operand maxima per tile
@@ -162,7 +174,8 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                         int32_t a = requant8<FAST>(sc[t][r], qk);
                         if (key < T) {
                             if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
-                            if (BIAS) a += brow[key];
+                            if (BIAS) { if (!MASK || brow) a += brow[key]; }
+                            if (MASK) { if (mrow[key]) a += mask_add; }
                             mx = max(mx, a);
                         }
                         sc[t][r] = a;
@@ -181,7 +194,13 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 if (t < nfull) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int32_t e = (int32_t)*reinterpret_cast<const uint16_t*>(lut_b + (__mul24(sc[t][r], -2) + mx2));
+                        int32_t e;
+                        if (MASK) {
+                            const int32_t delta = mx - sc[t][r];
+                            e = delta < NLUT ? (int32_t)lut[min(delta, NLUT - 1)] : 0;
+                        } else {
+                            e = (int32_t)*reinterpret_cast<const uint16_t*>(lut_b + (__mul24(sc[t][r], -2) + mx2));
+                        }
                         sc[t][r] = e;
                         sum += e;
                     }
@@ -189,7 +208,13 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int key = 16 * t + 4 * lg + r;
-                        const int32_t e = key < T ? (int32_t)lut[mx - sc[t][r]] : 0;
+                        int32_t e;
+                        if (MASK) {
+                            const int32_t delta = key < T ? mx - sc[t][r] : NLUT;
+                            e = delta < NLUT ? (int32_t)lut[min(delta, NLUT - 1)] : 0;
+                        } else {
+                            e = key < T ? (int32_t)lut[mx - sc[t][r]] : 0;
+                        }
                         sc[t][r] = e;
                         sum += e;
                     }
@@ -259,12 +284,22 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 template <int D, int NKT>
 static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, bool taps, bool bias, bool fast) {
     const int n_items = a.B * a.H;
-#define IVIT_ATT(TAPS_, BIAS_, FAST_)                                                                              \
-    hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, FAST_>), dim3(grid), dim3(ATT_THREADS), 0, s, a.qkv, a.rel_bias, \
-                       a.o, n_items, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs)
-    // the production path is <no taps, fast>; everything else shares one fully general instantiation per bias flag
-    if (!taps && fast) { if (bias) IVIT_ATT(false, true, true); else IVIT_ATT(false, false, true); }
-    else { if (bias) IVIT_ATT(true, true, false); else IVIT_ATT(true, false, false); }
+#define IVIT_ATT(TAPS_, BIAS_, MASK_, FAST_)                                                                       \
+    hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, MASK_, FAST_>), dim3(grid), dim3(ATT_THREADS), 0, s, a.qkv, \
+                       a.rel_bias, a.mask, a.n_mask, a.o, n_items, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores,    \
+                       a.tap_probs)
+    // the production paths are <no taps, fast>; everything else shares one fully general instantiation per bias / mask
+    // combination (a mask is always compiled with the bias code, which tests the bias pointer)
+    const bool masked = a.mask != nullptr;
+    if (!taps && fast) {
+        if (masked) IVIT_ATT(false, true, true, true);
+        else if (bias) IVIT_ATT(false, true, false, true);
+        else IVIT_ATT(false, false, false, true);
+    } else {
+        if (masked) IVIT_ATT(true, true, true, false);
+        else if (bias) IVIT_ATT(true, true, false, false);
+        else IVIT_ATT(true, false, false, false);
+    }
 #undef IVIT_ATT
 }
 
@@ -291,8 +326,8 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     const bool taps = a.tap_scores || a.tap_probs;
     const int64_t R = (int64_t)a.B * a.T;
     TraceScope trace(s, KIND_ATTENTION, 4 * n_items * a.T * a.T * d, 4 * R * a.C + (a.rel_bias ? (int64_t)a.H * a.T * a.T : 0));
-    return d == 64 ? launch_d<64>(s, a, grid, nkt, taps, a.rel_bias != nullptr, fast)
-                   : launch_d<32>(s, a, grid, nkt, taps, a.rel_bias != nullptr, fast);
+    return d == 64 ? launch_d<64>(s, a, grid, nkt, taps, a.rel_bias != nullptr || a.mask != nullptr, fast)
+                   : launch_d<32>(s, a, grid, nkt, taps, a.rel_bias != nullptr || a.mask != nullptr, fast);
 }
 
 }  // namespace ivit

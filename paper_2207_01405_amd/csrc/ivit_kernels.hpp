@@ -30,6 +30,7 @@ hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int
 
 struct AttentionArgs {
     const int8_t* qkv; const int8_t* rel_bias; int8_t* o;
+    const int8_t* mask; int n_mask;      // shifted-window mask [n_mask, T, T] or nullptr
     int B, T, C, H;
     Dyadic qk_rq; ShiftParams sm; Dyadic pv_rq;
     int8_t* tap_scores; int8_t* tap_probs;

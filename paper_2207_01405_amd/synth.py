@@ -143,6 +143,24 @@ def make_block(cfg, layer):
     return p
 
 
+def make_shift_mask(window=7, shift=3, grid=8):
+    """int8 [grid * grid, window^2, window^2] mask of shifted-window attention for one image: after a cyclic shift by
+    `shift`, the last row and column of windows hold tokens of different image regions; pairs from different regions
+    are masked (1), all other entries are 0.  Window order is row-major over the image, as the tokens are laid out."""
+    T = window * window
+    m = np.zeros((grid * grid, T, T), np.int8)
+    for wy in range(grid):
+        for wx in range(grid):
+            region = np.zeros((window, window), np.int32)
+            if wy == grid - 1:
+                region[window - shift:, :] += 1
+            if wx == grid - 1:
+                region[:, window - shift:] += 2
+            r = region.reshape(-1)
+            m[wy * grid + wx] = (r[:, None] != r[None, :]).astype(np.int8)
+    return m
+
+
 def make_final_ln(cfg):
     rng = np.random.default_rng([cfg["seed"], 3000])
     g, b = _ln(rng, cfg["C"])

@@ -33,7 +33,9 @@ def test_struct_layouts_match_the_header(lib):
     assert C.sizeof(binding.DebugTaps) == 64 and C.sizeof(binding.FinalLN) == 24
     # pointers 8-byte aligned, ints packed in pairs: count by hand from the header
     n_ptr = sum(1 for _, t in binding.BlockParams._fields_ if t is C.c_void_p)
-    assert n_ptr == 21 and C.sizeof(binding.BlockParams) == 21 * 8 + 4 * 4 + 5 * 8 + 2 * 16
+    # 22 pointers, 4 I-LayerNorm ints, 5 dyadic pairs, 2 shift-parameter structs, n_mask padded to 8 bytes
+    assert n_ptr == 22 and C.sizeof(binding.BlockParams) == 22 * 8 + 4 * 4 + 5 * 8 + 2 * 16 + 8
+    assert C.sizeof(binding.ImageParams) == 10 * 8 + 2 * 8 + 2 * 8        # 10 pointers, 2 ints each padded, 2 dyadic pairs
 
 
 def test_strerror(lib):
@@ -101,6 +103,7 @@ def _fake_block():
         if t is C.c_void_p:
             setattr(bp, name, FAKE)
     bp.rel_bias = None
+    bp.attn_mask = None
     for k in ("ln1_f_bits", "ln2_f_bits"):
         setattr(bp, k, 16)
     for k in ("ln1_c_shift", "ln2_c_shift"):

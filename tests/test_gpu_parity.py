@@ -408,3 +408,49 @@ def test_forward_under_hip_graph_capture_replays_identically(ivit):
         g.replay()
         torch.cuda.synchronize()
         assert_same(host(y_graph), want, "graph replay %d" % rep)
+
+
+# ------------------------------------------------------------------ shifted-window attention mask
+@pytest.mark.parametrize("name,B,i0,with_bias", [("c4_swin_t", 64, 32, True), ("c4_swin_t", 130, 32, False), ("c4_swin_t", 64, 2, True),
+                                                 ("c4_swin_t", 64, 5, True), ("c4_swin_t", 64, 6, False), ("c4_swin_t", 64, 11, True),
+                                                 ("c4_swin_t", 64, 1000, True), ("c2_deit_s", 5, 32, False), ("c0_tiny", 3, 12, False)])
+def test_attention_with_shift_mask(ivit, name, B, i0, with_bias):
+    cfg = synth.CONFIGS[name]
+    T = cfg["T"]
+    d = synth.dims_of(cfg, B)
+    blk = synth.make_block(cfg, 0)
+    sm = synth.shift_params(i0)
+    rng = np.random.default_rng(B + i0)
+    if T == 49:
+        mask = synth.make_shift_mask()
+    else:                                            # any pattern is legal: three mask types, random, diagonal kept
+        mask = (rng.random((3, T, T)) < 0.4).astype(np.int8)
+        mask[:, np.arange(T), np.arange(T)] = 0
+        mask[1, 7, :] = 1                            # a row with every key masked
+    rb = blk["rel_bias"] if with_bias and blk["rel_bias"] is not None else None
+    if with_bias and rb is None:
+        rb = np.clip(np.rint(rng.standard_normal((cfg["H"], T, T)) * 40), -127, 127).astype(np.int8)
+    qkv = synth.make_rows(B + T, B * T, 3 * cfg["C"], "normal", 32.0)
+    want, sc_ref, pr_ref = orc.attention(qkv, d, blk["qk_rq"], sm, blk["pv_rq"], rb, want_taps=True, mask=mask)
+    o = empty((B * T, cfg["C"])); pr = empty((B, cfg["H"], T, T))
+    ivit.ivit_attention(dev(qkv), o, d, blk["qk_rq"], sm, blk["pv_rq"], rel_bias=None if rb is None else dev(rb), mask=dev(mask), tap_probs=pr)
+    assert_same(host(pr), pr_ref, "masked probs")
+    assert_same(host(o), want, "masked attention")
+    o2 = empty(o.shape)
+    ivit.ivit_attention(dev(qkv), o2, d, blk["qk_rq"], sm, blk["pv_rq"], rel_bias=None if rb is None else dev(rb), mask=dev(mask))
+    assert_same(host(o2), want, "masked attention (no taps)")
+
+
+def test_encoder_block_with_shift_mask(ivit):
+    cfg = synth.CONFIGS["c4_swin_t"]
+    B = 128
+    d = synth.dims_of(cfg, B)
+    p = dict(synth.make_block(cfg, 0), attn_mask=synth.make_shift_mask())
+    x = synth.make_input(cfg)[: B * cfg["T"]]
+    y_ref, t_ref = orc.encoder_block(x, p, d, want_taps=True)
+    y, taps = _gpu_block(ivit, x, p, d, True)
+    for k in orc.TAP_NAMES:
+        assert_same(taps[k], t_ref[k], "masked block tensor " + k)
+    assert_same(y, y_ref, "masked block output")
+    y_plain, _ = orc.encoder_block(x, synth.make_block(cfg, 0), d, want_taps=True)
+    assert not np.array_equal(y_plain, y_ref)

@@ -530,3 +530,40 @@ def test_oracle_runs_clean_under_address_and_undefined_behaviour_sanitizers(tmp_
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0")
     r = subprocess.run([exe], capture_output=True, text=True, env=env, timeout=300)
     assert r.returncode == 0 and "sanitize_check: ok" in r.stdout, r.stdout[-2000:] + r.stderr[-4000:]
+
+
+# ------------------------------------------------------------------ shifted-window attention mask
+def test_masked_attention_drops_masked_keys_and_equals_shiftmax_on_the_rest():
+    cfg = synth.CONFIGS["c4_swin_t"]
+    B = 64
+    d = synth.dims_of(cfg, B)
+    blk = synth.make_block(cfg, 0)
+    qkv = synth.make_rows(5, B * cfg["T"], 3 * cfg["C"], "normal", 32.0)
+    mask = synth.make_shift_mask()
+    assert mask.shape == (64, 49, 49) and mask[0].sum() == 0 and mask[63].sum() > 0 and np.array_equal(mask[7], mask[7].T)
+    o0 = orc.attention(qkv, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], blk["rel_bias"])
+    o1, sc, pr = orc.attention(qkv, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], blk["rel_bias"], want_taps=True, mask=mask)
+    T, C = cfg["T"], cfg["C"]
+    plain = [w for w in range(64) if mask[w].sum() == 0]
+    assert np.array_equal(o0.reshape(B, T, C)[plain], o1.reshape(B, T, C)[plain])          # unmasked windows untouched
+    assert pr[np.broadcast_to(mask[:, None].astype(bool), pr.shape)].max() == 0           # exp(-100) is 0 in ShiftExp
+    # a masked row is the Shiftmax of its unmasked keys alone
+    w, h, i = 63, 1, 10
+    keep = mask[w, i] == 0
+    row = sc[w, h, i].astype(np.int64) + blk["rel_bias"][h, i].astype(np.int64)
+    sub = np.clip(row[keep], -127, 127).astype(np.int8)[None]                              # in range here: check
+    assert np.array_equal(sub[0].astype(np.int64), row[keep])
+    assert np.array_equal(pr[w, h, i][keep], orc.shiftmax(sub, blk["softmax"])[0])
+
+
+def test_shiftexp_is_zero_beyond_a_1024_entry_table_wherever_a_masked_key_can_land():
+    """What the GPU kernel relies on: a masked key sits at least 100 I_0 - 508 below the row maximum (scores and bias
+    are int8), and every such distance that is >= 1024 has ShiftExp exactly 0, for every I_0 the ABI allows."""
+    for i0 in list(range(1, 400)) + [511, 512, 1000, 4095, 4096, 30000, 65535]:
+        n = 16 - int(i0).bit_length()
+        lo = max(1024, 100 * i0 - 508)
+        hi = 100 * i0 + 508
+        if hi < lo:
+            continue
+        pts = np.unique(np.concatenate([np.arange(lo, min(hi, lo + 3000) + 1), np.linspace(lo, hi, 200).astype(np.int64), [hi]]))
+        assert orc.shiftexp_vec(-pts, i0, n).max() == 0, i0
