@@ -33,18 +33,6 @@ __device__ __forceinline__ int32_t requant64(int32_t v, int32_t b, int32_t c) {
     return clamp8_64(rnd_shift64(v, b, c));
 }
 
-// Same value as rnd_shift64 when 0 < b < 2^15, 16 <= c <= 31 and the result fits int32,
-// using only full-rate 24-bit multiplies: with v = hi * 2^16 + lo (0 <= lo < 2^16),
-//   (b v + 2^(c-1)) >> c = (b hi + ((b lo + 2^(c-1)) >> 16)) >> (c - 16),
-// because the 16 bits dropped by the inner shift lie below the final floor.
-__device__ __forceinline__ int32_t rnd_shift_b15(int32_t v, int32_t b, int32_t c) {
-    uint32_t lo = (uint32_t)v & 0xffffu;
-    int32_t hi = v >> 16;
-    uint32_t t = __umul24(lo, (uint32_t)b) + (1u << (c - 1));   // < 2^31 + 2^30
-    int32_t u = __mul24(hi, b) + (int32_t)(t >> 16);
-    return u >> (c - 16);
-}
-
 // round(b v / 2^c) when 1 <= c <= 31 and 1 <= b <= 2^c (a rescale by at most 1, so the result fits 32 bits):
 // one 64-bit multiply-add, then the 32 result bits are cut out of the 64-bit value.
 __device__ __forceinline__ bool dyadic_fits32(int32_t b, int32_t c) {
