@@ -1,8 +1,11 @@
 """ctypes front end of the CPU oracle (ivit_oracle.c).  TEST INFRASTRUCTURE ONLY.
 
 Compiles the C file with gcc on first use (plain -O2, no threads) and exposes
-numpy-in / numpy-out wrappers.  All arithmetic lives in the C file; this module
-only marshals arguments.  It imports nothing from the GPU package.
+numpy-in / numpy-out wrappers.  The integer operators live in the C file; this
+module marshals arguments and, for the layers around the encoder (token
+assembly, the window / stage structure of the windowed models, pooling), strings
+those operators together with plain numpy reshapes and int64 arithmetic.  It
+imports nothing from the GPU package.
 """
 import ctypes as C
 import os
@@ -21,6 +24,7 @@ __all__ = [
     "requant_vec", "rnd_shift_vec", "isqrt10_vec", "shiftexp_vec", "TAP_NAMES",
     "quantize_symmetric", "dyadic_from_float", "shift_params_from_scale",
     "embed_tokens", "classifier_head", "forward_image",
+    "window_partition", "window_reverse", "shift_mask", "swin_block", "patch_merge", "mean_pool", "swin_forward",
 ]
 
 
@@ -364,3 +368,106 @@ def forward_image(patches, image, blocks, d, final_ln):
     x = embed_tokens(tok, image["cls"], image["pos"], image["tok_rq"], image["pos_rq"], B)
     y = forward(x, blocks, d, final_ln=final_ln)
     return classifier_head(y, T, image["w_head"], image["bias_head"], image["head_rq_b"], image["head_rq_c"])
+
+
+# ---- windowed models (the Swin rows of Table 1): the integer ops above inside the window / stage structure of
+# the Swin Transformer, written with plain numpy reshapes.  Tokens of an image are kept in raster order [B, g, g, C].
+def window_partition(x, window):
+    """[B, g, g, C] -> [B * (g / window)^2, window^2, C], windows in raster order, tokens of a window in raster order."""
+    B, g, _, Cc = x.shape
+    n = g // window
+    return x.reshape(B, n, window, n, window, Cc).transpose(0, 1, 3, 2, 4, 5).reshape(B * n * n, window * window, Cc)
+
+
+def window_reverse(xw, window, g):
+    """Inverse of window_partition."""
+    n = g // window
+    Cc = xw.shape[-1]
+    B = xw.shape[0] // (n * n)
+    return xw.reshape(B, n, n, window, window, Cc).transpose(0, 1, 3, 2, 4, 5).reshape(B, g, g, Cc)
+
+
+def shift_mask(g, window, shift):
+    """int8 [(g / window)^2, window^2, window^2]: 1 where two tokens of a window of the cyclically shifted image come
+    from different regions of the image (three bands per axis: untouched windows, the unwrapped and the wrapped part of
+    the last window), else 0."""
+    label = np.zeros((1, g, g, 1), np.int32)
+    bands = (slice(0, g - window), slice(g - window, g - shift), slice(g - shift, g))
+    n = 0
+    for rows in bands:
+        for cols in bands:
+            label[0, rows, cols, 0] = n
+            n += 1
+    lw = window_partition(label, window)[:, :, 0]
+    return (lw[:, :, None] != lw[:, None, :]).astype(np.int8)
+
+
+def swin_block(x, p, g, window, shift, H):
+    """One block on x int8 [B, g, g, C]: I-LayerNorm, cyclic shift by -shift, window partition, attention per window
+    (relative-position bias, mask when shifted), reverse, shift back, projection + residual, then the MLP half."""
+    B, _, _, Cc = x.shape
+    F = np.shape(p["w_fc1"])[0]
+    flat = x.reshape(-1, Cc)
+    u = ilayernorm(flat, p["ln1_gamma"], p["ln1_beta"], p["ln1_f_bits"], p["ln1_c_shift"]).reshape(B, g, g, Cc)
+    if shift:
+        u = np.roll(u, (-shift, -shift), axis=(1, 2))
+    uw = window_partition(u, window)
+    nW = uw.shape[0]
+    qkv = linear_requant(uw.reshape(-1, Cc), p["w_qkv"], p["bias_qkv"], p["qkv_rq_b"], p["qkv_rq_c"])
+    d = dict(B=nW, T=window * window, C=Cc, H=H, F=F)
+    o = attention(qkv, d, p["qk_rq"], p["softmax"], p["pv_rq"], rel_bias=p.get("rel_bias"),
+                  mask=shift_mask(g, window, shift) if shift else None)
+    o = window_reverse(o.reshape(nW, window * window, Cc), window, g)
+    if shift:
+        o = np.roll(o, (shift, shift), axis=(1, 2))
+    xhat = linear_requant(o.reshape(-1, Cc), p["w_proj"], p["bias_proj"], p["proj_rq_b"], p["proj_rq_c"],
+                          residual=flat, res_rq=p["res1_rq"])
+    v = ilayernorm(xhat, p["ln2_gamma"], p["ln2_beta"], p["ln2_f_bits"], p["ln2_c_shift"])
+    h = linear_requant(v, p["w_fc1"], p["bias_fc1"], p["fc1_rq_b"], p["fc1_rq_c"], gelu=p["gelu"], gelu_rq=p["gelu_rq"])
+    y = linear_requant(h, p["w_fc2"], p["bias_fc2"], p["fc2_rq_b"], p["fc2_rq_c"], residual=xhat, res_rq=p["res2_rq"])
+    return y.reshape(B, g, g, Cc)
+
+
+def patch_merge(x, m):
+    """[B, g, g, C] -> [B, g/2, g/2, 2C]: the four tokens of each 2 x 2 neighbourhood are concatenated in the order
+    (row, column) offsets (0,0), (1,0), (0,1), (1,1), normalised by I-LayerNorm over 4C and reduced by a Dense layer
+    without bias."""
+    B, g, _, Cc = x.shape
+    cat = np.concatenate([x[:, 0::2, 0::2], x[:, 1::2, 0::2], x[:, 0::2, 1::2], x[:, 1::2, 1::2]], axis=-1)
+    u = ilayernorm(cat.reshape(-1, 4 * Cc), m["ln_gamma"], m["ln_beta"], m["f_bits"], m["c_shift"])
+    y = linear_requant(u, m["w"], None, m["rq_b"], m["rq_c"])
+    return y.reshape(B, g // 2, g // 2, -1)
+
+
+def mean_pool(x, rq):
+    """Average over the tokens of each image as a dyadic rescale of the token sum (the factor 1 / T sits in b / 2^c):
+    x int8 [B, T, C] -> int8 [B, C]."""
+    x = _arr(x, np.int8)
+    s = x.astype(np.int64).sum(axis=1)
+    return requant_vec(s, rq[0], rq[1]).astype(np.int8).reshape(s.shape)
+
+
+def swin_forward(patches, model, want_stages=False):
+    """patches int8 [B * g0 * g0, patch_dim] -> logits int8 [B, n_classes].  model: dict(grid, window, embed, stages,
+    final_ln, pool_rq, head); a stage is dict(C, H, merge (None for the first), blocks), a block carries `shift`."""
+    g, window = model["grid"], model["window"]
+    e = model["embed"]
+    B = patches.shape[0] // (g * g)
+    tok = linear_requant(patches, e["w"], e["bias"], e["rq_b"], e["rq_c"])
+    tok = ilayernorm(tok, e["ln_gamma"], e["ln_beta"], e["f_bits"], e["c_shift"])
+    x = tok.reshape(B, g, g, -1)
+    outs = []
+    for st in model["stages"]:
+        if st["merge"] is not None:
+            x = patch_merge(x, st["merge"])
+            g //= 2
+        for p in st["blocks"]:
+            x = swin_block(x, p, g, window, p["shift"], st["H"])
+        outs.append(x.reshape(B * g * g, -1).copy())
+    f = model["final_ln"]
+    Cc = x.shape[-1]
+    z = ilayernorm(x.reshape(-1, Cc), f["gamma"], f["beta"], f["f_bits"], f["c_shift"])
+    pooled = mean_pool(z.reshape(B, g * g, Cc), model["pool_rq"])
+    hd = model["head"]
+    logits = linear_requant(pooled, hd["w"], hd["bias"], hd["rq_b"], hd["rq_c"])
+    return (logits, outs, pooled) if want_stages else logits

@@ -194,6 +194,67 @@ def make_patches(cfg, n_images=None):
     return np.clip(np.rint(z), -127, 127).astype(np.int8)[: B * (cfg["T"] - 1)]
 
 
+# Hierarchical windowed models (the Swin rows of Table 1).  grid = tokens per image side after the patch embedding,
+# window = tokens per window side; stage s has width C * 2^s and depths[s] blocks that alternate between plain and
+# shifted windows (no shift once a window covers the whole grid).
+SWIN = {
+    "swin_tiny_test": dict(grid=16, window=4, C=32, heads=(1, 2, 4), depths=(2, 2, 2), patch_dim=48, n_classes=10,
+                           B=2, seed=11),
+    "swin_t": dict(grid=56, window=7, C=96, heads=(3, 6, 12, 24), depths=(2, 2, 6, 2), patch_dim=48, n_classes=1000,
+                   B=128, seed=12),
+}
+
+for _name, _cfg in SWIN.items():
+    _cfg["name"] = _name
+
+
+def make_swin_model(cfg):
+    """Every parameter of a windowed model: embedding (patch Dense + I-LayerNorm), per stage the patch merging
+    (I-LayerNorm over 4C + Dense to 2C, absent for the first stage) and its blocks (each with `shift` and a
+    relative-position bias), final I-LayerNorm, pooling pair and head."""
+    rng = np.random.default_rng([cfg["seed"], 8000])
+    window, T = cfg["window"], cfg["window"] ** 2
+    m = dict(grid=cfg["grid"], window=window, patch_dim=cfg["patch_dim"], n_classes=cfg["n_classes"])
+    C = cfg["C"]
+    (w, bias, rq_b, rq_c), _ = _dense(rng, C, cfg["patch_dim"], 32.0, 32.0, LN_OUT_SCALE)
+    g_, b_ = _ln(rng, C)
+    m["embed"] = dict(w=w, bias=bias, rq_b=rq_b, rq_c=rq_c, ln_gamma=g_, ln_beta=b_, f_bits=LN_F_BITS, c_shift=LN_C_SHIFT)
+    stages = []
+    g = cfg["grid"]
+    for s, (H, depth) in enumerate(zip(cfg["heads"], cfg["depths"])):
+        merge = None
+        if s > 0:
+            (w, _b, rq_b, rq_c), _ = _dense(rng, 2 * C, 4 * C, 1.0 / LN_OUT_SCALE, 32.0, LN_OUT_SCALE)
+            g_, b_ = _ln(rng, 4 * C)
+            merge = dict(ln_gamma=g_, ln_beta=b_, f_bits=LN_F_BITS, c_shift=LN_C_SHIFT, w=w, rq_b=rq_b, rq_c=rq_c)
+            C *= 2
+            g //= 2
+        bcfg = dict(T=T, C=C, H=H, F=4 * C, seed=cfg["seed"], i0="fixed", rel_bias=True)
+        blocks = []
+        for l in range(depth):
+            p = make_block(bcfg, 100 * s + l)
+            p["shift"] = window // 2 if (l % 2 == 1 and g > window) else 0
+            blocks.append(p)
+        stages.append(dict(C=C, H=H, grid=g, merge=merge, blocks=blocks))
+    m["stages"] = stages
+    g_, b_ = _ln(rng, C)
+    m["final_ln"] = dict(gamma=g_, beta=b_, f_bits=LN_F_BITS, c_shift=LN_C_SHIFT)
+    # the pooled mean of g * g int8 tokens, brought back to int8 at the same scale: b / 2^c ~ 1 / (g * g)
+    c = 20
+    m["pool_rq"] = (int(round(2.0 ** c / (g * g))), c)
+    (w, bias, rq_b, rq_c), _ = _dense(rng, cfg["n_classes"], C, 32.0, 32.0, LN_OUT_SCALE)
+    m["head"] = dict(w=w, bias=bias, rq_b=rq_b, rq_c=rq_c)
+    return m
+
+
+def make_swin_patches(cfg, n_images=None):
+    """int8 [B * grid^2, patch_dim]: flattened image patches in raster order."""
+    rng = np.random.default_rng([cfg["seed"], 9000])
+    B = cfg["B"] if n_images is None else n_images
+    z = rng.standard_normal((B * cfg["grid"] ** 2, cfg["patch_dim"])) * 32.0
+    return np.clip(np.rint(z), -127, 127).astype(np.int8)
+
+
 def make_model(cfg, n_blocks=None):
     n_blocks = cfg["L"] if n_blocks is None else n_blocks
     return [make_block(cfg, l) for l in range(n_blocks)]

@@ -567,3 +567,138 @@ def test_shiftexp_is_zero_beyond_a_1024_entry_table_wherever_a_masked_key_can_la
             continue
         pts = np.unique(np.concatenate([np.arange(lo, min(hi, lo + 3000) + 1), np.linspace(lo, hi, 200).astype(np.int64), [hi]]))
         assert orc.shiftexp_vec(-pts, i0, n).max() == 0, i0
+
+
+# ------------------------------------------------------------------ windowed models: window / stage structure
+def test_window_partition_and_reverse_by_explicit_loops():
+    rng = np.random.default_rng(21)
+    B, g, w, C = 2, 8, 4, 3
+    x = rng.integers(-127, 128, size=(B, g, g, C)).astype(np.int8)
+    xw = orc.window_partition(x, w)
+    n = g // w
+    assert xw.shape == (B * n * n, w * w, C)
+    for b in range(B):
+        for wy in range(n):
+            for wx in range(n):
+                for iy in range(w):
+                    for ix in range(w):
+                        assert np.array_equal(xw[(b * n + wy) * n + wx, iy * w + ix], x[b, wy * w + iy, wx * w + ix])
+    assert np.array_equal(orc.window_reverse(xw, w, g), x)
+
+
+@pytest.mark.parametrize("g,w,s", [(8, 4, 2), (14, 7, 3), (56, 7, 3)])
+def test_shift_mask_separates_exactly_the_tokens_the_cyclic_shift_wrapped(g, w, s):
+    """A token at position y of the shifted image came from (y + s) mod g: it wrapped iff y + s >= g.  Two tokens of a
+    window may attend to each other iff neither or both wrapped, per axis."""
+    m = orc.shift_mask(g, w, s)
+    n = g // w
+    assert m.shape == (n * n, w * w, w * w)
+    for wy in range(n):
+        for wx in range(n):
+            ys = np.repeat(np.arange(w) + wy * w, w)
+            xs = np.tile(np.arange(w) + wx * w, w)
+            wrapped = np.stack([ys + s >= g, xs + s >= g], 1)
+            want = (wrapped[:, None, :] != wrapped[None, :, :]).any(-1).astype(np.int8)
+            assert np.array_equal(m[wy * n + wx], want), (wy, wx)
+    if (g, w, s) == (56, 7, 3):
+        assert np.array_equal(m, synth.make_shift_mask(7, 3, 8))      # the generator's table, written another way
+
+
+def _tiny_swin_block(seed=5, C=32, H=1, T=16):
+    return synth.make_block(dict(T=T, C=C, H=H, F=4 * C, seed=seed, i0="fixed", rel_bias=True), 0)
+
+
+def test_swin_block_with_one_window_is_the_plain_encoder_block():
+    p = _tiny_swin_block()
+    rng = np.random.default_rng(22)
+    B, g = 3, 4
+    x = synth.quantize_act(rng.standard_normal((B, g, g, 32)))
+    y = orc.swin_block(x, p, g, window=4, shift=0, H=1)
+    want = orc.encoder_block(x.reshape(B * 16, 32), p, dict(B=B, T=16, C=32, H=1, F=128))
+    assert np.array_equal(y.reshape(B * 16, 32), want)
+
+
+@pytest.mark.parametrize("shift", [0, 2])
+def test_swin_block_equals_the_encoder_block_on_explicitly_gathered_windows(shift):
+    """Everything but attention acts on single tokens, so the block equals: gather tokens window by window (index
+    table built by loops from the definition of the cyclic shift), run the plain block with the mask, scatter back."""
+    p = _tiny_swin_block(seed=6)
+    rng = np.random.default_rng(23)
+    B, g, w, C = 2, 8, 4, 32
+    n = g // w
+    x = synth.quantize_act(rng.standard_normal((B, g, g, C)))
+    idx = np.empty((B, n * n, w * w), np.int64)
+    for b in range(B):
+        for wy in range(n):
+            for wx in range(n):
+                for iy in range(w):
+                    for ix in range(w):
+                        sy, sx = (wy * w + iy + shift) % g, (wx * w + ix + shift) % g    # where the shifted image took it from
+                        idx[b, wy * n + wx, iy * w + ix] = (b * g + sy) * g + sx
+    flat = x.reshape(-1, C)
+    q = dict(p)
+    if shift:
+        q["attn_mask"] = orc.shift_mask(g, w, shift)
+    yw = orc.encoder_block(flat[idx.reshape(-1)], q, dict(B=B * n * n, T=w * w, C=C, H=1, F=4 * C))
+    want = np.empty_like(flat)
+    want[idx.reshape(-1)] = yw
+    got = orc.swin_block(x, p, g, w, shift, H=1).reshape(-1, C)
+    assert np.array_equal(got, want)
+    if shift:       # and the mask matters: without it the result differs
+        q.pop("attn_mask")
+        assert not np.array_equal(orc.encoder_block(flat[idx.reshape(-1)], q, dict(B=B * n * n, T=w * w, C=C, H=1, F=4 * C)), yw)
+
+
+def test_patch_merge_concatenation_order_by_loops():
+    rng = np.random.default_rng(24)
+    B, g, C = 2, 4, 8
+    x = rng.integers(-127, 128, size=(B, g, g, C)).astype(np.int8)
+    (w, _b, rq_b, rq_c) = synth.make_linear(31, 2 * C, 4 * C)
+    gq = rng.integers(200, 300, size=4 * C).astype(np.int32)
+    bq = rng.integers(-2 ** 17, 2 ** 17, size=4 * C).astype(np.int32)
+    m = dict(ln_gamma=gq, ln_beta=bq, f_bits=16, c_shift=19, w=w, rq_b=rq_b, rq_c=rq_c)
+    y = orc.patch_merge(x, m)
+    assert y.shape == (B, g // 2, g // 2, 2 * C)
+    for b in range(B):
+        for yy in range(g // 2):
+            for xx in range(g // 2):
+                row = np.concatenate([x[b, 2 * yy, 2 * xx], x[b, 2 * yy + 1, 2 * xx], x[b, 2 * yy, 2 * xx + 1],
+                                      x[b, 2 * yy + 1, 2 * xx + 1]])[None]
+                u = orc.ilayernorm(row, gq, bq, 16, 19)
+                assert np.array_equal(y[b, yy, xx], orc.linear_requant(u, w, None, rq_b, rq_c)[0])
+
+
+def test_mean_pool_is_the_rounded_scaled_token_sum():
+    rng = np.random.default_rng(25)
+    B, T, C = 3, 49, 16
+    x = rng.integers(-127, 128, size=(B, T, C)).astype(np.int8)
+    c = 20
+    b = round(2 ** c / T)
+    got = orc.mean_pool(x, (b, c))
+    s = x.astype(np.int64).sum(1)
+    want = [[max(-127, min(127, round_half_up(Fraction(int(v) * b, 2 ** c)))) for v in row] for row in s]
+    assert got.tolist() == want
+    assert np.abs(got - x.astype(np.float64).mean(1)).max() <= 0.5 + 127 * T * abs(b / 2 ** c - 1 / T) + 1e-9
+    const = np.full((1, T, C), 77, np.int8)
+    assert (orc.mean_pool(const, (b, c)) == 77).all()
+    assert (orc.mean_pool(const, (2 * b, c)) == 127).all()          # clamps
+
+
+def test_swin_forward_chains_the_stages_and_images_are_independent():
+    cfg = synth.SWIN["swin_tiny_test"]
+    m = synth.make_swin_model(cfg)
+    x = synth.make_swin_patches(cfg)
+    logits, outs, pooled = orc.swin_forward(x, m, want_stages=True)
+    g0 = cfg["grid"]
+    assert [o.shape for o in outs] == [(2 * 256, 32), (2 * 64, 64), (2 * 16, 128)]
+    assert [[p["shift"] for p in st["blocks"]] for st in m["stages"]] == [[0, 2], [0, 2], [0, 0]]
+    one = orc.swin_forward(x[g0 * g0:], m)
+    assert np.array_equal(one, logits[1:])
+    # the last steps by hand from the last stage's output
+    f = m["final_ln"]
+    z = orc.ilayernorm(outs[-1], f["gamma"], f["beta"], f["f_bits"], f["c_shift"]).reshape(2, 16, 128)
+    assert np.array_equal(pooled, orc.mean_pool(z, m["pool_rq"]))
+    hd = m["head"]
+    assert np.array_equal(logits, orc.linear_requant(pooled, hd["w"], hd["bias"], hd["rq_b"], hd["rq_c"]))
+    for o in outs:
+        assert 4.0 < o.std() < 90.0 and (np.abs(o) == 127).mean() < 0.2
