@@ -84,6 +84,9 @@ typedef struct {
     const int8_t  *attn_mask;             /* nullable, [n_mask, T, T]: mask of shifted-window attention, see
                                              ivit_attention_masked                                       */
     int32_t        n_mask;                /* window b uses attn_mask[b % n_mask]; ignored without a mask  */
+    const int32_t *tok_index;             /* nullable, [n_win, T]: the tokens stay in image order and attention
+                                             gathers its windows through this table, see ivit_window_attention */
+    int32_t        n_win;                 /* windows per image; ignored without a table                   */
 } ivit_block_params;
 
 /* Optional device buffers that receive every intermediate int8 tensor of a block
@@ -142,7 +145,7 @@ int ivit_shiftgelu_raw(void* stream, const int8_t* x, int16_t* y16, int64_t n, i
  *   std  = max(1, tenth iterate of I <- (I + floor(var / I)) >> 1 from I = 2^floor(bitlen(var)/2));
  *   f = floor(2^f_bits / std);  y = clamp8(round((x - mean) * f * gamma_q[i] + beta_q[i], c_shift)).
  * gamma_q, beta_q [C] int32 carry the output scale (folded by the host).
- * Requirements: rows >= 0, 4 <= C <= 1024, C % 4 == 0, 1 <= f_bits <= 20, 1 <= c_shift <= 31,
+ * Requirements: rows >= 0, 4 <= C <= 2048, C % 4 == 0, 1 <= f_bits <= 20, 1 <= c_shift <= 31,
  * x and y 4-byte aligned; |gamma_q| < 2^15 and |(x - mean) * f * gamma_q + beta_q| < 2^31 - 2^(c_shift-1)
  * (a precondition on device data; otherwise the result wraps modulo 2^32).
  * Errors: NULL, SHAPE, PARAM, ALIGN, HIP. */
@@ -190,11 +193,24 @@ int ivit_attention_masked(void* stream, const int8_t* qkv, const int8_t* rel_bia
                           int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq, ivit_shift_params softmax,
                           ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs);
 
+/* Windowed attention on tokens that stay in image order (the windowed models of Table 1: every step of a block but
+ * attention acts on single tokens, so the cyclic shift and the window partition of those models reduce to WHICH
+ * rows attention reads and writes).  d->B counts windows, n_win of them per image, d->T tokens per window; image
+ * m owns rows [m * n_win * T, (m + 1) * n_win * T) of qkv and o, and token t of its window w is row
+ * m * n_win * T + tok_index[w * T + t].  tok_index int32 [n_win, T] (device) should be a permutation of
+ * 0 .. n_win * T - 1; entries outside that range are clamped into it (never a fault), and repeated entries make
+ * windows overwrite each other's output rows.  With tok_index == NULL this is ivit_attention_masked.  The taps
+ * stay window-major [B, H, T, T].  A table requires rel_bias (NULL), n_win >= 1 dividing d->B (SHAPE). */
+int ivit_window_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
+                          const int32_t* tok_index, int32_t n_win, int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq,
+                          ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs);
+
 /* Per-launch timing for benchmarks.  Between ivit_trace_begin and ivit_trace_end every kernel launch the
  * library makes (from any entry point, on any stream) is bracketed by two HIP events recorded on the stream
  * of the launch.  ivit_trace_end waits for the recorded events, then fills the HOST arrays (each nullable,
  * `capacity` entries) with, per launch in launch order: elapsed milliseconds, kind (1 I-LayerNorm, 2 Dense,
- * 3 Dense + residual, 4 Dense + ShiftGELU, 5 attention, 6 Shiftmax, 7 ShiftGELU, 8 token assembly), algorithmic integer
+ * 3 Dense + residual, 4 Dense + ShiftGELU, 5 attention, 6 Shiftmax, 7 ShiftGELU, 8 token assembly, 9 patch-merging
+ * gather, 10 mean pooling), algorithmic integer
  * operations (2 per int8 multiply-accumulate; 0 for row-wise kernels) and algorithmic HBM bytes (each
  * operand read once, each result written once); *count receives the number of launches seen.
  * One trace at a time per process, not thread-safe; launches beyond max_launches make ivit_trace_end
@@ -248,6 +264,66 @@ size_t ivit_image_workspace_bytes(const ivit_dims* d);
 int ivit_forward_image(void* stream, const int8_t* patches, int8_t* logits, const ivit_image_params* ip,
                        const ivit_block_params* blocks, int32_t n_blocks, const ivit_final_ln* final_ln,
                        const ivit_dims* d, void* workspace, size_t workspace_bytes);
+
+/* ---- Hierarchical windowed models (the Swin rows of Table 1).  The paper names the models and gives no equations for
+ * their structure; what is implemented is the published Swin Transformer layout with every operator replaced by the
+ * integer one of Sec. 3: tokens of an image stay in raster order [B, g, g, C]; a block attends inside window x window
+ * windows of the image shifted cyclically by -shift (ivit_window_attention with the tables below); between stages
+ * patch merging halves the grid and doubles the width; the head reads the average of the final tokens. ------------- */
+
+/* Concatenation step of patch merging: y[b, i, j, :] = x[b, 2i, 2j, :] | x[b, 2i+1, 2j, :] | x[b, 2i, 2j+1, :] |
+ * x[b, 2i+1, 2j+1, :].  x int8 [B, g, g, C], y int8 [B, g/2, g/2, 4C], both 16-byte aligned; g even, C % 16 == 0.
+ * (I-LayerNorm over 4C and a Dense layer without bias follow: ivit_ilayernorm, ivit_linear_requant.)
+ * Errors: NULL, SHAPE, ALIGN, HIP. */
+int ivit_patch_merge_gather(void* stream, const int8_t* x, int8_t* y, int32_t B, int32_t g, int32_t C);
+
+/* Average pooling as a dyadic rescale of the token sum (the factor 1 / T is part of b / 2^c, Sec. 3.2):
+ * y[b, c] = requant(sum_t x[b, t, c]; rq).  x int8 [B, T, C], y int8 [B, C], 4-byte aligned; C % 4 == 0, T <= 2^24.
+ * Errors: NULL, SHAPE, PARAM, ALIGN, HIP. */
+int ivit_mean_pool(void* stream, const int8_t* x, int8_t* y, int32_t B, int32_t T, int32_t C, ivit_dyadic rq);
+
+/* Host helpers (HOST pointers, nothing is launched).  Token-index table [n_win, T] and mask [n_win, T, T] of
+ * (shifted-)window attention on a g x g raster grid, n_win = (g / window)^2, T = window^2: the image is shifted by
+ * -shift along both axes and cut into windows in raster order; index[w][t] is the raster position in the unshifted
+ * image of token t of window w; mask[w][i][j] = 1 where tokens i and j of window w come from parts of the image
+ * that the shift brought together (all 0 for shift == 0).  g % window == 0, 0 <= shift < window.
+ * Errors: NULL, SHAPE, PARAM. */
+int ivit_swin_window_index(int32_t g, int32_t window, int32_t shift, int32_t* index);
+int ivit_swin_shift_mask(int32_t g, int32_t window, int32_t shift, int8_t* mask);
+
+/* One stage: n_blocks blocks of width C (H heads, MLP width F); every stage but the first starts with patch merging
+ * (I-LayerNorm merge_ln over 4 C_prev = 2 C channels, Dense w_merge [C, 4 C_prev] without bias).  Blocks of a
+ * stage with more than one window per image must carry tok_index / n_win (and attn_mask / n_mask when shifted). */
+typedef struct {
+    int32_t C, H, F, n_blocks;
+    const ivit_block_params* blocks;      /* host array [n_blocks]                                   */
+    ivit_final_ln merge_ln;               /* unused (zero) in the first stage                        */
+    const int8_t* w_merge;                /* [C, 4 C_prev]                                           */
+    const int32_t *merge_rq_b, *merge_rq_c;   /* [C]                                                 */
+} ivit_swin_stage;
+
+typedef struct {
+    int32_t grid, window;                 /* tokens per image side after the embedding; per window side (<= 16)  */
+    int32_t n_stages;                     /* 1..4; stage s works on a grid of grid / 2^s                        */
+    int32_t patch_dim, n_classes;
+    const int8_t* w_patch;  const int32_t *bias_patch /*nullable*/, *patch_rq_b, *patch_rq_c;   /* [C0, patch_dim] */
+    ivit_final_ln embed_ln;               /* I-LayerNorm after the patch Dense                                   */
+    ivit_swin_stage stages[4];
+    ivit_final_ln final_ln;
+    ivit_dyadic pool_rq;
+    const int8_t* w_head;   const int32_t *bias_head /*nullable*/, *head_rq_b, *head_rq_c;      /* [n_classes, C_last] */
+} ivit_swin_params;
+
+/* Workspace of ivit_forward_swin for B images (0 if the parameters are invalid). */
+size_t ivit_swin_workspace_bytes(const ivit_swin_params* p, int32_t B);
+
+/* Patches in, logits out.  patches int8 [B * grid^2, patch_dim] in raster order, logits int8 [B, n_classes], both
+ * 16-byte aligned; workspace 256-byte aligned.  Everything the host can check is checked before the first launch.
+ * Errors: those of the parts; SHAPE also for a grid the windows or the merging do not divide, a stage whose width is
+ * not twice the previous one, or tables whose window count differs from the stage's; NULL for a multi-window stage
+ * without tok_index. */
+int ivit_forward_swin(void* stream, const int8_t* patches, int8_t* logits, const ivit_swin_params* p, int32_t B,
+                      void* workspace, size_t workspace_bytes);
 
 /* ---- Host helpers: the floating-point side of a quantised model -> the integers this library takes. --------
  * Pure host code on HOST pointers; nothing is launched.  They realise Sec. 3.1 Eq. 6 (symmetric uniform

@@ -18,10 +18,12 @@ EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftg
            "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward",
            "ivit_trace_begin", "ivit_trace_end", "ivit_quantize_symmetric", "ivit_dyadic_from_float",
            "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
-           "ivit_forward_image", "ivit_attention_masked")
+           "ivit_forward_image", "ivit_attention_masked", "ivit_window_attention", "ivit_patch_merge_gather",
+           "ivit_mean_pool", "ivit_swin_window_index", "ivit_swin_shift_mask", "ivit_swin_workspace_bytes",
+           "ivit_forward_swin")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
-              7: "shiftgelu", 8: "embed_tokens"}
+              7: "shiftgelu", 8: "embed_tokens", 9: "patch_merge_gather", 10: "mean_pool"}
 
 
 class ShiftParams(C.Structure):
@@ -49,7 +51,7 @@ class BlockParams(C.Structure):
         ("w_fc1", _P), ("bias_fc1", _P), ("fc1_rq_b", _P), ("fc1_rq_c", _P),
         ("gelu", ShiftParams), ("gelu_rq", Dyadic),
         ("w_fc2", _P), ("bias_fc2", _P), ("fc2_rq_b", _P), ("fc2_rq_c", _P), ("res2_rq", Dyadic),
-        ("attn_mask", _P), ("n_mask", C.c_int32),
+        ("attn_mask", _P), ("n_mask", C.c_int32), ("tok_index", _P), ("n_win", C.c_int32),
     ]
 
 
@@ -68,6 +70,19 @@ class ImageParams(C.Structure):
 
 class FinalLN(C.Structure):
     _fields_ = [("gamma", _P), ("beta", _P), ("f_bits", C.c_int32), ("c_shift", C.c_int32)]
+
+
+class SwinStage(C.Structure):
+    _fields_ = [("C", C.c_int32), ("H", C.c_int32), ("F", C.c_int32), ("n_blocks", C.c_int32),
+                ("blocks", C.POINTER(BlockParams)), ("merge_ln", FinalLN), ("w_merge", _P), ("merge_rq_b", _P),
+                ("merge_rq_c", _P)]
+
+
+class SwinParams(C.Structure):
+    _fields_ = [("grid", C.c_int32), ("window", C.c_int32), ("n_stages", C.c_int32), ("patch_dim", C.c_int32),
+                ("n_classes", C.c_int32), ("w_patch", _P), ("bias_patch", _P), ("patch_rq_b", _P), ("patch_rq_c", _P),
+                ("embed_ln", FinalLN), ("stages", SwinStage * 4), ("final_ln", FinalLN), ("pool_rq", Dyadic),
+                ("w_head", _P), ("bias_head", _P), ("head_rq_b", _P), ("head_rq_c", _P)]
 
 
 class IvitError(RuntimeError):
@@ -101,6 +116,15 @@ def load():
     lib.ivit_attention.argtypes = [_P, _P, _P, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
     lib.ivit_attention_masked.restype = C.c_int
     lib.ivit_attention_masked.argtypes = [_P, _P, _P, _P, i32, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
+    lib.ivit_window_attention.restype = C.c_int
+    lib.ivit_window_attention.argtypes = [_P, _P, _P, _P, i32, _P, i32, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
+    lib.ivit_patch_merge_gather.restype = C.c_int; lib.ivit_patch_merge_gather.argtypes = [_P, _P, _P, i32, i32, i32]
+    lib.ivit_mean_pool.restype = C.c_int; lib.ivit_mean_pool.argtypes = [_P, _P, _P, i32, i32, i32, Dyadic]
+    lib.ivit_swin_window_index.restype = C.c_int; lib.ivit_swin_window_index.argtypes = [i32, i32, i32, _P]
+    lib.ivit_swin_shift_mask.restype = C.c_int; lib.ivit_swin_shift_mask.argtypes = [i32, i32, i32, _P]
+    lib.ivit_swin_workspace_bytes.restype = C.c_size_t; lib.ivit_swin_workspace_bytes.argtypes = [C.POINTER(SwinParams), i32]
+    lib.ivit_forward_swin.restype = C.c_int
+    lib.ivit_forward_swin.argtypes = [_P, _P, _P, C.POINTER(SwinParams), i32, _P, C.c_size_t]
     lib.ivit_encoder_block.restype = C.c_int
     lib.ivit_encoder_block.argtypes = [_P, _P, _P, C.POINTER(BlockParams), C.POINTER(Dims), _P, C.c_size_t,
                                        C.POINTER(DebugTaps)]
@@ -282,6 +306,9 @@ def block_params(p):
     m = p.get("attn_mask")
     bp.attn_mask = _ptr(m)
     bp.n_mask = 1 if m is None else int(m.shape[0])
+    ti = p.get("tok_index")
+    bp.tok_index = _ptr(ti)
+    bp.n_win = 1 if ti is None else int(ti.shape[0])
     return bp
 
 
@@ -351,4 +378,107 @@ def ivit_forward_image(patches, logits, image, blocks, d, workspace, final_ln, s
     st = load().ivit_forward_image(_stream(stream), _ptr(patches), _ptr(logits), C.byref(ip), arr, len(blocks), C.byref(fl),
                                    C.byref(dims(d)), _ptr(workspace), workspace.numel() * workspace.element_size())
     _check(st, "ivit_forward_image")
+    return logits
+
+
+def ivit_window_attention(qkv, o, d, qk_rq, softmax, pv_rq, rel_bias, tok_index, mask=None, tap_scores=None, tap_probs=None,
+                          stream=None):
+    """tok_index: int32 CUDA tensor [n_win, T]; mask: None or int8 [n_mask, T, T]."""
+    st = load().ivit_window_attention(_stream(stream), _ptr(qkv), _ptr(rel_bias), _ptr(mask),
+                                      1 if mask is None else int(mask.shape[0]), _ptr(tok_index),
+                                      1 if tok_index is None else int(tok_index.shape[0]), _ptr(o), C.byref(dims(d)),
+                                      dyadic(qk_rq), shift_params(softmax), dyadic(pv_rq), _ptr(tap_scores), _ptr(tap_probs))
+    _check(st, "ivit_window_attention")
+    return o
+
+
+def ivit_patch_merge_gather(x, y, B, g, Cc, stream=None):
+    _check(load().ivit_patch_merge_gather(_stream(stream), _ptr(x), _ptr(y), int(B), int(g), int(Cc)), "ivit_patch_merge_gather")
+    return y
+
+
+def ivit_mean_pool(x, y, B, T, Cc, rq, stream=None):
+    _check(load().ivit_mean_pool(_stream(stream), _ptr(x), _ptr(y), int(B), int(T), int(Cc), dyadic(rq)), "ivit_mean_pool")
+    return y
+
+
+def ivit_swin_window_index(g, window, shift):
+    """Host helper: numpy int32 [(g / window)^2, window^2]."""
+    import numpy as np
+    out = np.empty(((g // max(window, 1)) ** 2 if window > 0 else 0, window * window), np.int32)
+    _check(load().ivit_swin_window_index(int(g), int(window), int(shift), out.ctypes.data), "ivit_swin_window_index")
+    return out
+
+
+def ivit_swin_shift_mask(g, window, shift):
+    """Host helper: numpy int8 [(g / window)^2, window^2, window^2]."""
+    import numpy as np
+    T = window * window
+    out = np.empty(((g // max(window, 1)) ** 2 if window > 0 else 0, T, T), np.int8)
+    _check(load().ivit_swin_shift_mask(int(g), int(window), int(shift), out.ctypes.data), "ivit_swin_shift_mask")
+    return out
+
+
+def swin_to_device(model, device="cuda"):
+    """Uploads a windowed model (dict as the synthetic generator makes it) and attaches to every block the token-index
+    table and, for shifted blocks, the mask of its stage, built by the library's host helpers."""
+    import torch
+    up = lambda a: torch.from_numpy(a).to(device)
+    m = {k: v for k, v in model.items() if k not in ("embed", "stages", "final_ln", "head")}
+    for k in ("embed", "final_ln", "head"):
+        m[k] = to_device(model[k], device)
+    m["stages"] = []
+    tables = {}
+    for st in model["stages"]:
+        g, window = st["grid"], model["window"]
+        blocks = []
+        for p in st["blocks"]:
+            q = to_device({k: v for k, v in p.items() if k != "shift"}, device)
+            if g > window:
+                key = (g, p["shift"])
+                if key not in tables:
+                    tables[key] = (up(ivit_swin_window_index(g, window, p["shift"])),
+                                   up(ivit_swin_shift_mask(g, window, p["shift"])) if p["shift"] else None)
+                q["tok_index"], q["attn_mask"] = tables[key]
+            blocks.append(q)
+        m["stages"].append(dict(C=st["C"], H=st["H"], grid=g, blocks=blocks,
+                                merge=None if st["merge"] is None else to_device(st["merge"], device)))
+    return m
+
+
+def swin_params(m):
+    """SwinParams struct from a device model (swin_to_device); returns (struct, keep-alive list)."""
+    sp_ = SwinParams()
+    keep = []
+    sp_.grid, sp_.window, sp_.n_stages = int(m["grid"]), int(m["window"]), len(m["stages"])
+    sp_.patch_dim, sp_.n_classes = int(m["patch_dim"]), int(m["n_classes"])
+    e = m["embed"]
+    sp_.w_patch, sp_.bias_patch, sp_.patch_rq_b, sp_.patch_rq_c = _ptr(e["w"]), _ptr(e["bias"]), _ptr(e["rq_b"]), _ptr(e["rq_c"])
+    sp_.embed_ln = FinalLN(_ptr(e["ln_gamma"]), _ptr(e["ln_beta"]), int(e["f_bits"]), int(e["c_shift"]))
+    for i, st in enumerate(m["stages"]):
+        sg = sp_.stages[i]
+        sg.C, sg.H, sg.F, sg.n_blocks = int(st["C"]), int(st["H"]), 4 * int(st["C"]), len(st["blocks"])
+        arr = (BlockParams * max(1, len(st["blocks"])))(*[block_params(p) for p in st["blocks"]])
+        keep.append(arr)
+        sg.blocks = arr
+        mg = st["merge"]
+        if mg is not None:
+            sg.merge_ln = FinalLN(_ptr(mg["ln_gamma"]), _ptr(mg["ln_beta"]), int(mg["f_bits"]), int(mg["c_shift"]))
+            sg.w_merge, sg.merge_rq_b, sg.merge_rq_c = _ptr(mg["w"]), _ptr(mg["rq_b"]), _ptr(mg["rq_c"])
+    f = m["final_ln"]
+    sp_.final_ln = FinalLN(_ptr(f["gamma"]), _ptr(f["beta"]), int(f["f_bits"]), int(f["c_shift"]))
+    sp_.pool_rq = dyadic(m["pool_rq"])
+    h = m["head"]
+    sp_.w_head, sp_.bias_head, sp_.head_rq_b, sp_.head_rq_c = _ptr(h["w"]), _ptr(h["bias"]), _ptr(h["rq_b"]), _ptr(h["rq_c"])
+    return sp_, keep
+
+
+def ivit_swin_workspace_bytes(params, B):
+    return int(load().ivit_swin_workspace_bytes(C.byref(params), int(B)))
+
+
+def ivit_forward_swin(patches, logits, params, B, workspace, stream=None):
+    st = load().ivit_forward_swin(_stream(stream), _ptr(patches), _ptr(logits), C.byref(params), int(B), _ptr(workspace),
+                                  workspace.numel() * workspace.element_size())
+    _check(st, "ivit_forward_swin")
     return logits

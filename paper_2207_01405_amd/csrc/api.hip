@@ -2,6 +2,7 @@
 // one encoder block (I-ViT, arXiv 2207.01405, Eq. 1-5) and of the block stack.  See include/ivit.h.
 #include "../../include/ivit.h"
 
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 
@@ -25,7 +26,7 @@ inline int check_shift(const ivit_shift_params& p) {
 }
 
 inline int check_ln(int32_t C, int32_t f_bits, int32_t c_shift) {
-    if (C < 4 || C > 1024 || (C & 3)) return IVIT_ERR_SHAPE;
+    if (C < 4 || C > 2048 || (C & 3)) return IVIT_ERR_SHAPE;
     if (f_bits < 1 || f_bits > 20 || c_shift < 1 || c_shift > 31) return IVIT_ERR_PARAM;
     return IVIT_OK;
 }
@@ -46,6 +47,16 @@ int check_dims(const ivit_dims* d) {
     if (hd != 32 && hd != 64) return IVIT_ERR_SHAPE;
     if ((d->C & 15) || (d->F & 15) || d->C > 1024 || d->F > 65536) return IVIT_ERR_SHAPE;
     if ((int64_t)d->B * d->T > 0x7fffffffLL) return IVIT_ERR_SHAPE;
+    return IVIT_OK;
+}
+
+// A token-index table needs the relative-position bias (the gathering kernels are the windowed ones) and a
+// window count that divides the number of windows.
+int check_tok_index(const int32_t* tok_index, int32_t n_win, const int8_t* rel_bias, const ivit_dims* d) {
+    if (!tok_index) return IVIT_OK;
+    if (!rel_bias) return IVIT_ERR_NULL;
+    if (n_win < 1 || d->B % n_win != 0 || (int64_t)n_win * d->T > 0x7fffffffLL) return IVIT_ERR_SHAPE;
+    if (!aligned(tok_index, 4)) return IVIT_ERR_ALIGN;
     return IVIT_OK;
 }
 
@@ -78,6 +89,7 @@ int check_block(const ivit_block_params* p, const ivit_dims* d) {
         return st;
     if ((st = check_shift(p->softmax)) != IVIT_OK || (st = check_shift(p->gelu)) != IVIT_OK) return st;
     if (p->attn_mask && p->n_mask < 1) return IVIT_ERR_SHAPE;
+    if ((st = check_tok_index(p->tok_index, p->n_win, p->rel_bias, d)) != IVIT_OK) return st;
     if (!aligned(p->w_qkv, 16) || !aligned(p->w_proj, 16) || !aligned(p->w_fc1, 16) || !aligned(p->w_fc2, 16))
         return IVIT_ERR_ALIGN;
     const void* i32s[] = {p->ln1_gamma, p->ln1_beta, p->bias_qkv, p->qkv_rq_b, p->qkv_rq_c, p->bias_proj, p->proj_rq_b,
@@ -111,6 +123,7 @@ hipError_t run_block(hipStream_t s, const int8_t* x, int8_t* y, const ivit_block
     ivit::AttentionArgs aa{};
     aa.qkv = w.qkv; aa.rel_bias = p->rel_bias; aa.o = w.o; aa.B = d->B; aa.T = d->T; aa.C = C; aa.H = d->H;
     aa.mask = p->attn_mask; aa.n_mask = p->attn_mask ? p->n_mask : 1;
+    aa.tok_index = p->tok_index; aa.n_win = p->tok_index ? p->n_win : 1;
     aa.qk_rq = dy(p->qk_rq); aa.sm = sp(p->softmax); aa.pv_rq = dy(p->pv_rq);
     aa.tap_scores = taps ? taps->scores : nullptr; aa.tap_probs = taps ? taps->probs : nullptr;
     if ((e = ivit::launch_attention(s, aa))) return e;
@@ -229,10 +242,18 @@ int ivit_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, int8
 int ivit_attention_masked(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
                           int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq, ivit_shift_params softmax,
                           ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs) {
+    return ivit_window_attention(stream, qkv, rel_bias, mask, n_mask, nullptr, 1, o, d, qk_rq, softmax, pv_rq, tap_scores,
+                                 tap_probs);
+}
+
+int ivit_window_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
+                          const int32_t* tok_index, int32_t n_win, int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq,
+                          ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs) {
     if (!d) return IVIT_ERR_NULL;
     if (mask && n_mask < 1) return IVIT_ERR_SHAPE;
     int st;
     if ((st = check_dims(d)) != IVIT_OK) return st;
+    if ((st = check_tok_index(tok_index, n_win, rel_bias, d)) != IVIT_OK) return st;
     if (d->B > 0 && (!qkv || !o)) return IVIT_ERR_NULL;
     if ((st = check_dyadic(qk_rq)) != IVIT_OK || (st = check_dyadic(pv_rq)) != IVIT_OK ||
         (st = check_shift(softmax)) != IVIT_OK)
@@ -241,6 +262,7 @@ int ivit_attention_masked(void* stream, const int8_t* qkv, const int8_t* rel_bia
     ivit::AttentionArgs a{};
     a.qkv = qkv; a.rel_bias = rel_bias; a.o = o; a.B = d->B; a.T = d->T; a.C = d->C; a.H = d->H;
     a.mask = mask; a.n_mask = mask ? n_mask : 1;
+    a.tok_index = tok_index; a.n_win = tok_index ? n_win : 1;
     a.qk_rq = dy(qk_rq); a.sm = sp(softmax); a.pv_rq = dy(pv_rq); a.tap_scores = tap_scores; a.tap_probs = tap_probs;
     return hip_status(ivit::launch_attention(static_cast<hipStream_t>(stream), a));
 }
@@ -351,6 +373,149 @@ int ivit_forward_image(void* stream, const int8_t* patches, int8_t* logits, cons
     if ((st = ivit_forward(stream, tok_in, tok_out, blocks, n_blocks, final_ln, d, inner, workspace_bytes - 3 * act)) != IVIT_OK) return st;
     return ivit_classifier_head(stream, tok_out, d->T, ip->w_head, ip->bias_head, ip->head_rq_b, ip->head_rq_c, logits,
                                 d->B, ip->n_classes, d->C);
+}
+
+int ivit_patch_merge_gather(void* stream, const int8_t* x, int8_t* y, int32_t B, int32_t g, int32_t C) {
+    if (B < 0 || g < 2 || (g & 1) || g > 4096 || C < 16 || (C & 15) || C > 65536) return IVIT_ERR_SHAPE;
+    if (B > 0 && (!x || !y)) return IVIT_ERR_NULL;
+    if (!aligned(x, 16) || !aligned(y, 16)) return IVIT_ERR_ALIGN;
+    return hip_status(ivit::launch_patch_merge_gather(static_cast<hipStream_t>(stream), x, y, B, g, C));
+}
+
+int ivit_mean_pool(void* stream, const int8_t* x, int8_t* y, int32_t B, int32_t T, int32_t C, ivit_dyadic rq) {
+    if (B < 0 || T < 1 || T > (1 << 24) || C < 4 || (C & 3)) return IVIT_ERR_SHAPE;    // |sum| <= 127 T fits int32
+    if (B > 0 && (!x || !y)) return IVIT_ERR_NULL;
+    int st = check_dyadic(rq);
+    if (st != IVIT_OK) return st;
+    if (!aligned(x, 4) || !aligned(y, 4)) return IVIT_ERR_ALIGN;
+    return hip_status(ivit::launch_mean_pool(static_cast<hipStream_t>(stream), x, y, B, T, C, dy(rq)));
+}
+
+}  // extern "C"
+
+// ---- hierarchical windowed model: embedding, stages of blocks with patch merging between them, pooling, head ------
+namespace {
+
+struct SwinPlan {
+    ivit_dims dims[4];       // per stage: B = windows, T = window^2, C, H, F
+    int grid[4];             // tokens per image side in each stage
+    size_t act, inner, pooled, total;
+};
+
+int check_final_ln(const ivit_final_ln& l, int C) {
+    if (!l.gamma || !l.beta) return IVIT_ERR_NULL;
+    int st = check_ln(C, l.f_bits, l.c_shift);
+    if (st != IVIT_OK) return st;
+    return (aligned(l.gamma, 4) && aligned(l.beta, 4)) ? IVIT_OK : IVIT_ERR_ALIGN;
+}
+
+// Validates everything that can be validated on the host and sizes the workspace.
+int plan_swin(const ivit_swin_params* p, int32_t B, SwinPlan* plan) {
+    if (!p) return IVIT_ERR_NULL;
+    if (B < 0 || p->n_stages < 1 || p->n_stages > 4 || p->window < 1 || p->window > 16 || p->grid < p->window ||
+        p->grid > 4096 || p->patch_dim < 16 || (p->patch_dim & 15) || p->n_classes < 1)
+        return IVIT_ERR_SHAPE;
+    if (!p->w_patch || !p->patch_rq_b || !p->patch_rq_c || !p->w_head || !p->head_rq_b || !p->head_rq_c) return IVIT_ERR_NULL;
+    int st;
+    int g = p->grid;
+    size_t act = 0, inner = 0;
+    for (int s = 0; s < p->n_stages; ++s) {
+        const ivit_swin_stage& sg = p->stages[s];
+        if (s > 0) {
+            if (g & 1) return IVIT_ERR_SHAPE;
+            g >>= 1;
+            if (sg.C != 2 * p->stages[s - 1].C) return IVIT_ERR_SHAPE;
+            if (!sg.w_merge || !sg.merge_rq_b || !sg.merge_rq_c) return IVIT_ERR_NULL;
+            if ((st = check_final_ln(sg.merge_ln, 2 * sg.C)) != IVIT_OK) return st;       // over 4 C of the previous stage
+            if (!aligned(sg.w_merge, 16) || !aligned(sg.merge_rq_b, 4) || !aligned(sg.merge_rq_c, 4)) return IVIT_ERR_ALIGN;
+        }
+        if (g % p->window != 0 || sg.n_blocks < 0 || (sg.n_blocks > 0 && !sg.blocks)) return IVIT_ERR_SHAPE;
+        const int64_t n_win = (int64_t)(g / p->window) * (g / p->window);
+        if ((int64_t)B * n_win > 0x7fffffffLL) return IVIT_ERR_SHAPE;
+        ivit_dims d{(int32_t)(B * n_win), p->window * p->window, sg.C, sg.H, sg.F};
+        if (sg.H < 1 || (st = check_dims(&d)) != IVIT_OK) return st;
+        for (int l = 0; l < sg.n_blocks; ++l) {
+            const ivit_block_params& bp = sg.blocks[l];
+            if ((st = check_block(&bp, &d)) != IVIT_OK) return st;
+            // with more than one window per image the tokens (kept in image order) must be gathered into windows
+            if (n_win > 1 && (!bp.tok_index || bp.n_win != n_win)) return bp.tok_index ? IVIT_ERR_SHAPE : IVIT_ERR_NULL;
+            if (bp.tok_index && bp.n_win != n_win) return IVIT_ERR_SHAPE;
+            if (bp.attn_mask && bp.n_mask != n_win) return IVIT_ERR_SHAPE;
+        }
+        plan->dims[s] = d;
+        plan->grid[s] = g;
+        act = std::max(act, up256((size_t)B * g * g * sg.C));
+        inner = std::max(inner, ivit_workspace_bytes(&d));
+    }
+    if ((st = check_final_ln(p->embed_ln, p->stages[0].C)) != IVIT_OK) return st;
+    if ((st = check_final_ln(p->final_ln, p->stages[p->n_stages - 1].C)) != IVIT_OK) return st;
+    if ((st = check_dyadic(p->pool_rq)) != IVIT_OK) return st;
+    if (!aligned(p->w_patch, 16) || !aligned(p->w_head, 16)) return IVIT_ERR_ALIGN;
+    plan->act = act;
+    plan->inner = inner;
+    plan->pooled = up256((size_t)B * p->stages[p->n_stages - 1].C);
+    plan->total = 4 * act + plan->pooled + inner;
+    return IVIT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t ivit_swin_workspace_bytes(const ivit_swin_params* p, int32_t B) {
+    SwinPlan plan;
+    return plan_swin(p, B, &plan) == IVIT_OK ? plan.total : 0;
+}
+
+int ivit_forward_swin(void* stream, const int8_t* patches, int8_t* logits, const ivit_swin_params* p, int32_t B,
+                      void* workspace, size_t workspace_bytes) {
+    SwinPlan plan;
+    int st = plan_swin(p, B, &plan);
+    if (st != IVIT_OK) return st;
+    if (B > 0 && (!patches || !logits)) return IVIT_ERR_NULL;
+    if (!workspace || workspace_bytes < plan.total) return IVIT_ERR_WORKSPACE;
+    if (!aligned(workspace, 256) || !aligned(patches, 16) || !aligned(logits, 16)) return IVIT_ERR_ALIGN;
+    if (B == 0) return IVIT_OK;
+    int8_t* base = static_cast<int8_t*>(workspace);
+    int8_t* buf[2] = {base, base + plan.act};
+    int8_t* cat = base + 2 * plan.act;
+    int8_t* catn = base + 3 * plan.act;
+    int8_t* pooled = base + 4 * plan.act;
+    void* inner = pooled + plan.pooled;
+    const ivit_dyadic one{1, 1};
+    // embedding: patch Dense, then I-LayerNorm
+    const int g0 = p->grid, C0 = p->stages[0].C;
+    const int64_t R0 = (int64_t)B * g0 * g0;
+    if ((st = ivit_linear_requant(stream, patches, p->w_patch, p->bias_patch, p->patch_rq_b, p->patch_rq_c, nullptr, one,
+                                  nullptr, one, buf[0], R0, C0, p->patch_dim)) != IVIT_OK) return st;
+    if ((st = ivit_ilayernorm(stream, buf[0], p->embed_ln.gamma, p->embed_ln.beta, buf[1], R0, C0, p->embed_ln.f_bits,
+                              p->embed_ln.c_shift)) != IVIT_OK) return st;
+    int cur = 1;
+    for (int s = 0; s < p->n_stages; ++s) {
+        const ivit_swin_stage& sg = p->stages[s];
+        const int g = plan.grid[s];
+        const int64_t R = (int64_t)B * g * g;
+        if (s > 0) {     // patch merging: 2 x 2 concatenation, I-LayerNorm over 4 C_prev = 2 C, Dense to C without bias
+            const int Cp = p->stages[s - 1].C;
+            if ((st = ivit_patch_merge_gather(stream, buf[cur], cat, B, 2 * g, Cp)) != IVIT_OK) return st;
+            if ((st = ivit_ilayernorm(stream, cat, sg.merge_ln.gamma, sg.merge_ln.beta, catn, R, 4 * Cp, sg.merge_ln.f_bits,
+                                      sg.merge_ln.c_shift)) != IVIT_OK) return st;
+            if ((st = ivit_linear_requant(stream, catn, sg.w_merge, nullptr, sg.merge_rq_b, sg.merge_rq_c, nullptr, one,
+                                          nullptr, one, buf[cur ^ 1], R, sg.C, 4 * Cp)) != IVIT_OK) return st;
+            cur ^= 1;
+        }
+        if (sg.n_blocks > 0) {
+            if ((st = ivit_forward(stream, buf[cur], buf[cur ^ 1], sg.blocks, sg.n_blocks, nullptr, &plan.dims[s], inner,
+                                   plan.inner)) != IVIT_OK) return st;
+            cur ^= 1;
+        }
+    }
+    const int sl = p->n_stages - 1, gl = plan.grid[sl], Cl = p->stages[sl].C;
+    if ((st = ivit_ilayernorm(stream, buf[cur], p->final_ln.gamma, p->final_ln.beta, buf[cur ^ 1], (int64_t)B * gl * gl, Cl,
+                              p->final_ln.f_bits, p->final_ln.c_shift)) != IVIT_OK) return st;
+    if ((st = ivit_mean_pool(stream, buf[cur ^ 1], pooled, B, gl * gl, Cl, p->pool_rq)) != IVIT_OK) return st;
+    return ivit_linear_requant(stream, pooled, p->w_head, p->bias_head, p->head_rq_b, p->head_rq_c, nullptr, one, nullptr,
+                               one, logits, B, p->n_classes, Cl);
 }
 
 }  // extern "C"

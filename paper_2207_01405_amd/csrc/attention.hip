@@ -47,6 +47,7 @@ template <int D, int NKT, bool TAPS, bool BIAS, bool MASK, bool FAST>
 __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
                                                         const int8_t* __restrict__ mask, int n_mask,
+                                                        const int32_t* __restrict__ tok_index, int n_win,
                                                         int8_t* __restrict__ o, int n_items, int T, int C, int H,
                                                         Dyadic qk, ShiftParams sm, Dyadic pv,
                                                         int8_t* __restrict__ tap_s, int8_t* __restrict__ tap_p) {
@@ -80,11 +81,20 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
     const int first = xcd * (G / 8) + min(xcd, G % 8) + blockIdx.x / 8;
     for (int item = first; item < n_items; item += G) {
         const int b = item / H, h = item % H;
-        const int8_t* base = qkv + (int64_t)b * T * 3 * C + h * D;
+        const int8_t* base = qkv + h * D;
+        // row of token t of window b in qkv and o: consecutive rows, or (BIAS instances) looked up in the index table
+        // of the window's position inside its image; an entry outside the image is clamped, never followed
+        const int tpi = n_win * T;                 // tokens per image
+        const int32_t* trow = (BIAS && tok_index) ? tok_index + (b % n_win) * T : nullptr;
+        const int64_t row0 = (BIAS && tok_index) ? (int64_t)(b / n_win) * tpi : (int64_t)b * T;
+        auto row_of = [&](int t) -> int64_t {
+            if (BIAS) { if (trow) return row0 + (int)min((uint32_t)trow[t], (uint32_t)(tpi - 1)); }
+            return row0 + t;
+        };
         __syncthreads();                           // table ready / previous item's readers done
         // the query fragment of a tile is requested one tile ahead, the first one together with K and V
-        auto load_q64 = [&](int qt) { return *reinterpret_cast<const v4i*>(base + (int64_t)min(qt * 16 + li, T - 1) * 3 * C + 16 * lg); };
-        auto load_q32 = [&](int qt) { return *reinterpret_cast<const long*>(base + (int64_t)min(qt * 16 + li, T - 1) * 3 * C + 8 * lg); };
+        auto load_q64 = [&](int qt) { return *reinterpret_cast<const v4i*>(base + row_of(min(qt * 16 + li, T - 1)) * 3 * C + 16 * lg); };
+        auto load_q32 = [&](int qt) { return *reinterpret_cast<const long*>(base + row_of(min(qt * 16 + li, T - 1)) * 3 * C + 8 * lg); };
         v4i qn64 = {0, 0, 0, 0};
         long qn32 = 0;
         if (D == 64) qn64 = load_q64(wv); else qn32 = load_q32(wv);
@@ -95,8 +105,9 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
         for (int it = 0; it < NPC; ++it) {
             const int c = tid + ATT_THREADS * it;
             const int key = min(c / DCH, T - 1), part = c % DCH;
-            kreg[it] = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + C + 16 * part);
-            vreg[it] = *reinterpret_cast<const v4i*>(base + (int64_t)key * 3 * C + 2 * C + 16 * part);
+            const int8_t* kv_row = base + row_of(key) * 3 * C + 16 * part;
+            kreg[it] = *reinterpret_cast<const v4i*>(kv_row + C);
+            vreg[it] = *reinterpret_cast<const v4i*>(kv_row + 2 * C);
         }
 #pragma unroll
         for (int it = 0; it < NPC; ++it) {
@@ -273,7 +284,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 ow[n] = w;
             }
             if (q < T) {
-                int8_t* op = o + ((int64_t)b * T + q) * C + h * D + lg * (D / 4);
+                int8_t* op = o + row_of(q) * C + h * D + lg * (D / 4);
                 if (D == 64) *reinterpret_cast<uint4*>(op) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
                 else *reinterpret_cast<uint2*>(op) = make_uint2(ow[0], ow[1 % ND]);
             }
@@ -286,7 +297,7 @@ static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, bool t
     const int n_items = a.B * a.H;
 #define IVIT_ATT(TAPS_, BIAS_, MASK_, FAST_)                                                                       \
     hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, MASK_, FAST_>), dim3(grid), dim3(ATT_THREADS), 0, s, a.qkv, \
-                       a.rel_bias, a.mask, a.n_mask, a.o, n_items, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores,    \
+                       a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores,    \
                        a.tap_probs)
     // the production paths are <no taps, fast>; everything else shares one fully general instantiation per bias / mask
     // combination (a mask is always compiled with the bias code, which tests the bias pointer)
@@ -326,8 +337,8 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     const bool taps = a.tap_scores || a.tap_probs;
     const int64_t R = (int64_t)a.B * a.T;
     TraceScope trace(s, KIND_ATTENTION, 4 * n_items * a.T * a.T * d, 4 * R * a.C + (a.rel_bias ? (int64_t)a.H * a.T * a.T : 0));
-    return d == 64 ? launch_d<64>(s, a, grid, nkt, taps, a.rel_bias != nullptr || a.mask != nullptr, fast)
-                   : launch_d<32>(s, a, grid, nkt, taps, a.rel_bias != nullptr || a.mask != nullptr, fast);
+    const bool bias = a.rel_bias != nullptr || a.mask != nullptr || a.tok_index != nullptr;
+    return d == 64 ? launch_d<64>(s, a, grid, nkt, taps, bias, fast) : launch_d<32>(s, a, grid, nkt, taps, bias, fast);
 }
 
 }  // namespace ivit

@@ -60,4 +60,44 @@ int ivit_shift_params_from_scale(double s, int32_t width, int32_t m_bits, int32_
     return IVIT_OK;
 }
 
+// Token-index table of (shifted-)window attention on a g x g token grid kept in raster order: the image is shifted
+// cyclically by -shift along both axes and cut into window x window windows in raster order; entry [w][t] is the raster
+// position, in the unshifted image, of token t (raster order inside the window) of window w.
+int ivit_swin_window_index(int32_t g, int32_t window, int32_t shift, int32_t* index) {
+    if (g < 1 || window < 1 || g % window != 0 || g > 4096) return IVIT_ERR_SHAPE;
+    if (shift < 0 || shift >= window) return IVIT_ERR_PARAM;
+    if (!index) return IVIT_ERR_NULL;
+    const int n = g / window, T = window * window;
+    for (int wy = 0; wy < n; ++wy)
+        for (int wx = 0; wx < n; ++wx)
+            for (int iy = 0; iy < window; ++iy)
+                for (int ix = 0; ix < window; ++ix) {
+                    const int sy = (wy * window + iy + shift) % g, sx = (wx * window + ix + shift) % g;
+                    index[(wy * n + wx) * T + iy * window + ix] = sy * g + sx;
+                }
+    return IVIT_OK;
+}
+
+// Mask of shifted-window attention for the same layout: along each axis a position p of the shifted image lies in one of
+// three bands (p < g - window: windows the shift did not split; p < g - shift: the part of the last window that did not
+// wrap; else the part that wrapped around); two tokens of a window are masked (1) when their bands differ on either axis.
+int ivit_swin_shift_mask(int32_t g, int32_t window, int32_t shift, int8_t* mask) {
+    if (g < 1 || window < 1 || g % window != 0 || g > 4096) return IVIT_ERR_SHAPE;
+    if (shift < 0 || shift >= window) return IVIT_ERR_PARAM;
+    if (!mask) return IVIT_ERR_NULL;
+    const int n = g / window, T = window * window;
+    auto band = [&](int p) { return p < g - window ? 0 : (p < g - shift ? 1 : 2); };
+    for (int wy = 0; wy < n; ++wy)
+        for (int wx = 0; wx < n; ++wx) {
+            int8_t* m = mask + (int64_t)(wy * n + wx) * T * T;
+            for (int i = 0; i < T; ++i)
+                for (int j = 0; j < T; ++j) {
+                    const int yi = wy * window + i / window, xi = wx * window + i % window;
+                    const int yj = wy * window + j / window, xj = wx * window + j % window;
+                    m[i * T + j] = (band(yi) != band(yj) || band(xi) != band(xj)) ? 1 : 0;
+                }
+        }
+    return IVIT_OK;
+}
+
 }  // extern "C"

@@ -28,9 +28,13 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a);
 hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos, Dyadic tok_rq,
                                Dyadic pos_rq, int8_t* tokens, int B, int P, int C);
 
+hipError_t launch_patch_merge_gather(hipStream_t s, const int8_t* x, int8_t* y, int B, int g, int C);
+hipError_t launch_mean_pool(hipStream_t s, const int8_t* x, int8_t* y, int B, int T, int C, Dyadic rq);
+
 struct AttentionArgs {
     const int8_t* qkv; const int8_t* rel_bias; int8_t* o;
     const int8_t* mask; int n_mask;      // shifted-window mask [n_mask, T, T] or nullptr
+    const int32_t* tok_index; int n_win; // rows of the tokens of the n_win windows of an image [n_win, T], or nullptr
     int B, T, C, H;
     Dyadic qk_rq; ShiftParams sm; Dyadic pv_rq;
     int8_t* tap_scores; int8_t* tap_probs;
@@ -42,7 +46,7 @@ int num_cus();
 
 // Kinds of launches reported by the trace (ivit_trace_end); values are part of the C ABI.
 enum LaunchKind { KIND_ILAYERNORM = 1, KIND_GEMM = 2, KIND_GEMM_RESIDUAL = 3, KIND_GEMM_GELU = 4,
-                  KIND_ATTENTION = 5, KIND_SHIFTMAX = 6, KIND_SHIFTGELU = 7, KIND_EMBED = 8 };
+                  KIND_ATTENTION = 5, KIND_SHIFTMAX = 6, KIND_SHIFTGELU = 7, KIND_EMBED = 8, KIND_PATCH_MERGE = 9, KIND_MEAN_POOL = 10 };
 
 // Brackets one kernel launch with two HIP events on its stream while a trace is active; otherwise a no-op.
 // ops = algorithmic integer operations (2 per int8 multiply-accumulate), bytes = algorithmic HBM bytes.

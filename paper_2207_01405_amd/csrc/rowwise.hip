@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
 hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
                              int8_t* y, int64_t rows, int C, int f_bits, int c_shift) {
     if (rows == 0) return hipSuccess;
-    if ((C & 15) == 0 && C >= 64 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma_q | (uintptr_t)beta_q) & 15) == 0) {
+    if ((C & 15) == 0 && C >= 64 && C <= 1024 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma_q | (uintptr_t)beta_q) & 15) == 0) {
         // rows per workgroup = (256 / (C / 16)) * J
         const int rp = 256 / (C >> 4);
         // the smallest J whose workgroups are all resident at once (8 per CU): one round of the three dependent phases
@@ -207,7 +207,9 @@ hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamm
         case 1: hipLaunchKernelGGL(ilayernorm_kernel<1>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
         case 2: hipLaunchKernelGGL(ilayernorm_kernel<2>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
         case 3: hipLaunchKernelGGL(ilayernorm_kernel<3>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
-        default: hipLaunchKernelGGL(ilayernorm_kernel<4>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+        case 4: hipLaunchKernelGGL(ilayernorm_kernel<4>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+        case 5: case 6: hipLaunchKernelGGL(ilayernorm_kernel<6>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+        default: hipLaunchKernelGGL(ilayernorm_kernel<8>, dim3(grid), dim3(256), 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;   // C <= 2048
     }
     return hipGetLastError();
 }
@@ -500,6 +502,66 @@ hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int
         hipLaunchKernelGGL(embed_tokens_kernel<true>, dim3(grid), dim3(256), 0, s, patch_tok, cls, pos, tok_rq, pos_rq, tokens, n_pieces, P, C);
     else
         hipLaunchKernelGGL(embed_tokens_kernel<false>, dim3(grid), dim3(256), 0, s, patch_tok, cls, pos, tok_rq, pos_rq, tokens, n_pieces, P, C);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+// Patch merging of the hierarchical windowed models, the data movement only: the four tokens of each 2 x 2
+// neighbourhood of a g x g token grid are concatenated, in the order of (row, column) offsets (0,0), (1,0), (0,1),
+// (1,1), into one row of 4C bytes.  One thread per 16 bytes of output.
+__global__ __launch_bounds__(256) void patch_merge_gather_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y,
+                                                                 int64_t n_pieces, int g, int C) {
+    typedef int v4i __attribute__((ext_vector_type(4)));
+    const int cpr = C >> 4, g2 = g >> 1;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_pieces; i += (int64_t)gridDim.x * 256) {
+        const int64_t orow = i / (4 * cpr);
+        const int j = (int)(i - orow * (4 * cpr));
+        const int q = j / cpr, cc = j - q * cpr;
+        const int64_t b = orow / ((int64_t)g2 * g2);
+        const int rem = (int)(orow - b * g2 * g2);
+        const int yy = rem / g2, xx = rem - yy * g2;
+        const int64_t irow = (b * g + 2 * yy + (q & 1)) * g + 2 * xx + (q >> 1);
+        *reinterpret_cast<v4i*>(y + orow * 4 * C + (int64_t)16 * j) = *reinterpret_cast<const v4i*>(x + irow * C + 16 * cc);
+    }
+}
+
+hipError_t launch_patch_merge_gather(hipStream_t s, const int8_t* x, int8_t* y, int B, int g, int C) {
+    const int64_t n_pieces = (int64_t)B * (g / 2) * (g / 2) * 4 * (C >> 4);
+    if (n_pieces == 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((n_pieces + 255) / 256, (int64_t)num_cus() * 32);
+    TraceScope trace(s, KIND_PATCH_MERGE, 0, 2 * n_pieces * 16);
+    hipLaunchKernelGGL(patch_merge_gather_kernel, dim3(grid), dim3(256), 0, s, x, y, n_pieces, g, C);
+    return hipGetLastError();
+}
+
+// Average pooling over the tokens of an image as a dyadic rescale of the token sum: one thread per four channels of
+// an image walks the T rows (consecutive threads read consecutive dwords of a row).
+__global__ __launch_bounds__(256) void mean_pool_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y, int64_t n_words,
+                                                        int T, int C, Dyadic rq) {
+    const int wpr = C >> 2;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n_words; i += (int64_t)gridDim.x * 256) {
+        const int64_t b = i / wpr;
+        const int wd = (int)(i - b * wpr);
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(x + b * T * C) + wd;
+        int32_t acc[4] = {0, 0, 0, 0};
+        for (int t = 0; t < T; ++t) {
+            const uint32_t v = src[(int64_t)t * wpr];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += (int32_t)(int8_t)(v >> (8 * e));
+        }
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) w |= ((uint32_t)requant64(acc[e], rq.b, rq.c) & 0xffu) << (8 * e);
+        reinterpret_cast<uint32_t*>(y)[i] = w;
+    }
+}
+
+hipError_t launch_mean_pool(hipStream_t s, const int8_t* x, int8_t* y, int B, int T, int C, Dyadic rq) {
+    const int64_t n_words = (int64_t)B * (C >> 2);
+    if (n_words == 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((n_words + 255) / 256, (int64_t)num_cus() * 32);
+    TraceScope trace(s, KIND_MEAN_POOL, 0, (int64_t)B * (T + 1) * C);
+    hipLaunchKernelGGL(mean_pool_kernel, dim3(grid), dim3(256), 0, s, x, y, n_words, T, C, rq);
     return hipGetLastError();
 }
 

@@ -2,7 +2,9 @@
 the full-size synthetic configurations c1-c4 (the whole block stack of each), from oracle/ and the seeded generators
 only.  The GPU parity tests hash the library's output of the full batch the same way and compare.
 
-    python tests/golden/make_checksums.py [--configs c1_deit_t,c2_deit_s,c3_vit_b,c4_swin_t] [--workers 8]
+    python tests/golden/make_checksums.py [--configs c1_deit_t,c2_deit_s,c3_vit_b,c4_swin_t,swin_t] [--workers 8]
+
+For `swin_t` (the hierarchical windowed model, patches in, logits out) the digest is of each image's logits.
 
 Images are independent through the encoder, so each worker runs the oracle on a slice of the batch.
 """
@@ -42,9 +44,21 @@ def work(job):
     return name, lo, digest_rows(y, T, GROUP.get(name, 1))
 
 
+def work_swin(job):
+    name, lo, hi = job
+    import hashlib as h
+    import oracle
+    from paper_2207_01405_amd import synth
+    cfg = synth.SWIN[name]
+    model = synth.make_swin_model(cfg)
+    n = cfg["grid"] ** 2
+    logits = oracle.swin_forward(synth.make_swin_patches(cfg)[lo * n:hi * n], model)
+    return name, lo, [h.sha256(row.tobytes()).hexdigest()[:16] for row in logits]
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--configs", default="c1_deit_t,c2_deit_s,c3_vit_b,c4_swin_t")
+    ap.add_argument("--configs", default="c1_deit_t,c2_deit_s,c3_vit_b,c4_swin_t,swin_t")
     ap.add_argument("--workers", type=int, default=8)
     args = ap.parse_args()
     import oracle
@@ -52,6 +66,18 @@ def main():
     oracle.build()
     res = json.load(open(OUT)) if os.path.exists(OUT) else {}
     for name in args.configs.split(","):
+        if name in synth.SWIN:          # windowed model, patches to logits: one digest per image of its logits
+            cfg = synth.SWIN[name]
+            B = cfg["B"]
+            t0 = time.time()
+            dig = [None] * B
+            with Pool(args.workers) as pool:
+                for _, lo, d in pool.imap_unordered(work_swin, [(name, lo, min(B, lo + 2)) for lo in range(0, B, 2)]):
+                    dig[lo:lo + len(d)] = d
+            res[name] = dict(images=B, n_classes=cfg["n_classes"], sha256_64=dig)
+            print("%s: %d images in %.0f s" % (name, B, time.time() - t0), flush=True)
+            json.dump(res, open(OUT, "w"), indent=0)
+            continue
         cfg = synth.CONFIGS[name]
         B = cfg["B"]
         g = GROUP.get(name, 1)

@@ -3,6 +3,9 @@ bad arguments with the documented status before anything is launched (so none of
 import ctypes as C
 import os
 import re
+import subprocess
+
+import numpy as np
 
 import pytest
 
@@ -33,9 +36,32 @@ def test_struct_layouts_match_the_header(lib):
     assert C.sizeof(binding.DebugTaps) == 64 and C.sizeof(binding.FinalLN) == 24
     # pointers 8-byte aligned, ints packed in pairs: count by hand from the header
     n_ptr = sum(1 for _, t in binding.BlockParams._fields_ if t is C.c_void_p)
-    # 22 pointers, 4 I-LayerNorm ints, 5 dyadic pairs, 2 shift-parameter structs, n_mask padded to 8 bytes
-    assert n_ptr == 22 and C.sizeof(binding.BlockParams) == 22 * 8 + 4 * 4 + 5 * 8 + 2 * 16 + 8
+    # 23 pointers, 4 I-LayerNorm ints, 5 dyadic pairs, 2 shift-parameter structs, n_mask and n_win each padded to 8 bytes
+    assert n_ptr == 23 and C.sizeof(binding.BlockParams) == 23 * 8 + 4 * 4 + 5 * 8 + 2 * 16 + 2 * 8
     assert C.sizeof(binding.ImageParams) == 10 * 8 + 2 * 8 + 2 * 8        # 10 pointers, 2 ints each padded, 2 dyadic pairs
+
+
+def test_struct_sizes_and_offsets_agree_with_a_c_compiler(tmp_path):
+    """The header compiled by gcc reports the size of every struct and the offset of every field; ctypes must agree."""
+    structs = {"ivit_shift_params": binding.ShiftParams, "ivit_dyadic": binding.Dyadic, "ivit_dims": binding.Dims,
+               "ivit_block_params": binding.BlockParams, "ivit_debug_taps": binding.DebugTaps,
+               "ivit_final_ln": binding.FinalLN, "ivit_image_params": binding.ImageParams,
+               "ivit_swin_stage": binding.SwinStage, "ivit_swin_params": binding.SwinParams}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "ivit.h"', 'int main(void) {']
+    for cname, cls in structs.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (cname, cname))
+        for fname, _ in cls._fields_:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (cname, fname, cname, fname))
+    lines.append("return 0; }")
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c11", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = dict(l.split() for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, cls in structs.items():
+        assert int(out[cname]) == C.sizeof(cls), cname
+        for fname, _ in cls._fields_:
+            assert int(out["%s.%s" % (cname, fname)]) == getattr(cls, fname).offset, (cname, fname)
 
 
 def test_strerror(lib):
@@ -89,7 +115,7 @@ def test_rowwise_reject_bad_arguments(lib):
     ln = lib.ivit_ilayernorm
     assert ln(None, FAKE, None, FAKE, FAKE, 4, 64, 16, 19) == E["NULL"]
     assert ln(None, FAKE, FAKE, FAKE, FAKE, 4, 66, 16, 19) == E["SHAPE"]
-    assert ln(None, FAKE, FAKE, FAKE, FAKE, 4, 2048, 16, 19) == E["SHAPE"]
+    assert ln(None, FAKE, FAKE, FAKE, FAKE, 4, 2052, 16, 19) == E["SHAPE"]
     assert ln(None, FAKE, FAKE, FAKE, FAKE, -4, 64, 16, 19) == E["SHAPE"]
     assert ln(None, FAKE, FAKE, FAKE, FAKE, 4, 64, 21, 19) == E["PARAM"]
     assert ln(None, FAKE, FAKE, FAKE, FAKE, 4, 64, 16, 0) == E["PARAM"]
@@ -104,6 +130,7 @@ def _fake_block():
             setattr(bp, name, FAKE)
     bp.rel_bias = None
     bp.attn_mask = None
+    bp.tok_index = None
     for k in ("ln1_f_bits", "ln2_f_bits"):
         setattr(bp, k, 16)
     for k in ("ln1_c_shift", "ln2_c_shift"):
@@ -163,3 +190,102 @@ def test_synthetic_configs_fit_the_supported_shapes(lib):
     for cfg in synth.CONFIGS.values():
         d = binding.dims(synth.dims_of(cfg))
         assert lib.ivit_workspace_bytes(C.byref(d)) > 0
+
+
+# ------------------------------------------------------------------ windowed models: tables, gather, pooling, forward
+@pytest.mark.parametrize("g,w,s", [(8, 4, 2), (8, 4, 0), (56, 7, 3), (28, 7, 3), (14, 7, 3), (7, 7, 0), (12, 3, 1), (16, 4, 3)])
+def test_window_index_and_shift_mask_match_the_oracle(lib, g, w, s):
+    import oracle as orc
+    idx = binding.ivit_swin_window_index(g, w, s)
+    ids = np.arange(g * g, dtype=np.int32).reshape(1, g, g, 1)
+    assert np.array_equal(idx, orc.window_partition(np.roll(ids, (-s, -s), axis=(1, 2)), w)[:, :, 0])
+    assert sorted(idx.reshape(-1).tolist()) == list(range(g * g))
+    m = binding.ivit_swin_shift_mask(g, w, s)
+    assert np.array_equal(m, orc.shift_mask(g, w, s) if s else np.zeros_like(m))
+
+
+def test_window_tables_reject_bad_arguments(lib):
+    buf = (C.c_int32 * 64)()
+    assert lib.ivit_swin_window_index(8, 3, 0, buf) == E["SHAPE"] and lib.ivit_swin_window_index(0, 4, 0, buf) == E["SHAPE"]
+    assert lib.ivit_swin_window_index(8, 4, 4, buf) == E["PARAM"] and lib.ivit_swin_window_index(8, 4, -1, buf) == E["PARAM"]
+    assert lib.ivit_swin_window_index(8, 4, 1, None) == E["NULL"] and lib.ivit_swin_shift_mask(8, 4, 1, None) == E["NULL"]
+    assert lib.ivit_swin_shift_mask(8, 5, 1, buf) == E["SHAPE"] and lib.ivit_swin_shift_mask(8, 4, 7, buf) == E["PARAM"]
+
+
+def test_window_attention_and_small_ops_reject_bad_arguments(lib):
+    d = binding.Dims(8, 16, 64, 2, 256)
+    wa = lambda rb=FAKE, ti=FAKE, n_win=4, dd=d: lib.ivit_window_attention(None, FAKE, rb, None, 1, ti, n_win, FAKE, C.byref(dd),
+                                                                          DY, SP, DY, None, None)
+    assert wa(rb=None) == E["NULL"]                      # a table needs the bias
+    assert wa(n_win=3) == E["SHAPE"] and wa(n_win=0) == E["SHAPE"]
+    assert wa(ti=FAKE + 2) == E["ALIGN"]
+    assert wa(dd=binding.Dims(0, 16, 64, 2, 256)) == 0
+    pm = lib.ivit_patch_merge_gather
+    assert pm(None, FAKE, FAKE, 2, 7, 64) == E["SHAPE"] and pm(None, FAKE, FAKE, 2, 8, 24) == E["SHAPE"]
+    assert pm(None, None, FAKE, 2, 8, 64) == E["NULL"] and pm(None, FAKE + 8, FAKE, 2, 8, 64) == E["ALIGN"]
+    assert pm(None, None, None, 0, 8, 64) == 0
+    mp = lib.ivit_mean_pool
+    assert mp(None, FAKE, FAKE, 2, 0, 64, DY) == E["SHAPE"] and mp(None, FAKE, FAKE, 2, 49, 62, DY) == E["SHAPE"]
+    assert mp(None, FAKE, None, 2, 49, 64, DY) == E["NULL"] and mp(None, FAKE, FAKE, 2, 49, 64, binding.Dyadic(0, 3)) == E["PARAM"]
+    assert mp(None, None, None, 0, 49, 64, DY) == 0
+
+
+def _fake_swin(grid=16, window=4, C0=32, heads=(1, 2, 4), depths=(2, 2, 2)):
+    sp = binding.SwinParams()
+    keep = []
+    sp.grid, sp.window, sp.n_stages, sp.patch_dim, sp.n_classes = grid, window, len(heads), 48, 10
+    for k in ("w_patch", "bias_patch", "patch_rq_b", "patch_rq_c", "w_head", "bias_head", "head_rq_b", "head_rq_c"):
+        setattr(sp, k, FAKE)
+    ln = binding.FinalLN(FAKE, FAKE, 16, 19)
+    sp.embed_ln = ln; sp.final_ln = ln; sp.pool_rq = DY
+    g = grid
+    for s, (H, n) in enumerate(zip(heads, depths)):
+        if s:
+            g //= 2
+        st = sp.stages[s]
+        st.C, st.H, st.F, st.n_blocks = C0 << s, H, 4 * (C0 << s), n
+        arr = (binding.BlockParams * n)()
+        for l in range(n):
+            bp = _fake_block()
+            bp.rel_bias = FAKE
+            if g > window:
+                bp.tok_index = FAKE; bp.n_win = (g // window) ** 2
+                if l % 2:
+                    bp.attn_mask = FAKE; bp.n_mask = bp.n_win
+            arr[l] = bp
+        keep.append(arr)
+        st.blocks = arr
+        if s:
+            st.merge_ln = ln; st.w_merge = FAKE; st.merge_rq_b = FAKE; st.merge_rq_c = FAKE
+    return sp, keep
+
+
+def test_forward_swin_validation(lib):
+    sp, keep = _fake_swin()
+    n = lib.ivit_swin_workspace_bytes(C.byref(sp), 2)
+    # four activation-size buffers of the first stage plus the block workspace of the largest stage
+    assert n >= 4 * 2 * 256 * 32 + lib.ivit_workspace_bytes(C.byref(binding.Dims(2 * 16, 16, 32, 1, 128))) and n % 256 == 0
+    run = lambda p=sp, B=2, ws=0x100000, nb=n, x=FAKE: lib.ivit_forward_swin(None, x, FAKE, C.byref(p), B, ws, nb)
+    assert run(ws=None) == E["WORKSPACE"] and run(nb=n - 1) == E["WORKSPACE"] and run(ws=0x100000 + 64) == E["ALIGN"]
+    assert run(x=None) == E["NULL"] and run(B=-1) == E["SHAPE"] and run(B=0) == 0
+    bad, k2 = _fake_swin(); bad.stages[1].C = 96
+    assert run(bad) == E["SHAPE"] and lib.ivit_swin_workspace_bytes(C.byref(bad), 2) == 0
+    bad, k2 = _fake_swin(grid=12)                       # 12 -> 6: the windows of 4 do not divide the second stage
+    assert run(bad) == E["SHAPE"]
+    bad, k2 = _fake_swin(); k2[0][1].tok_index = None   # a multi-window stage needs its table
+    assert run(bad) == E["NULL"]
+    bad, k2 = _fake_swin(); k2[1][1].n_mask = 3         # mask count differs from the stage's window count
+    assert run(bad) == E["SHAPE"]
+    bad, k2 = _fake_swin(); k2[0][0].n_win = 4
+    assert run(bad) == E["SHAPE"]
+    bad, k2 = _fake_swin(); bad.stages[2].w_merge = None
+    assert run(bad) == E["NULL"]
+    bad, k2 = _fake_swin(); bad.pool_rq = binding.Dyadic(1, 0)
+    assert run(bad) == E["PARAM"]
+    bad, k2 = _fake_swin(); bad.n_stages = 5
+    assert run(bad) == E["SHAPE"]
+    bad, k2 = _fake_swin(); k2[2][0].gelu = binding.ShiftParams(0, 1, 31, 8)
+    assert run(bad) == E["PARAM"]
+    for cfg in synth.SWIN.values():                     # the synthetic windowed models fit
+        sp2, k3 = _fake_swin(cfg["grid"], cfg["window"], cfg["C"], cfg["heads"], cfg["depths"])
+        assert lib.ivit_swin_workspace_bytes(C.byref(sp2), cfg["B"]) > 0

@@ -47,7 +47,7 @@ def assert_same(got, want, what):
 @pytest.mark.parametrize("rows,C,dist", [
     (0, 64, "normal"), (1, 64, "normal"), (65, 64, "normal"), (1001, 96, "normal"), (777, 192, "uniform"),
     (2049, 384, "normal"), (300, 768, "student_t"), (33, 1024, "normal"), (50, 100, "normal"), (7, 4, "uniform"),
-    (64, 384, "const")])
+    (64, 384, "const"), (131, 1536, "normal"), (20, 2048, "student_t"), (9, 1040, "uniform")])
 def test_ilayernorm(ivit, rows, C, dist):
     rng = np.random.default_rng(rows + C)
     x = synth.make_rows(rows + C, rows, C, dist, 30.0)
@@ -454,3 +454,142 @@ def test_encoder_block_with_shift_mask(ivit):
     assert_same(y, y_ref, "masked block output")
     y_plain, _ = orc.encoder_block(x, synth.make_block(cfg, 0), d, want_taps=True)
     assert not np.array_equal(y_plain, y_ref)
+
+
+# ------------------------------------------------------------------ windowed models: gathered windows, merging, pooling, forward
+def _oracle_window_attention(qkv, B, g, w, s, C, H, blk, sm, rel_bias):
+    """The definition: roll the image-order tensor, cut it into windows, attend, put the windows back, roll back."""
+    q = qkv.reshape(B, g, g, 3 * C)
+    if s:
+        q = np.roll(q, (-s, -s), axis=(1, 2))
+    qw = orc.window_partition(q, w)
+    d = dict(B=qw.shape[0], T=w * w, C=C, H=H, F=4 * C)
+    o, sc, pr = orc.attention(qw.reshape(-1, 3 * C), d, blk["qk_rq"], sm, blk["pv_rq"], rel_bias, want_taps=True,
+                              mask=orc.shift_mask(g, w, s) if s else None)
+    oi = orc.window_reverse(o.reshape(-1, w * w, C), w, g)
+    if s:
+        oi = np.roll(oi, (s, s), axis=(1, 2))
+    return oi.reshape(-1, C), pr, d
+
+
+@pytest.mark.parametrize("B,g,w,s,C,H", [(3, 56, 7, 3, 96, 3), (2, 56, 7, 0, 96, 3), (5, 28, 7, 3, 192, 6), (9, 14, 7, 3, 384, 12),
+                                         (2, 16, 4, 2, 64, 1), (1, 12, 3, 1, 64, 2), (4, 7, 7, 0, 768, 24)])
+def test_window_attention_on_image_order_tokens(ivit, B, g, w, s, C, H):
+    T = w * w
+    blk = synth.make_block(dict(T=T, C=C, H=H, F=4 * C, seed=40 + g, i0="fixed", rel_bias=True), 0)
+    sm = synth.shift_params(32)
+    qkv = synth.make_rows(B * g + s, B * g * g, 3 * C, "normal", 32.0)
+    want, pr_ref, d = _oracle_window_attention(qkv, B, g, w, s, C, H, blk, sm, blk["rel_bias"])
+    idx = dev(ivit.ivit_swin_window_index(g, w, s))
+    mask = dev(ivit.ivit_swin_shift_mask(g, w, s)) if s else None
+    o = empty((B * g * g, C)); pr = empty((d["B"], H, T, T))
+    ivit.ivit_window_attention(dev(qkv), o, d, blk["qk_rq"], sm, blk["pv_rq"], dev(blk["rel_bias"]), idx, mask=mask, tap_probs=pr)
+    assert_same(host(pr), pr_ref, "window attention probabilities")
+    assert_same(host(o), want, "window attention output (image order)")
+    o2 = empty(o.shape)
+    ivit.ivit_window_attention(dev(qkv), o2, d, blk["qk_rq"], sm, blk["pv_rq"], dev(blk["rel_bias"]), idx, mask=mask)
+    assert_same(host(o2), want, "window attention output (no taps)")
+
+
+def test_window_attention_clamps_table_entries_outside_the_image(ivit):
+    """An entry beyond the image reads (and writes) the image's last row instead of faulting."""
+    B, g, w, C, H = 2, 8, 4, 64, 2
+    T, n_win = w * w, 4
+    blk = synth.make_block(dict(T=T, C=C, H=H, F=4 * C, seed=77, i0="fixed", rel_bias=True), 0)
+    sm = synth.shift_params(32)
+    qkv = synth.make_rows(5, B * g * g, 3 * C, "normal", 32.0)
+    idx = ivit.ivit_swin_window_index(g, w, 0)
+    orphan = int(idx[0, 5])
+    bad = idx.copy(); bad[0, 5] = 10 ** 9
+    clamped = idx.copy(); clamped[0, 5] = g * g - 1
+    rows = (np.arange(B)[:, None, None] * g * g + clamped[None]).reshape(-1)
+    d = dict(B=B * n_win, T=T, C=C, H=H, F=4 * C)
+    ow = orc.attention(qkv[rows], d, blk["qk_rq"], sm, blk["pv_rq"], blk["rel_bias"])
+    o = empty((B * g * g, C)); o.fill_(-128)
+    ivit.ivit_window_attention(dev(qkv), o, d, blk["qk_rq"], sm, blk["pv_rq"], dev(blk["rel_bias"]), dev(bad))
+    got = host(o)
+    for b in range(B):
+        assert (got[b * g * g + orphan] == -128).all()          # no window owns this row any more
+    check = np.ones(B * n_win * T, bool)
+    for b in range(B):                                          # the last row of each image has two writers
+        check[(rows == b * g * g + g * g - 1)] = False
+    assert_same(got[rows[check]], ow[check], "rows with one writer")
+
+
+@pytest.mark.parametrize("B,g,w,s,C,H,layer", [(2, 56, 7, 3, 96, 3, 1), (2, 28, 7, 0, 192, 6, 0), (3, 14, 7, 3, 384, 12, 1), (2, 8, 4, 2, 32, 1, 1)])
+def test_swin_block_all_tensors(ivit, B, g, w, s, C, H, layer):
+    """The block on image-order tokens with the library's index table and mask, every tensor: row-wise tensors against
+    the oracle's block, scores and probabilities (window-major) against the oracle's attention on explicit windows."""
+    T, n_win = w * w, (g // w) ** 2
+    p = synth.make_block(dict(T=T, C=C, H=H, F=4 * C, seed=50 + g, i0="fixed", rel_bias=True), layer)
+    x = synth.quantize_act(np.random.default_rng(g + s).standard_normal((B * g * g, C)))
+    y_ref = orc.swin_block(x.reshape(B, g, g, C), p, g, w, s, H).reshape(-1, C)
+    q = dict(p, tok_index=ivit.ivit_swin_window_index(g, w, s))
+    if s:
+        q["attn_mask"] = ivit.ivit_swin_shift_mask(g, w, s)
+    d = dict(B=B * n_win, T=T, C=C, H=H, F=4 * C)
+    y, taps = _gpu_block(ivit, x, q, d, True)
+    assert_same(y, y_ref, "swin block output")
+    u = orc.ilayernorm(x, p["ln1_gamma"], p["ln1_beta"], p["ln1_f_bits"], p["ln1_c_shift"])
+    assert_same(taps["u"], u, "u")
+    qkv = orc.linear_requant(u, p["w_qkv"], p["bias_qkv"], p["qkv_rq_b"], p["qkv_rq_c"])
+    assert_same(taps["qkv"], qkv, "qkv (image order)")
+    o_ref, pr_ref, _ = _oracle_window_attention(qkv, B, g, w, s, C, H, p, p["softmax"], p["rel_bias"])
+    assert_same(taps["probs"], pr_ref, "probs (window major)")
+    assert_same(taps["o"], o_ref, "o (image order)")
+    y2, _ = _gpu_block(ivit, x, q, d, False)
+    assert_same(y2, y_ref, "swin block output (no taps)")
+
+
+@pytest.mark.parametrize("B,g,C", [(0, 8, 32), (1, 2, 16), (3, 56, 96), (2, 28, 192), (5, 14, 384), (2, 6, 48)])
+def test_patch_merge_gather(ivit, B, g, C):
+    x = synth.make_rows(B + g, B * g * g, C, "uniform").reshape(B, g, g, C)
+    want = np.concatenate([x[:, 0::2, 0::2], x[:, 1::2, 0::2], x[:, 0::2, 1::2], x[:, 1::2, 1::2]], axis=-1)
+    y = empty((B, g // 2, g // 2, 4 * C))
+    ivit.ivit_patch_merge_gather(dev(x), y, B, g, C)
+    assert_same(host(y), want, "patch merging concatenation")
+
+
+@pytest.mark.parametrize("B,T,C,rq", [(0, 49, 64, (21400, 20)), (1, 1, 4, (2 ** 14, 14)), (128, 49, 768, (21400, 20)),
+                                      (7, 16, 128, (2 ** 16, 20)), (3, 197, 384, (2 ** 30 + 12345, 37)), (5, 49, 96, (2 ** 20, 20))])
+def test_mean_pool(ivit, B, T, C, rq):
+    x = synth.make_rows(B + T, B * T, C, "normal", 50.0).reshape(B, T, C)
+    y = empty((B, C))
+    ivit.ivit_mean_pool(dev(x), y, B, T, C, rq)
+    assert_same(host(y), orc.mean_pool(x, rq) if B else np.empty((0, C), np.int8), "mean pool")
+
+
+def _gpu_swin(ivit, cfg, model, patches, B):
+    import torch
+    m = ivit.swin_to_device(model)
+    sp, keep = ivit.swin_params(m)
+    ws = torch.empty(ivit.ivit_swin_workspace_bytes(sp, B), dtype=torch.uint8, device="cuda")
+    logits = empty((B, cfg["n_classes"]))
+    ivit.ivit_forward_swin(dev(patches), logits, sp, B, ws)
+    return host(logits)
+
+
+@pytest.mark.parametrize("name,B", [("swin_tiny_test", 2), ("swin_tiny_test", 7), ("swin_t", 2)])
+def test_forward_swin_patches_to_logits(ivit, name, B):
+    cfg = synth.SWIN[name]
+    model = synth.make_swin_model(cfg)
+    patches = synth.make_swin_patches(cfg, B)
+    want = orc.swin_forward(patches, model)
+    assert want.std() > 5
+    assert_same(_gpu_swin(ivit, cfg, model, patches, B), want, "%s logits" % name)
+
+
+def test_forward_swin_full_size_every_image_against_stored_oracle_digests(ivit):
+    """Swin-T shape, 128 images (the shape the benchmark times): digests of the oracle's logits per image, written by
+    tests/golden/make_checksums.py, against digests of the library's logits."""
+    import hashlib
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "forward_checksums.json")
+    ref = json.load(open(path))["swin_t"]
+    cfg = synth.SWIN["swin_t"]
+    assert (ref["images"], ref["n_classes"]) == (cfg["B"], cfg["n_classes"])
+    got = np.ascontiguousarray(_gpu_swin(ivit, cfg, synth.make_swin_model(cfg), synth.make_swin_patches(cfg), cfg["B"]))
+    dig = [hashlib.sha256(got[i].tobytes()).hexdigest()[:16] for i in range(cfg["B"])]
+    bad = [i for i, (a, b) in enumerate(zip(dig, ref["sha256_64"])) if a != b]
+    assert len(dig) == len(ref["sha256_64"]) and not bad, "swin_t: %d of %d digests differ, first %s" % (len(bad), len(dig), bad[:5])
