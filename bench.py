@@ -39,6 +39,39 @@ def measured_traffic(workload):
     return None
 
 
+def time_swin(binding, synth, torch, name, steps, stream):
+    """The hierarchical windowed model (Swin-T shape), patches in, logits out, with its per-kind kernel time."""
+    scfg = synth.SWIN[name]
+    sm = binding.swin_to_device(synth.make_swin_model(scfg))
+    sp, keep = binding.swin_params(sm)
+    SB = scfg["B"]
+    sp_patches = torch.from_numpy(synth.make_swin_patches(scfg)).cuda()
+    sp_logits = torch.empty((SB, scfg["n_classes"]), dtype=torch.int8, device="cuda")
+    wss = torch.empty(binding.ivit_swin_workspace_bytes(sp, SB), dtype=torch.uint8, device="cuda")
+    for _ in range(3):
+        binding.ivit_forward_swin(sp_patches, sp_logits, sp, SB, wss, stream=stream)
+    torch.cuda.synchronize()
+    n = max(10, steps // 2)
+    ts = time.perf_counter()
+    for _ in range(n):
+        binding.ivit_forward_swin(sp_patches, sp_logits, sp, SB, wss, stream=stream)
+    torch.cuda.synchronize()
+    el = (time.perf_counter() - ts) / n
+    n_launch = 7 * sum(scfg["depths"]) + 3 * (len(scfg["depths"]) - 1) + 5
+    binding.ivit_trace_begin(3 * n_launch + 16)
+    for _ in range(3):
+        binding.ivit_forward_swin(sp_patches, sp_logits, sp, SB, wss, stream=stream)
+    srec = binding.ivit_trace_end(3 * n_launch + 16)
+    by_kind = {}
+    s_ops = 0
+    for ms, kind, ops, nbytes in srec:
+        by_kind[binding.KIND_NAMES[kind]] = by_kind.get(binding.KIND_NAMES[kind], 0.0) + ms / 3
+        s_ops += ops
+    return dict(workload=name, batch=SB, ms_per_step=round(el * 1e3, 4), images_per_s=round(SB / el, 1),
+                launches_per_step=len(srec) // 3, int8_gops_per_image=round(s_ops / 3 / SB / 1e9, 3),
+                kernel_ms_per_step={k: round(v, 4) for k, v in sorted(by_kind.items())})
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -52,6 +85,7 @@ def main():
     ap.add_argument("--batch-sweep", default="", help="comma-separated batch sizes to time as well (same weights), e.g. 1,8,16,32,64,128")
     ap.add_argument("--no-image-path", action="store_true", help="skip the patches-to-logits timing (embedding + blocks + head)")
     ap.add_argument("--swin", default="swin_t", help="windowed model to time as well, patches to logits ('' = skip)")
+    ap.add_argument("--swin-only", action="store_true", help="time only the windowed model and print its figures (for profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device copy a few times (reference for hardware byte counters) and exit")
     args = ap.parse_args()
@@ -72,6 +106,10 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": 1 << 30, "calibrate_copy_bytes_written": 1 << 30, "launches": 4}))
         return
     binding.load()
+    if args.swin_only:
+        print(json.dumps({"swin": time_swin(binding, synth, torch, args.swin or "swin_t", args.steps,
+                                            torch.cuda.current_stream().cuda_stream)}))
+        return
 
     cfg = synth.CONFIGS[args.workload]
     d = synth.dims_of(cfg)
@@ -140,39 +178,7 @@ def main():
                           n_classes=synth.N_CLASSES[cfg["name"]])
         del patches, logits, wsi
 
-    # ---- the hierarchical windowed model (Swin-T shape), patches in, logits out, with its per-kind kernel time
-    swin = None
-    if args.swin:
-        scfg = synth.SWIN[args.swin]
-        sm = binding.swin_to_device(synth.make_swin_model(scfg))
-        sp, keep = binding.swin_params(sm)
-        SB = scfg["B"]
-        sp_patches = torch.from_numpy(synth.make_swin_patches(scfg)).cuda()
-        sp_logits = torch.empty((SB, scfg["n_classes"]), dtype=torch.int8, device="cuda")
-        wss = torch.empty(binding.ivit_swin_workspace_bytes(sp, SB), dtype=torch.uint8, device="cuda")
-        for _ in range(3):
-            binding.ivit_forward_swin(sp_patches, sp_logits, sp, SB, wss, stream=stream)
-        torch.cuda.synchronize()
-        n = max(10, args.steps // 2)
-        ts = time.perf_counter()
-        for _ in range(n):
-            binding.ivit_forward_swin(sp_patches, sp_logits, sp, SB, wss, stream=stream)
-        torch.cuda.synchronize()
-        el = (time.perf_counter() - ts) / n
-        n_launch = 7 * sum(scfg["depths"]) + 3 * (len(scfg["depths"]) - 1) + 5
-        binding.ivit_trace_begin(3 * n_launch + 16)
-        for _ in range(3):
-            binding.ivit_forward_swin(sp_patches, sp_logits, sp, SB, wss, stream=stream)
-        srec = binding.ivit_trace_end(3 * n_launch + 16)
-        by_kind = {}
-        s_ops = 0
-        for ms, kind, ops, nbytes in srec:
-            by_kind[binding.KIND_NAMES[kind]] = by_kind.get(binding.KIND_NAMES[kind], 0.0) + ms / 3
-            s_ops += ops
-        swin = dict(workload=args.swin, batch=SB, ms_per_step=round(el * 1e3, 4), images_per_s=round(SB / el, 1),
-                    launches_per_step=len(srec) // 3, int8_gops_per_image=round(s_ops / 3 / SB / 1e9, 3),
-                    kernel_ms_per_step={k: round(v, 4) for k, v in sorted(by_kind.items())})
-        del sp_patches, sp_logits, wss, sm, keep
+    swin = time_swin(binding, synth, torch, args.swin, args.steps, stream) if args.swin else None
 
     # ---- per-kernel durations with HIP events, same workload, same process
     launches_per_step = 7 * L

@@ -79,35 +79,67 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
     // qkv (two 64-byte head slices per line), which then meet in one L2
     const int G = gridDim.x, xcd = blockIdx.x % 8;
     const int first = xcd * (G / 8) + min(xcd, G % 8) + blockIdx.x / 8;
+    // Rows of qkv / o.  Without a table token t of window b is row b T + t.  With one (BIAS instances only) the rows
+    // come from the index table of the window's position inside its image; an entry outside the image is clamped,
+    // never followed.  The table entries this thread needs for an item (its K / V pieces and its first query tile) are
+    // fetched one item ahead, so that the loads of K, V and Q never wait for an index.
+    constexpr int NPC = (NKT * 16 * DCH + ATT_THREADS - 1) / ATT_THREADS;     // 16-byte pieces per thread and operand
+    const int tpi = n_win * T;                     // tokens per image
+    const bool gather = BIAS && tok_index != nullptr;
+    int kvrow[NPC], qrow0 = 0, kvnext[NPC], qnext = 0;
+    auto fetch_rows = [&](int item, int (&kv)[NPC], int& qr) {
+        const int b = item / H;
+        const int32_t* tr = tok_index + (b % n_win) * T;
+        const int r0 = (b / n_win) * tpi;
+#pragma unroll
+        for (int it = 0; it < NPC; ++it) {
+            const int key = min((tid + ATT_THREADS * it) / DCH, T - 1);
+            kv[it] = r0 + (int)min((uint32_t)tr[key], (uint32_t)(tpi - 1));
+        }
+        qr = r0 + (int)min((uint32_t)tr[min(wv * 16 + li, T - 1)], (uint32_t)(tpi - 1));
+    };
+    if (BIAS) { if (gather && first < n_items) fetch_rows(first, kvrow, qrow0); }
+
     for (int item = first; item < n_items; item += G) {
         const int b = item / H, h = item % H;
         const int8_t* base = qkv + h * D;
-        // row of token t of window b in qkv and o: consecutive rows, or (BIAS instances) looked up in the index table
-        // of the window's position inside its image; an entry outside the image is clamped, never followed
-        const int tpi = n_win * T;                 // tokens per image
-        const int32_t* trow = (BIAS && tok_index) ? tok_index + (b % n_win) * T : nullptr;
-        const int64_t row0 = (BIAS && tok_index) ? (int64_t)(b / n_win) * tpi : (int64_t)b * T;
-        auto row_of = [&](int t) -> int64_t {
+        const int32_t* trow = gather ? tok_index + (b % n_win) * T : nullptr;
+        const int64_t row0 = gather ? (int64_t)(b / n_win) * tpi : (int64_t)b * T;
+        auto row_of = [&](int t) -> int64_t {      // any token of this window (t < T)
             if (BIAS) { if (trow) return row0 + (int)min((uint32_t)trow[t], (uint32_t)(tpi - 1)); }
             return row0 + t;
         };
+        auto q_row = [&](int qt) -> int64_t {      // row of this lane's query of tile qt
+            if (BIAS) { if (gather && qt == wv) return qrow0; }
+            return row_of(min(qt * 16 + li, T - 1));
+        };
         __syncthreads();                           // table ready / previous item's readers done
         // the query fragment of a tile is requested one tile ahead, the first one together with K and V
-        auto load_q64 = [&](int qt) { return *reinterpret_cast<const v4i*>(base + row_of(min(qt * 16 + li, T - 1)) * 3 * C + 16 * lg); };
-        auto load_q32 = [&](int qt) { return *reinterpret_cast<const long*>(base + row_of(min(qt * 16 + li, T - 1)) * 3 * C + 8 * lg); };
+        auto load_q64 = [&](int qt) { return *reinterpret_cast<const v4i*>(base + q_row(qt) * 3 * C + 16 * lg); };
+        auto load_q32 = [&](int qt) { return *reinterpret_cast<const long*>(base + q_row(qt) * 3 * C + 8 * lg); };
         v4i qn64 = {0, 0, 0, 0};
         long qn32 = 0;
         if (D == 64) qn64 = load_q64(wv); else qn32 = load_q32(wv);
         // all of this thread's K and V pieces are requested before the first one is used: one memory latency per item
-        constexpr int NPC = (NKT * 16 * DCH + ATT_THREADS - 1) / ATT_THREADS;     // 16-byte pieces per thread and operand
         v4i kreg[NPC], vreg[NPC];
 #pragma unroll
         for (int it = 0; it < NPC; ++it) {
             const int c = tid + ATT_THREADS * it;
             const int key = min(c / DCH, T - 1), part = c % DCH;
-            const int8_t* kv_row = base + row_of(key) * 3 * C + 16 * part;
+            int64_t row = row0 + key;
+            if (BIAS) { if (gather) row = kvrow[it]; }
+            const int8_t* kv_row = base + row * 3 * C + 16 * part;
             kreg[it] = *reinterpret_cast<const v4i*>(kv_row + C);
             vreg[it] = *reinterpret_cast<const v4i*>(kv_row + 2 * C);
+        }
+        const int64_t orow0 = q_row(wv);           // output row of the first query tile (before the indices move on)
+        if (BIAS) {
+            if (gather && item + G < n_items) {
+                fetch_rows(item + G, kvnext, qnext);
+#pragma unroll
+                for (int it = 0; it < NPC; ++it) kvrow[it] = kvnext[it];
+                qrow0 = qnext;
+            }
         }
 #pragma unroll
         for (int it = 0; it < NPC; ++it) {
@@ -167,13 +199,18 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
             for (int t = 0; t < NKT; ++t) {
                 if (t < nfull) {                   // uniform: every key of the tile exists
+                    // the lane's four keys are four consecutive bytes of the bias and the mask row: one (unaligned)
+                    // dword each instead of four byte loads
+                    uint32_t bw = 0, mw = 0;
+                    if (BIAS) { if (!MASK || brow) __builtin_memcpy(&bw, brow + 16 * t + 4 * lg, 4); }
+                    if (MASK) __builtin_memcpy(&mw, mrow + 16 * t + 4 * lg, 4);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int key = 16 * t + 4 * lg + r;
                         int32_t a = requant8<FAST>(sc[t][r], qk);
                         if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
-                        if (BIAS) { if (!MASK || brow) a += brow[key]; }
-                        if (MASK) { if (mrow[key]) a += mask_add; }
+                        if (BIAS) a += (int32_t)(int8_t)(bw >> (8 * r));
+                        if (MASK) { if ((mw >> (8 * r)) & 0xffu) a += mask_add; }
                         sc[t][r] = a;
                     }
                     mx = max(mx, max(sc[t][0], sc[t][1]));       // two three-operand maxima per tile
@@ -284,7 +321,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 ow[n] = w;
             }
             if (q < T) {
-                int8_t* op = o + row_of(q) * C + h * D + lg * (D / 4);
+                int8_t* op = o + (qt == wv ? orow0 : row_of(q)) * C + h * D + lg * (D / 4);
                 if (D == 64) *reinterpret_cast<uint4*>(op) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
                 else *reinterpret_cast<uint2*>(op) = make_uint2(ow[0], ow[1 % ND]);
             }

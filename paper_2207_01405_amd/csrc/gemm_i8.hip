@@ -293,7 +293,11 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     int32_t* qc_s = qb_s + NS;
     int32_t* bias_s = qc_s + NS;
     int64_t* hb_s = reinterpret_cast<int64_t*>(bias_s + NS);   // bias * b + 2^(c-1): the 64-bit addend of the fast requantisation
-    int8_t* gelu_lut = reinterpret_cast<int8_t*>(hb_s + NS);
+    int32_t* lo_s = reinterpret_cast<int32_t*>(hb_s + NS);     // the four tables of the 24-bit requantisation (see below)
+    int32_t* hi_s = lo_s + NS;
+    int32_t* mb_s = hi_s + NS;
+    int32_t* ad_s = mb_s + NS;
+    int8_t* gelu_lut = reinterpret_cast<int8_t*>(ad_s + NS);
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int li = lane & 31, lg = lane >> 5;
@@ -345,7 +349,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         if (++lu == nunits) { lu = 0; lgrp += stride; }
     };
     if (has_work) issue(xa);                            // in flight during the prologue
-    bool slow_any;
+    bool slow_any, wide_any;
 
     // ---- prologue: the slab (zero padded to whole units and whole slabs), its parameters, the GELU table; all
     // global loads are issued before anything waits for one of them
@@ -367,11 +371,37 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             const int32_t I = (int32_t)(int8_t)tid;
             gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
         }
+        // 24-bit requantisation.  With v = dot + bias, the int8 result clamp8((v b + 2^(c-1)) >> c) is the same for all
+        // v >= Lp (127) and all v <= Ln (-127), Lp / Ln being the first v that reach +-127; for b < 2^c the result AT Lp
+        // and Ln is exactly +-127.  So v is limited to [Ln, Lp] first, after which T = v b + 2^(c-1) lies in
+        // (-128 2^c, 128 2^c) and T 2^(24-c) fits 32 bits with the result in its top byte: one median of three against
+        // [Ln - bias, Lp - bias], one 24-bit multiply-add by b 2^(24-c) (the addend, taken modulo 2^32, carries bias and
+        // rounding), no shift and no final clamp.  Needs c <= 24, b 2^(24-c) < 2^23 and bounds that fit 24 bits;
+        // anything else takes the 64-bit paths below.
+        bool chan_24 = true;
+        if (tid < NS) {
+            int32_t lo = 0, hi = 0, mb = 0, ad = 0;
+            if (n0 + tid < N) {
+                chan_24 = pc >= 1 && pc <= 24 && pb >= 1 && pb < (1 << ((pc - 1) & 31));
+                if (chan_24) {
+                    const int64_t half = (int64_t)1 << (pc - 1), two_c = (int64_t)1 << pc;
+                    const int64_t Lp = (127 * two_c - half + pb - 1) / pb;
+                    const int64_t Ln = -((127 * two_c - half + 1 + pb - 1) / pb);
+                    const int64_t l = Ln - pbias, h = Lp - pbias;
+                    chan_24 = l >= -(1 << 23) && h < (1 << 23);
+                    lo = (int32_t)l; hi = (int32_t)h; mb = pb << (24 - pc);
+                    ad = (int32_t)(uint32_t)((uint64_t)((int64_t)pbias * pb + half) << (24 - pc));
+                }
+            }
+            lo_s[tid] = lo; hi_s[tid] = hi; mb_s[tid] = mb; ad_s[tid] = ad;
+        }
+        wide_any = __syncthreads_and(chan_24) == 0;
         const bool chan_fast = tid >= NS || dyadic_fits32(pb, pc);
         slow_any = __syncthreads_and(chan_fast) == 0;
     }
     if (!has_work) return;
     const bool fast = !slow_any && (EPI != EPI_RESIDUAL || dyadic_fits32(P.res_rq.b, P.res_rq.c));
+    const bool fast24 = EPI != EPI_RESIDUAL && !wide_any;
 
     // The accumulators hold the bare dot products: the first MFMA group of a token group takes C = 0, and the bias
     // enters through the 64-bit addend of the requantisation (general path: added explicitly).
@@ -424,7 +454,32 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     auto finish = [&]() __attribute__((always_inline)) {
         const int64_t tok = cgrp * 32 + li;
         const int nl = 16 * NCB * lg;                   // slab-local first channel of the lane
-        if (fast) {
+        if (EPI != EPI_RESIDUAL && fast24) {
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                v4i outv;
+#pragma unroll
+                for (int w4 = 0; w4 < 4; ++w4) {
+                    const v4i lo = *reinterpret_cast<const v4i*>(&lo_s[nl + 16 * cb + 4 * w4]);
+                    const v4i hi = *reinterpret_cast<const v4i*>(&hi_s[nl + 16 * cb + 4 * w4]);
+                    const v4i mb = *reinterpret_cast<const v4i*>(&mb_s[nl + 16 * cb + 4 * w4]);
+                    const v4i ad = *reinterpret_cast<const v4i*>(&ad_s[nl + 16 * cb + 4 * w4]);
+                    uint32_t o[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int32_t m;
+                        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(acc[cb][4 * w4 + r]), "v"(lo[r]), "v"(hi[r]));
+                        o[r] = (uint32_t)(__mul24(m, mb[r]) + ad[r]);             // result in the top byte
+                        if (EPI == EPI_GELU) o[r] = (uint32_t)gelu_lut[o[r] >> 24];   // result in the low byte
+                    }
+                    // top (GELU: low) bytes of o[0..3] -> one word
+                    const uint32_t p01 = __builtin_amdgcn_perm(o[1], o[0], EPI == EPI_GELU ? 0x0c0c0400u : 0x0c0c0703u);
+                    const uint32_t p23 = __builtin_amdgcn_perm(o[3], o[2], EPI == EPI_GELU ? 0x04000c0cu : 0x07030c0cu);
+                    outv[w4] = (int)(p01 | p23);
+                }
+                *reinterpret_cast<v4i*>(stage + li * SP + nl + 16 * cb) = outv;
+            }
+        } else if (fast) {
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
                 v4i resv = {0, 0, 0, 0};
@@ -537,8 +592,9 @@ static bool ws_plan(const LinearArgs& a, int& ncb, int& unit, int& nunits, int& 
     pitch = kp + ((kp / 16) % 2 == 0 ? 16 : 32);        // (pitch / 16) odd: 16 lanes x 16 bytes cover all LDS banks
     // 128-channel slabs halve the activation traffic per MFMA; with fewer than six of them the 64-channel slabs'
     // finer work items fill the wavefronts more evenly
-    for (ncb = (a.N + 127) / 128 >= 6 ? 4 : 2; ncb >= 2; ncb >>= 1) {
-        lds_bytes = (size_t)32 * ncb * pitch + 5 * 4 * 32 * ncb + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 32 * (WS_CHUNK + 16));
+    int ncb0 = (a.N + 127) / 128 >= 6 ? 4 : 2;
+    for (ncb = ncb0; ncb >= 2; ncb >>= 1) {
+        lds_bytes = (size_t)32 * ncb * pitch + 9 * 4 * 32 * ncb + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 32 * (WS_CHUNK + 16));
         if (lds_bytes <= (size_t)WS_LDS_MAX) return true;
     }
     return false;

@@ -544,7 +544,17 @@ __global__ __launch_bounds__(256) void mean_pool_kernel(const int8_t* __restrict
         const int wd = (int)(i - b * wpr);
         const uint32_t* src = reinterpret_cast<const uint32_t*>(x + b * T * C) + wd;
         int32_t acc[4] = {0, 0, 0, 0};
-        for (int t = 0; t < T; ++t) {
+        int t = 0;
+        for (; t + 8 <= T; t += 8) {               // eight independent loads in flight
+            uint32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(t + u) * wpr];
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc[e] += (int32_t)(int8_t)(v[u] >> (8 * e));
+        }
+        for (; t < T; ++t) {
             const uint32_t v = src[(int64_t)t * wpr];
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc[e] += (int32_t)(int8_t)(v >> (8 * e));

@@ -6,6 +6,7 @@ paper_2207_01405_amd.synth.  Sizes span several tiles and ragged tails; the full
 the GPU in the shape the benchmark times and are checked on sampled images, which the oracle computes one by
 one (images are independent through the encoder).
 """
+import math
 from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
@@ -185,6 +186,51 @@ def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit):
         want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
         assert_same(host(y), want, "linear general")
         assert np.abs(want.astype(np.int32)).mean() > 2
+
+
+@pytest.mark.parametrize("K", [128, 1536])
+def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, K):
+    """Per-channel parameters at and around the limits of the 24-bit requantisation (shift 1..24, multiplier just
+    below and at 2^(c-1), biases that push the clamp bounds to and past 24 bits), on operands that drive the
+    accumulators to both saturated ends (K * 127^2 exceeds 2^23 for the larger K) and through the whole range.
+    Slabs of 64 channels share one regime each, so both the narrow path and its fallbacks run."""
+    rng = np.random.default_rng(K)
+    M, N = 333, 64 * 10
+    x = synth.make_rows(K, M, K, "uniform")
+    x[0:8] = 127; x[8:16] = -127; x[16:24] = 0; x[24:32, ::2] = 127; x[24:32, 1::2] = -127
+    w = synth.make_rows(K + 1, N, K, "uniform")
+    w[0::64] = 127; w[1::64] = -127; w[2::64] = 0
+    w[3::64] = (np.arange(K) % 2 * 2 - 1) * 127
+    b = np.empty(N, np.int64); c = np.empty(N, np.int64); bias = np.zeros(N, np.int64)
+    sig = math.sqrt(K) * 73.0 * 73.0                                   # accumulator spread of uniform operands
+    for slab in range(10):
+        sl = slice(64 * slab, 64 * slab + 64)
+        if slab < 6:        # narrow path: c from the top of the range down, b ~ 30 2^c / sigma, capped below 2^(c-1)
+            cc = (24, 23, 20, 17, 14, 11)[slab]
+            top = 2 ** (cc - 1) - 1
+            c[sl] = cc
+            b[sl] = np.clip(rng.integers(int(20 * 2 ** cc / sig) + 1, int(40 * 2 ** cc / sig) + 2, size=64), 1, top)
+            b[64 * slab] = top; b[64 * slab + 1] = 1
+            bias[sl] = rng.integers(-int(3 * sig), int(3 * sig), size=64)
+            bias[64 * slab + 5] = 2 ** 20; bias[64 * slab + 6] = -2 ** 20
+        elif slab == 6:     # b = 2^(c-1) exactly: just outside
+            c[sl] = 16; b[sl] = 2 ** 15
+        elif slab == 7:     # biases near +-2^23: bounds leave the 24-bit range for some channels
+            c[sl] = 22; b[sl] = rng.integers(2 ** 14, 2 ** 15, size=64); bias[sl] = rng.choice([-1, 1], 64) * (2 ** 23 - rng.integers(0, 2 ** 17, size=64))
+        elif slab == 8:     # c = 25: outside
+            c[sl] = 25; b[sl] = rng.integers(2 ** 15, 2 ** 16, size=64)
+        else:               # mixed shifts inside one slab, all narrow
+            c[sl] = rng.integers(18, 25, size=64); b[sl] = [int(rng.integers(2 ** (cc - 10), 2 ** (cc - 8))) for cc in c[sl]]
+            bias[sl] = rng.integers(-2 ** 18, 2 ** 18, size=64)
+    b = b.astype(np.int32); c = c.astype(np.int32); bias = bias.astype(np.int32)
+    gl = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21))
+    for kw in ({}, gl):
+        y = empty((M, N))
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, **kw)
+        want = orc.linear_requant(x, w, bias, b, c, **kw)
+        assert_same(host(y), want, "linear at the limits of the narrow path" + (" + gelu" if kw else ""))
+    plain = orc.linear_requant(x, w, bias, b, c)
+    assert (plain == 127).mean() > 0.02 and (plain == -127).mean() > 0.02 and (np.abs(plain) < 127).mean() > 0.3
 
 
 # ------------------------------------------------------------------ fused attention
