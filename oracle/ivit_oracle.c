@@ -110,6 +110,30 @@ void orc_shiftgelu_raw(const int8_t* x, int32_t* g, int64_t n, orc_shift_params 
     for (int64_t i = 0; i < n; ++i) g[i] = (int32_t)orc_shiftgelu_raw1(x[i], p);
 }
 
+/* ShiftGELU with the maximum of Algorithm 2 taken over each row of the tensor (the other reading of the
+ * algorithm's max(I_p), which names no axis): m = max(0, max_j I_p[j]) (the floor at 0 keeps the argument of
+ * ShiftExp(-m) non-positive), I_exp = ShiftExp(I_p - m), I_exp' = ShiftExp(-m), I_div = IntDiv(I_exp,
+ * I_exp + I_exp'), result I * I_div requantised to int8.  Far below a large row maximum both ShiftExp values
+ * shift out to 0; there I_div is taken as 0 (the paper does not treat the case).  Needs a wide ShiftExp
+ * (I_0 << N up to 2^30) to be usable. */
+void orc_shiftgelu_rowmax(const int8_t* x, int8_t* y, int64_t rows, int32_t cols, orc_shift_params p, orc_dyadic out_rq) {
+    for (int64_t r = 0; r < rows; ++r) {
+        const int8_t* xr = x + r * (int64_t)cols;
+        int64_t m = 0;
+        for (int32_t j = 0; j < cols; ++j) {
+            int64_t I = xr[j], Ip = I + (I >> 1) + (I >> 3) + (I >> 4);
+            if (Ip > m) m = Ip;
+        }
+        int64_t e2 = orc_shiftexp(-m, p.i0, p.n_shift);
+        for (int32_t j = 0; j < cols; ++j) {
+            int64_t I = xr[j], Ip = I + (I >> 1) + (I >> 3) + (I >> 4);
+            int64_t e1 = orc_shiftexp(Ip - m, p.i0, p.n_shift);
+            int64_t dv = (e1 + e2 > 0) ? orc_intdiv(e1, e1 + e2, p.k_out, p.m_bits) : 0;
+            y[r * (int64_t)cols + j] = (int8_t)orc_requant(I * dv, out_rq.b, out_rq.c);
+        }
+    }
+}
+
 /* ShiftGELU followed by the dyadic requantisation of its int16-range result to int8. */
 void orc_shiftgelu(const int8_t* x, int8_t* y, int64_t n, orc_shift_params p, orc_dyadic out_rq) {
     for (int64_t i = 0; i < n; ++i)

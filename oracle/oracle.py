@@ -19,7 +19,7 @@ _LIB = os.path.join(_HERE, "liboracle.so")
 
 __all__ = [
     "build", "rnd_shift", "clamp_k", "requant", "shiftexp", "intdiv", "isqrt10",
-    "shiftgelu_raw", "shiftgelu", "shiftmax", "ilayernorm", "linear_requant",
+    "shiftgelu_raw", "shiftgelu", "shiftgelu_rowmax", "shiftmax", "ilayernorm", "linear_requant",
     "attention", "encoder_block", "forward", "ShiftParams", "Dyadic",
     "requant_vec", "rnd_shift_vec", "isqrt10_vec", "shiftexp_vec", "TAP_NAMES",
     "quantize_symmetric", "dyadic_from_float", "shift_params_from_scale",
@@ -86,6 +86,8 @@ def _L():
         lib.orc_isqrt10.restype = i64; lib.orc_isqrt10.argtypes = [i64]
         lib.orc_shiftgelu_raw.restype = None; lib.orc_shiftgelu_raw.argtypes = [_P, _P, i64, ShiftParams]
         lib.orc_shiftgelu.restype = None; lib.orc_shiftgelu.argtypes = [_P, _P, i64, ShiftParams, Dyadic]
+        lib.orc_shiftgelu_rowmax.restype = None
+        lib.orc_shiftgelu_rowmax.argtypes = [_P, _P, i64, i32, ShiftParams, Dyadic]
         lib.orc_shiftmax.restype = None
         lib.orc_shiftmax.argtypes = [_P, _P, i32, i32, _P, i64, i32, i32, ShiftParams]
         lib.orc_ilayernorm.restype = None; lib.orc_ilayernorm.argtypes = [_P, _P, _P, _P, i64, i32, i32, i32]
@@ -159,6 +161,15 @@ def shiftgelu(x, p, out_rq):
     x = _arr(x, np.int8)
     y = np.empty(x.shape, np.int8)
     _L().orc_shiftgelu(_ptr(x), _ptr(y), x.size, _sp(p), _dy(out_rq))
+    return y
+
+
+def shiftgelu_rowmax(x, p, out_rq):
+    """x: int8 [rows, cols]; the maximum of Algorithm 2 is taken over each row."""
+    x = _arr(x, np.int8)
+    rows, cols = x.shape
+    y = np.empty_like(x)
+    _L().orc_shiftgelu_rowmax(_ptr(x), _ptr(y), rows, cols, _sp(p), _dy(out_rq))
     return y
 
 

@@ -702,3 +702,68 @@ def test_swin_forward_chains_the_stages_and_images_are_independent():
     assert np.array_equal(logits, orc.linear_requant(pooled, hd["w"], hd["bias"], hd["rq_b"], hd["rq_c"]))
     for o in outs:
         assert 4.0 < o.std() < 90.0 and (np.abs(o) == 127).mean() < 0.2
+
+
+# ------------------------------------------------------------------ alternative readings kept as variants
+# The row-maximum form needs a wide ShiftExp (values up to 2^29 here) and, with sums that large, a reciprocal
+# 2^M / sum with M well above 31, or IntDiv keeps only three bits of the quotient.
+WIDE = dict(i0=32, n_shift=24, m_bits=46, k_out=8)
+
+
+def test_shiftgelu_rowmax_equals_the_elementwise_form_where_the_two_maxima_coincide():
+    """Rows without a positive entry have m = 0 for every element in both readings; a constant row has m = I_p."""
+    rq = (24171, 21)
+    neg = -np.abs(synth.make_rows(61, 40, 96, "normal", 40.0))
+    assert np.array_equal(orc.shiftgelu_rowmax(neg, WIDE, rq), orc.shiftgelu(neg, WIDE, rq))
+    const = np.repeat(np.arange(-127, 128, dtype=np.int8)[:, None], 7, axis=1)
+    assert np.array_equal(orc.shiftgelu_rowmax(const, WIDE, rq), orc.shiftgelu(const, WIDE, rq))
+    one = np.arange(-127, 128, dtype=np.int8)[:, None]
+    assert np.array_equal(orc.shiftgelu_rowmax(one, WIDE, rq), orc.shiftgelu(one, WIDE, rq))
+
+
+@pytest.mark.parametrize("i0,tol", [(32, 0.06), (16, 0.09)])
+def test_shiftgelu_rowmax_against_float_gelu(i0, tol):
+    """x sigmoid(1.702 x) in floating point; Eq. 18 is an identity for any maximum, so the row form has the same
+    target.  Tolerance: the two approximations of ShiftExp plus one output LSB, relative to the output scale."""
+    p = dict(WIDE, i0=i0, n_shift=29 - i0.bit_length())
+    S = 1.0 / i0
+    x = synth.make_rows(62, 64, 384, "normal", 1.2 * i0)          # real values about N(0, 1.2^2), a few beyond 4
+    s_out = 4.0 / 127.0
+    b, c = orc.dyadic_from_float(S / 128.0 / s_out, 15)
+    got = orc.shiftgelu_rowmax(x, p, (b, c)).astype(np.float64) * s_out
+    xr = x.astype(np.float64) * S
+    want = xr / (1.0 + np.exp(-1.702 * xr))
+    assert np.abs(got - np.clip(want, -4, 4)).max() <= tol * max(1.0, np.abs(want).max())
+
+
+def test_shiftgelu_rowmax_loses_small_values_next_to_a_large_maximum_with_a_16_bit_shiftexp():
+    """Why the elementwise reading is the default: with the 16-bit ShiftExp range of the other operators, a row whose
+    maximum is large shifts BOTH exponent images of a moderate element out to zero; the quotient is then undefined
+    (taken as 0) although the true GELU value is not small.  A wide ShiftExp pushes this far out."""
+    narrow = dict(i0=8, n_shift=12, m_bits=31, k_out=8)
+    wide = dict(i0=8, n_shift=26, m_bits=46, k_out=8)
+    row = np.array([[64, 16, 8, 0, -8]], np.int8)                # real 8, 2, 1, 0, -1
+    rq = (2 ** 14, 21)                                           # x * 128 -> x
+    elem = orc.shiftgelu(row, narrow, rq)[0]
+    assert elem[1] >= 15 and elem[2] >= 6                        # GELU(2) = 1.94 -> 15 or 16, GELU(1) = 0.85 -> 6 or 7
+    lost = orc.shiftgelu_rowmax(row, narrow, rq)[0]
+    assert lost[0] == elem[0] and lost[2] == 0 and lost[4] == 0 != elem[4]    # both exponent images vanished
+    kept = orc.shiftgelu_rowmax(row, wide, rq)[0]
+    assert np.abs(kept.astype(int) - elem.astype(int)).max() <= 1
+    far = np.array([[127, 16, 8, 0, -8]], np.int8)               # a maximum of 15.9: beyond even the widest 32-bit ShiftExp
+    assert orc.shiftgelu_rowmax(far, wide, rq)[0][1] == 0
+
+
+def test_floor_requantisation_differs_from_the_rounded_one_by_at_most_one_step():
+    """Eq. 10 printed as a bare shift (floor) against Eq. 8's rounding, the reading used everywhere here: the floor is
+    never above, at most one below, and they differ for about half of all values, which is why the rounded form
+    (exactly floor(b v / 2^c + 1/2)) is the one built."""
+    rng = np.random.default_rng(63)
+    v = rng.integers(-2 ** 22, 2 ** 22, size=20000)
+    for b, c in ((23170, 22), (2 ** 14, 20), (32767, 24)):
+        rounded = orc.rnd_shift_vec(v * b, c)
+        floored = (v * b) >> c
+        d = rounded - floored
+        assert d.min() == 0 and d.max() == 1 and 0.4 < d.mean() < 0.6
+        frac = [Fraction(int(x) * b, 2 ** c) for x in v[:200]]
+        assert floored[:200].tolist() == [math.floor(f) for f in frac]
