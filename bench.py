@@ -238,6 +238,8 @@ def main():
         hbm_run("ilayernorm", C, lambda a, o: binding.ivit_ilayernorm(a, ln_p["ln1_gamma"], ln_p["ln1_beta"], o,
                                                                        ln_p["ln1_f_bits"], ln_p["ln1_c_shift"], stream=stream))
         hbm_run("shiftmax", T, lambda a, o: binding.ivit_shiftmax(a, o, sp, stream=stream))
+        wide = dict(i0=32, n_shift=24, m_bits=46, k_out=8)       # the row-maximum variant of ShiftGELU on MLP-hidden rows
+        hbm_run("shiftgelu_rowmax", F, lambda a, o: binding.ivit_shiftgelu_rowmax(a, o, wide, (24171, 21), stream=stream))
         src = torch.ones(half, dtype=torch.int8, device="cuda"); dst = torch.empty_like(src)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         dst.copy_(src); torch.cuda.synchronize()

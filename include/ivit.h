@@ -140,6 +140,16 @@ int ivit_shiftgelu(void* stream, const int8_t* x, int8_t* y, int64_t n,
  * i.e. the tensor before its rescale to int8.  y16 [n] int16, 2-byte aligned. */
 int ivit_shiftgelu_raw(void* stream, const int8_t* x, int16_t* y16, int64_t n, ivit_shift_params p);
 
+/* ShiftGELU with the other reading of Algorithm 2's max(I_p), which names no axis: the maximum over each row,
+ * m = max(0, max_j I_p[row][j]); I_exp = ShiftExp(I_p - m), I_exp' = ShiftExp(-m), I_div = IntDiv(I_exp, I_exp + I_exp')
+ * (0 where both ShiftExp values have shifted out to 0), y = requant(I * I_div; out_rq).  Far from a large row maximum
+ * this form loses the value altogether unless ShiftExp is wide, so here the shift parameters may be wide:
+ * i0 << n_shift <= 2^30 and k_out - 1 <= m_bits <= 46 (the reciprocal of IntDiv is formed in 64 bits).
+ * x, y int8 [rows, cols] dense, 4-byte aligned (y may alias x); rows >= 0, 4 <= cols <= 4096, cols % 4 == 0.
+ * Errors: NULL, SHAPE, PARAM, ALIGN, HIP. */
+int ivit_shiftgelu_rowmax(void* stream, const int8_t* x, int8_t* y, int64_t rows, int32_t cols, ivit_shift_params p,
+                          ivit_dyadic out_rq);
+
 /* I-LayerNorm (Sec. 3.5, Eq. 19-20) on each row of x [rows, C]:
  *   mean = floor((sum x + floor(C/2)) / C);  var = floor(sum (x - mean)^2 / C);
  *   std  = max(1, tenth iterate of I <- (I + floor(var / I)) >> 1 from I = 2^floor(bitlen(var)/2));

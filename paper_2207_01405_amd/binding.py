@@ -20,7 +20,7 @@ EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftg
            "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
            "ivit_forward_image", "ivit_attention_masked", "ivit_window_attention", "ivit_patch_merge_gather",
            "ivit_mean_pool", "ivit_swin_window_index", "ivit_swin_shift_mask", "ivit_swin_workspace_bytes",
-           "ivit_forward_swin")
+           "ivit_forward_swin", "ivit_shiftgelu_rowmax")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
               7: "shiftgelu", 8: "embed_tokens", 9: "patch_merge_gather", 10: "mean_pool"}
@@ -109,6 +109,7 @@ def load():
     lib.ivit_shiftmax.restype = C.c_int
     lib.ivit_shiftmax.argtypes = [_P, _P, _P, i32, i32, _P, i64, i32, i32, ShiftParams]
     lib.ivit_shiftgelu.restype = C.c_int; lib.ivit_shiftgelu.argtypes = [_P, _P, _P, i64, ShiftParams, Dyadic]
+    lib.ivit_shiftgelu_rowmax.restype = C.c_int; lib.ivit_shiftgelu_rowmax.argtypes = [_P, _P, _P, i64, i32, ShiftParams, Dyadic]
     lib.ivit_shiftgelu_raw.restype = C.c_int; lib.ivit_shiftgelu_raw.argtypes = [_P, _P, _P, i64, ShiftParams]
     lib.ivit_ilayernorm.restype = C.c_int; lib.ivit_ilayernorm.argtypes = [_P, _P, _P, _P, _P, i64, i32, i32, i32]
     lib.ivit_workspace_bytes.restype = C.c_size_t; lib.ivit_workspace_bytes.argtypes = [C.POINTER(Dims)]
@@ -249,6 +250,13 @@ def ivit_shiftmax(x, y, p, bias=None, H=1, T=1, cols=None, stream=None):
 def ivit_shiftgelu(x, y, p, out_rq, stream=None):
     st = load().ivit_shiftgelu(_stream(stream), _ptr(x), _ptr(y), x.numel(), shift_params(p), dyadic(out_rq))
     _check(st, "ivit_shiftgelu")
+    return y
+
+
+def ivit_shiftgelu_rowmax(x, y, p, out_rq, stream=None):
+    rows, cols = x.shape
+    st = load().ivit_shiftgelu_rowmax(_stream(stream), _ptr(x), _ptr(y), rows, cols, shift_params(p), dyadic(out_rq))
+    _check(st, "ivit_shiftgelu_rowmax")
     return y
 
 

@@ -209,6 +209,19 @@ int ivit_shiftgelu(void* stream, const int8_t* x, int8_t* y, int64_t n, ivit_shi
     return hip_status(ivit::launch_shiftgelu(static_cast<hipStream_t>(stream), x, y, nullptr, n, sp(p), dy(out_rq)));
 }
 
+int ivit_shiftgelu_rowmax(void* stream, const int8_t* x, int8_t* y, int64_t rows, int32_t cols, ivit_shift_params p,
+                          ivit_dyadic out_rq) {
+    if (rows < 0 || cols < 4 || cols > 4096 || (cols & 3)) return IVIT_ERR_SHAPE;
+    if (rows > 0 && (!x || !y)) return IVIT_ERR_NULL;
+    // the wide form of the shift parameters: ShiftExp values up to 2^30, reciprocal of IntDiv up to 2^46
+    if (p.i0 < 1 || p.n_shift < 0 || p.n_shift > 30 || ((int64_t)p.i0 << p.n_shift) > ((int64_t)1 << 30)) return IVIT_ERR_PARAM;
+    if (p.k_out < 2 || p.k_out > 8 || p.m_bits < p.k_out - 1 || p.m_bits > 46) return IVIT_ERR_PARAM;
+    int st = check_dyadic(out_rq);
+    if (st != IVIT_OK) return st;
+    if (!aligned(x, 4) || !aligned(y, 4)) return IVIT_ERR_ALIGN;
+    return hip_status(ivit::launch_shiftgelu_rowmax(static_cast<hipStream_t>(stream), x, y, rows, cols, sp(p), dy(out_rq)));
+}
+
 int ivit_shiftgelu_raw(void* stream, const int8_t* x, int16_t* y16, int64_t n, ivit_shift_params p) {
     if (n < 0) return IVIT_ERR_SHAPE;
     if (n > 0 && (!x || !y16)) return IVIT_ERR_NULL;

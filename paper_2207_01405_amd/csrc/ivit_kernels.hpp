@@ -17,6 +17,9 @@ hipError_t launch_shiftmax(hipStream_t s, const int8_t* x, const int8_t* bias, i
 hipError_t launch_shiftgelu(hipStream_t s, const int8_t* x, int8_t* y8, int16_t* y16, int64_t n,
                             ShiftParams p, Dyadic out_rq);
 
+hipError_t launch_shiftgelu_rowmax(hipStream_t s, const int8_t* x, int8_t* y, int64_t rows, int cols, ShiftParams p,
+                                   Dyadic rq);
+
 struct LinearArgs {
     const int8_t* x; const int8_t* w; const int32_t* bias; const int32_t* rq_b; const int32_t* rq_c;
     const int8_t* residual; Dyadic res_rq;

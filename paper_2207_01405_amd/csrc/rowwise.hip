@@ -455,6 +455,75 @@ hipError_t launch_shiftgelu(hipStream_t s, const int8_t* x, int8_t* y8, int16_t*
     return hipGetLastError();
 }
 
+// ShiftGELU with the maximum of Algorithm 2 taken over each row (the alternative reading of max(I_p)): m = max(0,
+// max_j I_p[j]).  Given m, the result is a function of the int8 input alone, so each wavefront (one row at a time)
+// finds m with one pass over its registers, tabulates the 256 results for this m in LDS (four entries per lane:
+// ShiftExp of I_p - m, IntDiv with a 64-bit reciprocal since this form needs M above 31, requantisation) and
+// looks every element up.  Entries for inputs above the maximum cannot occur and are skipped.
+template <int NT>
+__global__ __launch_bounds__(256) void shiftgelu_rowmax_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y,
+                                                               int64_t rows, int cols, ShiftParams p, Dyadic rq) {
+    __shared__ int8_t lut_all[4][256];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int8_t* lut = lut_all[wv];
+    const int64_t wave = (int64_t)blockIdx.x * 4 + wv;
+    const int64_t nwaves = (int64_t)gridDim.x * 4;
+    const int ndw = cols >> 2;
+    const int sh = p.m_bits - (p.k_out - 1);
+    auto ip_of = [](int32_t I) { return I + (I >> 1) + (I >> 3) + (I >> 4); };
+    for (int64_t row = wave; row < rows; row += nwaves) {
+        const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + row * cols);
+        uint32_t xv[NT];
+        int32_t mx = -128;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int idx = lane + 64 * t;
+            xv[t] = idx < ndw ? xr[idx] : 0x80808080u;           // padding: -128, never the maximum of a real row
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mx = max(mx, (int32_t)(int8_t)(xv[t] >> (8 * e)));
+        }
+        mx = wave_max(mx);                                       // I_p is increasing in I: the row maximum of I_p is I_p(max I)
+        const int32_t m = max(ip_of(mx), 0);
+        const uint32_t e2 = shiftexp(-m, p.i0, p.n_shift);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int32_t I = (int32_t)(int8_t)(lane + 64 * k);  // the value whose low byte is the table index
+            int32_t out = 0;
+            if (I <= mx) {
+                const uint32_t e1 = shiftexp(ip_of(I) - m, p.i0, p.n_shift);
+                const uint32_t sum = e1 + e2;                    // at most 2^31
+                const uint64_t dv = sum ? ((((uint64_t)1 << p.m_bits) / sum) * e1) >> sh : 0;
+                out = requant64(I * (int32_t)dv, rq.b, rq.c);
+            }
+            lut[lane + 64 * k] = (int8_t)out;
+        }
+        __builtin_amdgcn_wave_barrier();                         // LDS serves a wavefront's accesses in order: the reads below see the table
+        uint32_t* yr = reinterpret_cast<uint32_t*>(y + row * cols);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const int idx = lane + 64 * t;
+            uint32_t o = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o |= ((uint32_t)(uint8_t)lut[(xv[t] >> (8 * e)) & 0xffu]) << (8 * e);
+            if (idx < ndw) yr[idx] = o;
+        }
+        __builtin_amdgcn_wave_barrier();                         // next row's table is written after these reads were issued
+    }
+}
+
+hipError_t launch_shiftgelu_rowmax(hipStream_t s, const int8_t* x, int8_t* y, int64_t rows, int cols, ShiftParams p,
+                                   Dyadic rq) {
+    if (rows == 0) return hipSuccess;
+    const int grid = (int)std::min<int64_t>((rows + 3) / 4, (int64_t)num_cus() * 16);
+    const int nt = (cols / 4 + 63) / 64;
+    TraceScope trace(s, KIND_SHIFTGELU, 0, 2 * rows * cols);
+#define IVIT_RM(NT_) hipLaunchKernelGGL(shiftgelu_rowmax_kernel<NT_>, dim3(grid), dim3(256), 0, s, x, y, rows, cols, p, rq)
+    if (nt <= 1) IVIT_RM(1); else if (nt <= 2) IVIT_RM(2); else if (nt <= 4) IVIT_RM(4); else if (nt <= 6) IVIT_RM(6);
+    else if (nt <= 8) IVIT_RM(8); else if (nt <= 12) IVIT_RM(12); else IVIT_RM(16);
+#undef IVIT_RM
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------------------
 // Token assembly of the embedding layer: class token, patch tokens and position embedding, each int8 at its own
 // scale, brought to the token scale by two dyadic rescales and added (the residual-add rule of Eq. 1-2 applied to

@@ -112,6 +112,13 @@ def test_rowwise_reject_bad_arguments(lib):
     assert ge(None, None, FAKE, 4, SP, DY) == E["NULL"] and ge(None, FAKE, FAKE, -4, SP, DY) == E["SHAPE"]
     assert ge(None, FAKE, FAKE, 4, SP, binding.Dyadic(1, 0)) == E["PARAM"] and ge(None, FAKE, FAKE, 0, SP, DY) == 0
     assert lib.ivit_shiftgelu_raw(None, FAKE, FAKE + 1, 4, SP) == E["ALIGN"]
+    rm = lib.ivit_shiftgelu_rowmax
+    wide = binding.ShiftParams(32, 24, 46, 8)
+    assert rm(None, None, FAKE, 4, 64, wide, DY) == E["NULL"] and rm(None, FAKE, FAKE, -1, 64, wide, DY) == E["SHAPE"]
+    assert rm(None, FAKE, FAKE, 4, 66, wide, DY) == E["SHAPE"] and rm(None, FAKE, FAKE, 4, 4100, wide, DY) == E["SHAPE"]
+    assert rm(None, FAKE, FAKE, 4, 64, binding.ShiftParams(32, 26, 46, 8), DY) == E["PARAM"]      # 32 << 26 > 2^30
+    assert rm(None, FAKE, FAKE, 4, 64, binding.ShiftParams(32, 24, 47, 8), DY) == E["PARAM"]
+    assert rm(None, FAKE + 1, FAKE, 4, 64, wide, DY) == E["ALIGN"] and rm(None, None, None, 0, 64, wide, DY) == 0
     ln = lib.ivit_ilayernorm
     assert ln(None, FAKE, None, FAKE, FAKE, 4, 64, 16, 19) == E["NULL"]
     assert ln(None, FAKE, FAKE, FAKE, FAKE, 4, 66, 16, 19) == E["SHAPE"]

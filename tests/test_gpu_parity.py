@@ -143,6 +143,26 @@ def test_shiftgelu(ivit, n, i0):
         assert_same(host(yb), orc.shiftgelu(x, p, rq), "shiftgelu unaligned")
 
 
+@pytest.mark.parametrize("rows,cols,i0,wide,dist", [
+    (0, 64, 32, True, "normal"), (1, 4, 32, True, "uniform"), (37, 100, 32, True, "normal"), (513, 384, 16, True, "normal"),
+    (300, 1536, 32, True, "student_t"), (65, 3072, 8, True, "normal"), (9, 4096, 32, True, "uniform"), (200, 768, 32, False, "normal"),
+    (64, 1536, 8, False, "student_t"), (40, 256, 4, True, "const")])
+def test_shiftgelu_rowmax(ivit, rows, cols, i0, wide, dist):
+    """The row-maximum reading of Algorithm 2, wide (ShiftExp up to 2^29, 46-bit reciprocal) and 16-bit parameters."""
+    x = synth.make_rows(rows + cols, rows, cols, dist, 1.5 * i0)
+    if rows > 3:
+        x[1] = -np.abs(x[1]); x[2, 0] = 127; x[3] = 127
+    p = dict(i0=i0, n_shift=29 - i0.bit_length(), m_bits=46, k_out=8) if wide else synth.shift_params(i0)
+    rq = (24171, 21)
+    y = empty((rows, cols))
+    ivit.ivit_shiftgelu_rowmax(dev(x), y, p, rq)
+    assert_same(host(y), orc.shiftgelu_rowmax(x, p, rq) if rows else x, "shiftgelu with the row maximum")
+    if rows:
+        z = dev(x)
+        ivit.ivit_shiftgelu_rowmax(z, z, p, rq)                     # in place
+        assert_same(host(z), orc.shiftgelu_rowmax(x, p, rq), "shiftgelu with the row maximum, in place")
+
+
 # ------------------------------------------------------------------ Dense / MatMul + requant
 LIN_SHAPES = [(0, 64, 64), (1, 1, 16), (5, 7, 80), (65, 192, 64), (130, 40, 256), (129, 100, 48), (1000, 384, 384),
               (197, 1536, 384), (300, 384, 1536), (257, 130, 3072), (64, 256, 16),
