@@ -103,6 +103,16 @@ __device__ __forceinline__ uint32_t div_small(uint32_t v, uint32_t x) {
     return q;
 }
 
+// ShiftExp for arguments of small magnitude (|I| < 2^20, as every int8-derived argument is): the same value as
+// shiftexp() with the division by I_0 done through div_small.
+__device__ __forceinline__ uint32_t shiftexp_small(int32_t I, int32_t i0, int32_t n_shift) {
+    const int32_t Ip = I + (I >> 1) - (I >> 4);
+    const int32_t q = (int32_t)div_small((uint32_t)(-Ip), (uint32_t)i0);
+    const int32_t r = -Ip - q * i0;
+    const int32_t Ib = ((-r) >> 1) + i0;
+    return q > 31 ? 0u : (((uint32_t)Ib << n_shift) >> q);
+}
+
 // Tenth iterate of I <- (I + floor(v / I)) >> 1 from I = 2^floor(bitlen(v) / 2) (Eq. 20); 0 for v = 0.
 __device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
     if (v == 0) return 0;

@@ -471,6 +471,7 @@ __global__ __launch_bounds__(256) void shiftgelu_rowmax_kernel(const int8_t* __r
     const int ndw = cols >> 2;
     const int sh = p.m_bits - (p.k_out - 1);
     auto ip_of = [](int32_t I) { return I + (I >> 1) + (I >> 3) + (I >> 4); };
+    const double two_m = (double)((uint64_t)1 << p.m_bits);
     for (int64_t row = wave; row < rows; row += nwaves) {
         const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + row * cols);
         uint32_t xv[NT];
@@ -484,15 +485,19 @@ __global__ __launch_bounds__(256) void shiftgelu_rowmax_kernel(const int8_t* __r
         }
         mx = wave_max(mx);                                       // I_p is increasing in I: the row maximum of I_p is I_p(max I)
         const int32_t m = max(ip_of(mx), 0);
-        const uint32_t e2 = shiftexp(-m, p.i0, p.n_shift);
+        const uint32_t e2 = shiftexp_small(-m, p.i0, p.n_shift);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int32_t I = (int32_t)(int8_t)(lane + 64 * k);  // the value whose low byte is the table index
             int32_t out = 0;
             if (I <= mx) {
-                const uint32_t e1 = shiftexp(ip_of(I) - m, p.i0, p.n_shift);
+                const uint32_t e1 = shiftexp_small(ip_of(I) - m, p.i0, p.n_shift);
                 const uint32_t sum = e1 + e2;                    // at most 2^31
-                const uint64_t dv = sum ? ((((uint64_t)1 << p.m_bits) / sum) * e1) >> sh : 0;
+                // floor(2^M / sum), M <= 46, through one double-precision division: the quotient is correctly rounded
+                // and, when it is not an integer, lies at least 1 / sum below the next one, which is more than half
+                // a unit in the last place of any quotient up to 2^52; so the truncation is the exact floor
+                const uint64_t inv = sum ? (uint64_t)(two_m / (double)sum) : 0;
+                const uint64_t dv = (inv * e1) >> sh;
                 out = requant64(I * (int32_t)dv, rq.b, rq.c);
             }
             lut[lane + 64 * k] = (int8_t)out;
