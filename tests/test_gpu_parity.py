@@ -167,7 +167,9 @@ def test_shiftgelu_rowmax(ivit, rows, cols, i0, wide, dist):
 LIN_SHAPES = [(0, 64, 64), (1, 1, 16), (5, 7, 80), (65, 192, 64), (130, 40, 256), (129, 100, 48), (1000, 384, 384),
               (197, 1536, 384), (300, 384, 1536), (257, 130, 3072), (64, 256, 16),
               # weight-stationary kernel: partial channel slabs, one-chunk K, even / odd unit counts, many groups per wavefront
-              (333, 208, 96), (40, 16, 32), (515, 2304, 768), (30011, 128, 384), (2100, 768, 1152), (77, 1168, 640)]
+              (333, 208, 96), (40, 16, 32), (515, 2304, 768), (30011, 128, 384), (2100, 768, 1152), (77, 1168, 640),
+              # the largest K the entry point takes, and many short rows
+              (3, 16, 65536), (70001, 16, 16)]
 
 
 @pytest.mark.parametrize("M,N,K", LIN_SHAPES)
@@ -206,6 +208,24 @@ def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit):
         want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
         assert_same(host(y), want, "linear general")
         assert np.abs(want.astype(np.int32)).mean() > 2
+
+
+def test_linear_requant_largest_accumulators(ivit):
+    """K = 65536 with every operand at +-127: the dot products reach +-65536 * 127^2 = +-1.057e9, the largest an int32
+    accumulator of this entry point ever holds; shifts chosen so that results spread over the int8 range."""
+    M, N, K = 8, 32, 65536
+    x = np.full((M, K), 127, np.int8); x[1] = -127; x[2, ::2] = -127; x[3, : K // 4] = -127; x[4:] = synth.make_rows(1, 4, K, "uniform")
+    w = np.full((N, K), 127, np.int8); w[1::2] = -127; w[2, ::3] = 0; w[5] = synth.make_rows(2, 1, K, "uniform")[0]
+    bias = np.linspace(-2 ** 20, 2 ** 20, N).astype(np.int32)
+    rq_c = np.full(N, 24, np.int32); rq_c[8:16] = 31; rq_c[16:24] = 40
+    rq_b = np.full(N, 3, np.int32); rq_b[8:16] = 200; rq_b[16:24] = 2 ** 17 + 1; rq_b[24:] = 1
+    for kw_o, kw_g in (({}, {}), (dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)),) * 2):
+        y = empty((M, N))
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, **kw_g)
+        want = orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o)
+        assert_same(host(y), want, "linear with the largest accumulators")
+    plain = orc.linear_requant(x, w, bias, rq_b, rq_c)
+    assert (np.abs(plain) == 127).any() and (np.abs(plain) < 127).mean() > 0.3
 
 
 @pytest.mark.parametrize("K", [128, 1536])
