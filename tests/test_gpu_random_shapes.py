@@ -1,0 +1,180 @@
+"""GPU parity on seeded random shapes and parameters.
+
+The named cases of test_gpu_parity.py pick shapes by hand; this module draws them (fixed seeds, so every run sees
+the same cases) to cross the kernels' internal boundaries in combinations nobody thought of: channel slabs of 64 and
+128 with partial tails, K in one or several 128-byte chunks with and without padding, even and odd unit counts, the
+24-bit / 64-bit / general requantisation paths, 4 to 16 key tiles, both head widths, bias and mask.
+Every case is compared bit for bit with the CPU oracle; sizes keep the oracle at a few seconds for the whole module.
+"""
+import numpy as np
+import pytest
+
+import oracle as orc
+from paper_2207_01405_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    import torch
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def empty(shape):
+    import torch
+    return torch.empty(shape, dtype=torch.int8, device="cuda")
+
+
+def same(got, want, what):
+    if not np.array_equal(got, want):
+        bad = np.argwhere(np.asarray(got) != np.asarray(want))
+        raise AssertionError("%s: %d of %d elements differ, first at %s" % (what, len(bad), np.size(want), tuple(bad[0])))
+
+
+def _dense_params(rng, N, K, regime):
+    """Per-channel (b, c) and bias in one of the regimes the epilogue distinguishes."""
+    sig = np.sqrt(K) * 73.0 * 40.0                       # accumulator spread: uniform activations, normal-ish weights
+    if regime == "narrow":                               # c <= 24, b well below 2^(c-1)
+        c = rng.integers(16, 25, size=N)
+        b = np.array([max(1, int(30.0 * 2.0 ** cc / sig * rng.uniform(0.5, 2.0))) for cc in c])
+        b = np.minimum(b, 2 ** (c - 1) - 1)
+    elif regime == "fits32":                             # c up to 31, b <= 2^c
+        c = rng.integers(25, 32, size=N)
+        b = np.array([max(1, int(30.0 * 2.0 ** cc / sig * rng.uniform(0.5, 2.0))) for cc in c])
+        b = np.minimum(b, 2 ** 31 - 1)
+    else:                                                # anything the interface allows
+        c = rng.integers(1, 47, size=N)
+        b = np.array([int(np.clip(30.0 * 2.0 ** cc / sig * rng.uniform(0.5, 2.0), 1, 2 ** 31 - 1)) for cc in c])
+    bias = rng.integers(-int(2 * sig), int(2 * sig) + 1, size=N)
+    return b.astype(np.int32), c.astype(np.int32), bias.astype(np.int32)
+
+
+@pytest.mark.parametrize("seed", range(36))
+def test_linear_random(ivit, seed):
+    rng = np.random.default_rng(1000 + seed)
+    K = 16 * int(rng.choice([1, 2, 3, 5, 6, 8, 12, 16, 24, 25, 48, 96, 100, 192]))
+    N = int(rng.choice([16, 48, 64, 80, 128, 144, 256, 400, 1000, 7, 33])) if seed % 3 else 16 * int(rng.integers(1, 60))
+    M = int(rng.choice([1, 31, 32, 33, 255, 700, 2049, 5000]))
+    M = max(1, min(M, int(4e8 / (N * K))))                   # keeps the oracle's triple loop under a second
+    regime = ("narrow", "fits32", "general")[seed % 3] if seed % 4 else "narrow"
+    epi = ("plain", "residual", "gelu")[(seed // 3) % 3]
+    x = synth.make_rows(seed, M, K, "uniform")
+    w = np.clip(np.rint(rng.standard_normal((N, K)) * 40.0), -127, 127).astype(np.int8)
+    b, c, bias = _dense_params(rng, N, K, regime)
+    use_bias = seed % 5 != 0
+    kw_o, kw_g = {}, {}
+    if epi == "residual":
+        res = synth.make_rows(seed + 1, M, N, "uniform")
+        rq = (int(rng.integers(2 ** 14, 2 ** 15)), 15) if seed % 2 else (int(rng.integers(1, 2 ** 31)), int(rng.integers(31, 40)))
+        kw_o = dict(residual=res, res_rq=rq); kw_g = dict(residual=dev(res), res_rq=rq)
+    elif epi == "gelu":
+        i0 = int(rng.choice([4, 11, 32, 64, 200]))
+        kw_o = dict(gelu=synth.shift_params(i0), gelu_rq=(int(rng.integers(2 ** 14, 2 ** 15)), int(rng.integers(19, 23)))); kw_g = dict(kw_o)
+    y = empty((M, N))
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias) if use_bias else None, dev(b), dev(c), y, **kw_g)
+    want = orc.linear_requant(x, w, bias if use_bias else None, b, c, **kw_o)
+    same(host(y), want, "linear M=%d N=%d K=%d %s %s" % (M, N, K, regime, epi))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_attention_random(ivit, seed):
+    rng = np.random.default_rng(2000 + seed)
+    D = int(rng.choice([32, 64]))
+    H = int(rng.choice([1, 2, 3, 5]))
+    C = D * H
+    T = int(rng.choice([1, 7, 16, 17, 49, 64, 65, 100, 128, 197, 209, 256]))
+    B = int(rng.choice([1, 2, 5])) if T > 100 else int(rng.choice([1, 3, 9, 20]))
+    d = dict(B=B, T=T, C=C, H=H, F=4 * C)
+    i0 = int(rng.choice([3, 8, 32, 100, 500]))
+    sm = synth.shift_params(i0)
+    qk = (int(rng.integers(2 ** 14, 2 ** 15)), int(rng.integers(19, 23)))
+    pv = (int(rng.integers(2 ** 14, 2 ** 15)), int(rng.integers(19, 23)))
+    if seed % 6 == 5:                                        # pairs outside the 32-bit range
+        qk = (int(rng.integers(2 ** 28, 2 ** 31)), 35); pv = (int(rng.integers(2 ** 28, 2 ** 31)), 36)
+    qkv = synth.make_rows(seed, B * T, 3 * C, "normal", float(rng.choice([8.0, 32.0, 60.0])))
+    rb = np.clip(np.rint(rng.standard_normal((H, T, T)) * 30), -127, 127).astype(np.int8) if seed % 2 else None
+    mask = None
+    if seed % 3 == 0:
+        n_mask = int(rng.choice([1, 2, 3]))
+        mask = (rng.random((n_mask, T, T)) < 0.3).astype(np.int8)
+        mask[:, np.arange(T), np.arange(T)] = 0
+    want, _, pr_ref = orc.attention(qkv, d, qk, sm, pv, rb, want_taps=True, mask=mask)
+    for taps in (False, True):
+        o = empty((B * T, C)); pr = empty((B, H, T, T)) if taps else None
+        ivit.ivit_attention(dev(qkv), o, d, qk, sm, pv, rel_bias=None if rb is None else dev(rb),
+                            mask=None if mask is None else dev(mask), tap_probs=pr)
+        same(host(o), want, "attention B=%d T=%d H=%d D=%d taps=%s" % (B, T, H, D, taps))
+        if taps:
+            same(host(pr), pr_ref, "attention probabilities")
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_rowwise_random(ivit, seed):
+    rng = np.random.default_rng(3000 + seed)
+    rows = int(rng.choice([1, 2, 63, 64, 65, 1000, 4097]))
+    # I-LayerNorm
+    C = 4 * int(rng.choice([1, 3, 16, 24, 48, 96, 100, 192, 256, 300, 384, 512]))
+    x = synth.make_rows(seed, rows, C, ("normal", "uniform", "student_t")[seed % 3], 30.0)
+    g = np.rint((1.0 + 0.2 * rng.standard_normal(C)) * 256).astype(np.int32)
+    bt = np.rint(0.2 * rng.standard_normal(C) * 2 ** 24).astype(np.int32)
+    # (F, c) pairs that keep |dev f gamma + beta| inside 31 bits for these rows, the operator's stated precondition
+    fb, cs = [(12, 15), (16, 19), (16, 17), (14, 18)][int(rng.integers(0, 4))]
+    y = empty((rows, C))
+    ivit.ivit_ilayernorm(dev(x), dev(g), dev(bt), y, fb, cs)
+    same(host(y), orc.ilayernorm(x, g, bt, fb, cs), "ilayernorm rows=%d C=%d F=%d c=%d" % (rows, C, fb, cs))
+    # Shiftmax, with and without a leading dimension and a bias
+    cols = int(rng.choice([1, 2, 15, 16, 17, 49, 64, 100, 197, 255, 256, 257, 600, 1024]))
+    ld = cols + int(rng.choice([0, 0, 3, 16]))
+    i0 = int(rng.choice([2, 8, 32, 77, 1000]))
+    xs = synth.make_rows(seed + 7, rows, ld, "normal", float(rng.choice([10.0, 40.0])))
+    ys = empty((rows, cols))
+    ivit.ivit_shiftmax(dev(xs), ys, synth.shift_params(i0), cols=cols)
+    same(host(ys), orc.shiftmax(xs, synth.shift_params(i0), cols=cols), "shiftmax rows=%d cols=%d ld=%d i0=%d" % (rows, cols, ld, i0))
+    if seed % 2:
+        Hh, Tt = int(rng.choice([1, 3])), int(rng.choice([1, 5, 49]))
+        bias = np.clip(np.rint(rng.standard_normal((Hh, Tt, cols)) * 30), -127, 127).astype(np.int8)
+        ivit.ivit_shiftmax(dev(xs), ys, synth.shift_params(i0), bias=dev(bias), H=Hh, T=Tt, cols=cols)
+        same(host(ys), orc.shiftmax(xs, synth.shift_params(i0), bias=bias, H=Hh, T=Tt, cols=cols), "shiftmax with bias")
+    # ShiftGELU, both readings
+    n = rows * C
+    gq = (int(rng.integers(2 ** 14, 2 ** 15)), int(rng.integers(19, 23)))
+    yg = empty((n,))
+    ivit.ivit_shiftgelu(dev(x.reshape(-1)), yg, synth.shift_params(i0 if i0 <= 255 else 32), gq)
+    same(host(yg), orc.shiftgelu(x.reshape(-1), synth.shift_params(i0 if i0 <= 255 else 32), gq), "shiftgelu")
+    wide = dict(i0=min(i0, 255), n_shift=29 - min(i0, 255).bit_length(), m_bits=int(rng.choice([31, 40, 46])), k_out=8)
+    yr = empty((rows, C))
+    ivit.ivit_shiftgelu_rowmax(dev(x), yr, wide, gq)
+    same(host(yr), orc.shiftgelu_rowmax(x, wide, gq), "shiftgelu with the row maximum")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_block_random(ivit, seed):
+    """Whole blocks on random widths, with every intermediate tensor."""
+    import torch
+    rng = np.random.default_rng(4000 + seed)
+    D = int(rng.choice([32, 64]))
+    H = int(rng.choice([1, 2, 3, 4]))
+    C = D * H
+    T = int(rng.choice([5, 16, 49, 65, 130]))
+    B = int(rng.choice([1, 2, 4]))
+    F = 16 * int(rng.choice([4, 9, 16, C // 4]))
+    cfg = dict(T=T, C=C, H=H, F=F, seed=40 + seed, i0=("fixed", "loguniform")[seed % 2], rel_bias=bool(seed % 3 == 0))
+    p = synth.make_block(cfg, seed)
+    d = dict(B=B, T=T, C=C, H=H, F=F)
+    x = synth.quantize_act(rng.standard_normal((B * T, C)))
+    y_ref, t_ref = orc.encoder_block(x, p, d, want_taps=True)
+    R = B * T
+    ws = torch.empty(ivit.ivit_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    taps = {"u": empty((R, C)), "qkv": empty((R, 3 * C)), "scores": empty((B, H, T, T)), "probs": empty((B, H, T, T)),
+            "o": empty((R, C)), "xhat": empty((R, C)), "v": empty((R, C)), "h": empty((R, F))}
+    y = empty((R, C))
+    ivit.ivit_encoder_block(dev(x), y, ivit.to_device(p), d, ws, taps=taps)
+    for k in orc.TAP_NAMES:
+        same(host(taps[k]), t_ref[k], "block tensor %s (B=%d T=%d C=%d H=%d F=%d)" % (k, B, T, C, H, F))
+    same(host(y), y_ref, "block output")
