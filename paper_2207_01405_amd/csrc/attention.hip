@@ -48,7 +48,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                                                         const int8_t* __restrict__ rel_bias,
                                                         const int8_t* __restrict__ mask, int n_mask,
                                                         const int32_t* __restrict__ tok_index, int n_win,
-                                                        int8_t* __restrict__ o, int n_items, int T, int C, int H,
+                                                        int8_t* __restrict__ o, int n_items, int split, int T, int C, int H,
                                                         Dyadic qk, ShiftParams sm, Dyadic pv,
                                                         int8_t* __restrict__ tap_s, int8_t* __restrict__ tap_p) {
     constexpr int KROW = D + 16;                  // K row pitch (bytes)
@@ -87,8 +87,8 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
     const int tpi = n_win * T;                     // tokens per image
     const bool gather = BIAS && tok_index != nullptr;
     int kvrow[NPC], qrow0 = 0, kvnext[NPC], qnext = 0;
-    auto fetch_rows = [&](int item, int (&kv)[NPC], int& qr) {
-        const int b = item / H;
+    auto fetch_rows = [&](int work, int (&kv)[NPC], int& qr) {
+        const int item = work / split, b = item / H;
         const int32_t* tr = tok_index + (b % n_win) * T;
         const int r0 = (b / n_win) * tpi;
 #pragma unroll
@@ -96,11 +96,17 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             const int key = min((tid + ATT_THREADS * it) / DCH, T - 1);
             kv[it] = r0 + (int)min((uint32_t)tr[key], (uint32_t)(tpi - 1));
         }
-        qr = r0 + (int)min((uint32_t)tr[min(wv * 16 + li, T - 1)], (uint32_t)(tpi - 1));
+        qr = r0 + (int)min((uint32_t)tr[min((work % split + split * wv) * 16 + li, T - 1)], (uint32_t)(tpi - 1));
     };
-    if (BIAS) { if (gather && first < n_items) fetch_rows(first, kvrow, qrow0); }
+    // a work item is one (window, head) or, with split > 1, every split-th query tile of it: when there are too few
+    // (window, head) pairs to give every workgroup slot of the device one, each pair is shared by `split` workgroups
+    // (K and V are staged by each of them; they are small)
+    const int n_work = n_items * split;
+    if (BIAS) { if (gather && first < n_work) fetch_rows(first, kvrow, qrow0); }
 
-    for (int item = first; item < n_items; item += G) {
+    for (int work = first; work < n_work; work += G) {
+        const int item = work / split, part = work % split;
+        const int qt0 = part + split * wv;         // this wavefront's first query tile
         const int b = item / H, h = item % H;
         const int8_t* base = qkv + h * D;
         const int32_t* trow = gather ? tok_index + (b % n_win) * T : nullptr;
@@ -110,7 +116,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             return row0 + t;
         };
         auto q_row = [&](int qt) -> int64_t {      // row of this lane's query of tile qt
-            if (BIAS) { if (gather && qt == wv) return qrow0; }
+            if (BIAS) { if (gather && qt == qt0) return qrow0; }
             return row_of(min(qt * 16 + li, T - 1));
         };
         __syncthreads();                           // table ready / previous item's readers done
@@ -119,7 +125,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
         auto load_q32 = [&](int qt) { return *reinterpret_cast<const long*>(base + q_row(qt) * 3 * C + 8 * lg); };
         v4i qn64 = {0, 0, 0, 0};
         long qn32 = 0;
-        if (D == 64) qn64 = load_q64(wv); else qn32 = load_q32(wv);
+        if (D == 64) qn64 = load_q64(qt0); else qn32 = load_q32(qt0);
         // all of this thread's K and V pieces are requested before the first one is used: one memory latency per item
         v4i kreg[NPC], vreg[NPC];
 #pragma unroll
@@ -132,10 +138,10 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             kreg[it] = *reinterpret_cast<const v4i*>(kv_row + C);
             vreg[it] = *reinterpret_cast<const v4i*>(kv_row + 2 * C);
         }
-        const int64_t orow0 = q_row(wv);           // output row of the first query tile (before the indices move on)
+        const int64_t orow0 = q_row(qt0);          // output row of the first query tile (before the indices move on)
         if (BIAS) {
-            if (gather && item + G < n_items) {
-                fetch_rows(item + G, kvnext, qnext);
+            if (gather && work + G < n_work) {
+                fetch_rows(work + G, kvnext, qnext);
 #pragma unroll
                 for (int it = 0; it < NPC; ++it) kvrow[it] = kvnext[it];
                 qrow0 = qnext;
@@ -159,14 +165,14 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
         }
         __syncthreads();
 
-        for (int qt = wv; qt < nqt; qt += ATT_WAVES) {
+        for (int qt = qt0; qt < nqt; qt += split * ATT_WAVES) {
             const int q = qt * 16 + li;            // this lane's query token
             const int qc = min(q, T - 1);
             int32_t sc[NKT][4];
             // ---- scores: S^T tile t = K_t (16 keys x D) . Q^T (D x 16 queries)
             if (D == 64) {
                 const v4i qf = qn64;
-                qn64 = load_q64(qt + ATT_WAVES);
+                qn64 = load_q64(qt + split * ATT_WAVES);
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) {
                     const v4i kf = *reinterpret_cast<const v4i*>(&Ks[(16 * t + li) * KROW + 16 * lg]);
@@ -176,7 +182,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 }
             } else {
                 const long qf = qn32;
-                qn32 = load_q32(qt + ATT_WAVES);
+                qn32 = load_q32(qt + split * ATT_WAVES);
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) {
                     const long kf = *reinterpret_cast<const long*>(&Ks[(16 * t + li) * KROW + 8 * lg]);
@@ -321,7 +327,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 ow[n] = w;
             }
             if (q < T) {
-                int8_t* op = o + (qt == wv ? orow0 : row_of(q)) * C + h * D + lg * (D / 4);
+                int8_t* op = o + (qt == qt0 ? orow0 : row_of(q)) * C + h * D + lg * (D / 4);
                 if (D == 64) *reinterpret_cast<uint4*>(op) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
                 else *reinterpret_cast<uint2*>(op) = make_uint2(ow[0], ow[1 % ND]);
             }
@@ -330,11 +336,11 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 }
 
 template <int D, int NKT>
-static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, bool taps, bool bias, bool fast) {
+static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, int split, bool taps, bool bias, bool fast) {
     const int n_items = a.B * a.H;
 #define IVIT_ATT(TAPS_, BIAS_, MASK_, FAST_)                                                                       \
     hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, MASK_, FAST_>), dim3(grid), dim3(ATT_THREADS), 0, s, a.qkv, \
-                       a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores,    \
+                       a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items, split, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores,    \
                        a.tap_probs)
     // the production paths are <no taps, fast>; everything else shares one fully general instantiation per bias / mask
     // combination (a mask is always compiled with the bias code, which tests the bias pointer)
@@ -352,11 +358,11 @@ static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, bool t
 }
 
 template <int D>
-static hipError_t launch_d(hipStream_t s, const AttentionArgs& a, int grid, int nkt, bool taps, bool bias, bool fast) {
-    if (nkt <= 4) launch_flags<D, 4>(s, a, grid, taps, bias, fast);
-    else if (nkt <= 8) launch_flags<D, 8>(s, a, grid, taps, bias, fast);
-    else if (nkt <= 13) launch_flags<D, 13>(s, a, grid, taps, bias, fast);
-    else launch_flags<D, 16>(s, a, grid, taps, bias, fast);
+static hipError_t launch_d(hipStream_t s, const AttentionArgs& a, int grid, int split, int nkt, bool taps, bool bias, bool fast) {
+    if (nkt <= 4) launch_flags<D, 4>(s, a, grid, split, taps, bias, fast);
+    else if (nkt <= 8) launch_flags<D, 8>(s, a, grid, split, taps, bias, fast);
+    else if (nkt <= 13) launch_flags<D, 13>(s, a, grid, split, taps, bias, fast);
+    else launch_flags<D, 16>(s, a, grid, split, taps, bias, fast);
     return hipGetLastError();
 }
 
@@ -365,8 +371,12 @@ static bool fits32_host(Dyadic d) { return d.c >= 1 && d.c <= 31 && d.b >= 1 && 
 hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     const int64_t n_items = (int64_t)a.B * a.H;
     if (n_items == 0) return hipSuccess;
-    const int grid = (int)std::min<int64_t>(n_items, (int64_t)num_cus() * 4);
     const int nkt = (a.T + 15) / 16;
+    // With fewer (window, head) pairs than compute units, several workgroups share a pair (each takes every split-th
+    // query tile) so that the device is filled: about two workgroups per CU, at least one tile per wavefront.  With
+    // more pairs than that sharing only adds staging work (measured: 768 pairs, 30 us unshared, 33 us shared by two).
+    const int split = (int)std::max<int64_t>(1, std::min<int64_t>(2 * (int64_t)num_cus() / n_items, nkt / ATT_WAVES));
+    const int grid = (int)std::min<int64_t>(n_items * split, (int64_t)num_cus() * 4);
     const int d = a.C / a.H;
     const int sh = a.sm.m_bits - (a.sm.k_out - 1);
     const bool fast = fits32_host(a.qk_rq) && fits32_host(a.pv_rq) && sh >= 1 &&
@@ -375,7 +385,7 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     const int64_t R = (int64_t)a.B * a.T;
     TraceScope trace(s, KIND_ATTENTION, 4 * n_items * a.T * a.T * d, 4 * R * a.C + (a.rel_bias ? (int64_t)a.H * a.T * a.T : 0));
     const bool bias = a.rel_bias != nullptr || a.mask != nullptr || a.tok_index != nullptr;
-    return d == 64 ? launch_d<64>(s, a, grid, nkt, taps, bias, fast) : launch_d<32>(s, a, grid, nkt, taps, bias, fast);
+    return d == 64 ? launch_d<64>(s, a, grid, split, nkt, taps, bias, fast) : launch_d<32>(s, a, grid, split, nkt, taps, bias, fast);
 }
 
 }  // namespace ivit
