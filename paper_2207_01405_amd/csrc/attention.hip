@@ -43,14 +43,17 @@ __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d) {
 
 // FAST: both dyadic pairs are rescales by at most 1 with c <= 31 (32-bit requantisation) and the row sum always
 // exceeds 2^(k_out-1), so that IntDiv is one multiply-high by the pre-shifted reciprocal.
-template <int D, int NKT, bool TAPS, bool BIAS, bool MASK, bool FAST>
+// TFIX: 0, or the token count known at compile time (49, the 7 x 7 windows): every test of a key or query against T then
+// folds, and the fifteen absent keys of the last key tile cost nothing.
+template <int D, int NKT, bool TAPS, bool BIAS, bool MASK, bool FAST, int TFIX = 0>
 __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
                                                         const int8_t* __restrict__ mask, int n_mask,
                                                         const int32_t* __restrict__ tok_index, int n_win,
-                                                        int8_t* __restrict__ o, int n_items, int split, int T, int C, int H,
+                                                        int8_t* __restrict__ o, int n_items, int split, int T_arg, int C, int H,
                                                         Dyadic qk, ShiftParams sm, Dyadic pv,
                                                         int8_t* __restrict__ tap_s, int8_t* __restrict__ tap_p) {
+    const int T = TFIX ? TFIX : T_arg;
     constexpr int KROW = D + 16;                  // K row pitch (bytes)
     constexpr int NKC = (NKT + 3) / 4;            // 64-key chunks of the P V contraction
     constexpr int VROW = NKC * 64 + 16;           // V^T row pitch (bytes)
@@ -345,7 +348,16 @@ static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, int sp
     // the production paths are <no taps, fast>; everything else shares one fully general instantiation per bias / mask
     // combination (a mask is always compiled with the bias code, which tests the bias pointer)
     const bool masked = a.mask != nullptr;
-    if (!taps && fast) {
+    if (D == 32 && NKT == 4 && a.T == 49 && !taps && fast && bias) {          // the windowed models' shape
+        if (masked)
+            hipLaunchKernelGGL((attention_kernel<D, NKT, false, true, true, true, (D == 32 && NKT == 4) ? 49 : 0>), dim3(grid),
+                               dim3(ATT_THREADS), 0, s, a.qkv, a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items,
+                               split, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs);
+        else
+            hipLaunchKernelGGL((attention_kernel<D, NKT, false, true, false, true, (D == 32 && NKT == 4) ? 49 : 0>), dim3(grid),
+                               dim3(ATT_THREADS), 0, s, a.qkv, a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items,
+                               split, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs);
+    } else if (!taps && fast) {
         if (masked) IVIT_ATT(false, true, true, true);
         else if (bias) IVIT_ATT(false, true, false, true);
         else IVIT_ATT(false, false, false, true);
