@@ -388,7 +388,12 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     // query tile) so that the device is filled: about two workgroups per CU, at least one tile per wavefront.  With
     // more pairs than that sharing only adds staging work (measured: 768 pairs, 30 us unshared, 33 us shared by two).
     const int split = (int)std::max<int64_t>(1, std::min<int64_t>(2 * (int64_t)num_cus() / n_items, nkt / ATT_WAVES));
-    const int grid = (int)std::min<int64_t>(n_items * split, (int64_t)num_cus() * 4);
+    // workgroups per CU: windows of at most 64 tokens need little LDS and few registers, and their short items are
+    // bound by latency, so many more workgroups are kept in flight (8192 windows x 3 heads: 86 us with 4, 72 us with 16)
+    // (up to 16 per CU, as long as each still loops over about four items, which keeps the rounds even)
+    const int64_t n_work = n_items * split, cus = num_cus();
+    const int64_t wgs = nkt <= 4 ? std::max<int64_t>(4 * cus, std::min<int64_t>(16 * cus, n_work / 4)) : 4 * cus;
+    const int grid = (int)std::min<int64_t>(n_work, wgs);
     const int d = a.C / a.H;
     const int sh = a.sm.m_bits - (a.sm.k_out - 1);
     const bool fast = fits32_host(a.qk_rq) && fits32_host(a.pv_rq) && sh >= 1 &&
