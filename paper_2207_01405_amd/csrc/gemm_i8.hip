@@ -553,14 +553,15 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         // 32 memory lines.  Through the staging rows each store instruction writes whole rows instead: 2 NCB
         // adjacent lanes cover the 32 NCB bytes of one token.
         __builtin_amdgcn_wave_barrier();
-        constexpr int LPR = 2 * NCB, RPI = 64 / LPR;    // lanes per row, rows per store instruction
+        constexpr int LPR = 2 * NCB, RPI = 64 / LPR;    // lanes per row, rows per store instruction (NCB = 3: 4 lanes idle)
         const int srow = lane / LPR, piece = lane % LPR;
 #pragma unroll
-        for (int t = 0; t < NCB; ++t) {
+        for (int t = 0; t * RPI < 32; ++t) {
             const int row = t * RPI + srow;
-            const v4i v = *reinterpret_cast<const v4i*>(stage + row * SP + 16 * piece);
+            const bool mine = srow < RPI && row < 32;
+            const v4i v = *reinterpret_cast<const v4i*>(stage + (mine ? row : 0) * SP + 16 * piece);
             const int64_t tk = cgrp * 32 + row;
-            if (tk < M && n0 + 16 * piece < N) *reinterpret_cast<v4i*>(P.y + tk * N + n0 + 16 * piece) = v;
+            if (mine && tk < M && n0 + 16 * piece < N) *reinterpret_cast<v4i*>(P.y + tk * N + n0 + 16 * piece) = v;
         }
         __builtin_amdgcn_wave_barrier();
     };
@@ -593,7 +594,20 @@ static bool ws_plan(const LinearArgs& a, int& ncb, int& unit, int& nunits, int& 
     // 128-channel slabs halve the activation traffic per MFMA; with fewer than six of them the 64-channel slabs'
     // finer work items fill the wavefronts more evenly
     int ncb0 = (a.N + 127) / 128 >= 6 ? 4 : 2;
-    for (ncb = ncb0; ncb >= 2; ncb >>= 1) {
+    // With many token groups per wavefront (65536 rows and more) the rounds are long enough to be counted: a slab
+    // width of 128, 96 or 64 channels is picked by rounds x (tiles per unit + fixed work per unit), which puts the
+    // widths of the windowed models' first stages (288 = 3 x 96, 96, 576) on 96-channel slabs without empty tiles.
+    const int64_t groups = (a.M + 31) / 32;
+    if (groups >= 2048) {
+        double best = 0.0;
+        for (int n = 4; n >= 2; --n) {
+            const int slabs = (a.N + 32 * n - 1) / (32 * n);
+            const int64_t waves = (int64_t)WS_WAVES * std::max(1, num_cus() / slabs);
+            const double cost = (double)((groups + waves - 1) / waves) * (n + 1.2);
+            if (n == 4 || cost < best) { best = cost; ncb0 = n; }
+        }
+    }
+    for (ncb = ncb0; ncb >= 2; --ncb) {
         lds_bytes = (size_t)32 * ncb * pitch + 9 * 4 * 32 * ncb + 256 + (size_t)WS_WAVES * std::max(32 * (32 * ncb + 16), 32 * (WS_CHUNK + 16));
         if (lds_bytes <= (size_t)WS_LDS_MAX) return true;
     }
@@ -611,6 +625,7 @@ static void launch_ws_ncb(hipStream_t s, const WsParams& W, int unit, int grid, 
 template <int EPI>
 static void launch_ws(hipStream_t s, const WsParams& W, int ncb, int unit, int grid, size_t lds_bytes) {
     if (ncb == 4) launch_ws_ncb<EPI, 4>(s, W, unit, grid, lds_bytes);
+    else if (ncb == 3) launch_ws_ncb<EPI, 3>(s, W, unit, grid, lds_bytes);
     else launch_ws_ncb<EPI, 2>(s, W, unit, grid, lds_bytes);
 }
 
