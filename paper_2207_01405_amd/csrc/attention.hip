@@ -36,8 +36,19 @@ __device__ __forceinline__ int vt_pos(int k) {
     return (k & ~63) + ((k >> 2) & 3) * 16 + ((k >> 4) & 3) * 4 + (k & 3);
 }
 
-template <bool FAST>
-__device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d) {
+// Constants of the 24-bit requantisation of one per-tensor dyadic pair (no bias): the accumulator is limited to
+// [lo, hi], the first values that give -127 / +127, after which (v b + 2^(c-1)) 2^(24-c) fits 32 bits with the int8
+// result in its top byte.  Valid for c <= 24, b < 2^(c-1) and bounds inside 24 bits (narrow_of() decides).
+struct Narrow { int32_t lo, hi, mb, ad; };
+
+// FAST: 0 general 64-bit requantisation, 1 pairs that fit 32 bits, 2 the 24-bit form above.
+template <int FAST>
+__device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d, Narrow n) {
+    if (FAST == 2) {
+        int32_t m;
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(v), "v"(n.lo), "v"(n.hi));
+        return (__mul24(m, n.mb) + n.ad) >> 24;
+    }
     return FAST ? clamp8(rnd_shift_fit32(v, d.b, d.c)) : requant64(v, d.b, d.c);
 }
 
@@ -45,13 +56,13 @@ __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d) {
 // exceeds 2^(k_out-1), so that IntDiv is one multiply-high by the pre-shifted reciprocal.
 // TFIX: 0, or the token count known at compile time (49, the 7 x 7 windows): every test of a key or query against T then
 // folds, and the fifteen absent keys of the last key tile cost nothing.
-template <int D, int NKT, bool TAPS, bool BIAS, bool MASK, bool FAST, int TFIX = 0>
+template <int D, int NKT, bool TAPS, bool BIAS, bool MASK, int FAST, int TFIX = 0>
 __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
                                                         const int8_t* __restrict__ mask, int n_mask,
                                                         const int32_t* __restrict__ tok_index, int n_win,
                                                         int8_t* __restrict__ o, int n_items, int split, int T_arg, int C, int H,
-                                                        Dyadic qk, ShiftParams sm, Dyadic pv,
+                                                        Dyadic qk, ShiftParams sm, Dyadic pv, Narrow nqk, Narrow npv,
                                                         int8_t* __restrict__ tap_s, int8_t* __restrict__ tap_p) {
     const int T = TFIX ? TFIX : T_arg;
     constexpr int KROW = D + 16;                  // K row pitch (bytes)
@@ -216,7 +227,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int key = 16 * t + 4 * lg + r;
-                        int32_t a = requant8<FAST>(sc[t][r], qk);
+                        int32_t a = requant8<FAST>(sc[t][r], qk, nqk);
                         if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
                         if (BIAS) a += (int32_t)(int8_t)(bw >> (8 * r));
                         if (MASK) { if ((mw >> (8 * r)) & 0xffu) a += mask_add; }
@@ -228,7 +239,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int key = 16 * t + 4 * lg + r;
-                        int32_t a = requant8<FAST>(sc[t][r], qk);
+                        int32_t a = requant8<FAST>(sc[t][r], qk, nqk);
                         if (key < T) {
                             if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
                             if (BIAS) { if (!MASK || brow) a += brow[key]; }
@@ -326,7 +337,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             for (int n = 0; n < ND; ++n) {
                 uint32_t w = 0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) w |= ((uint32_t)requant8<FAST>(oacc[n][r], pv) & 0xffu) << (8 * r);
+                for (int r = 0; r < 4; ++r) w |= ((uint32_t)requant8<FAST>(oacc[n][r], pv, npv) & 0xffu) << (8 * r);
                 ow[n] = w;
             }
             if (q < T) {
@@ -338,33 +349,42 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
     }
 }
 
+// The 24-bit constants of a pair, or false when the pair needs the wider forms.
+static bool narrow_of(Dyadic d, Narrow& n) {
+    if (d.c < 1 || d.c > 24 || d.b < 1 || d.b >= (1 << (d.c - 1))) return false;
+    const int64_t half = (int64_t)1 << (d.c - 1), two_c = (int64_t)1 << d.c;
+    const int64_t hi = (127 * two_c - half + d.b - 1) / d.b;             // first v with round(v b / 2^c) >= 127
+    const int64_t lo = -((127 * two_c - half + 1 + d.b - 1) / d.b);      // last v with round(v b / 2^c) <= -127
+    if (lo < -(1 << 23) || hi >= (1 << 23)) return false;
+    n.lo = (int32_t)lo; n.hi = (int32_t)hi; n.mb = d.b << (24 - d.c); n.ad = (int32_t)(half << (24 - d.c));
+    return true;
+}
+
 template <int D, int NKT>
 static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, int split, bool taps, bool bias, bool fast) {
     const int n_items = a.B * a.H;
-#define IVIT_ATT(TAPS_, BIAS_, MASK_, FAST_)                                                                       \
-    hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, MASK_, FAST_>), dim3(grid), dim3(ATT_THREADS), 0, s, a.qkv, \
-                       a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items, split, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores,    \
-                       a.tap_probs)
-    // the production paths are <no taps, fast>; everything else shares one fully general instantiation per bias / mask
-    // combination (a mask is always compiled with the bias code, which tests the bias pointer)
+    Narrow nqk{}, npv{};
+    const bool narrow = narrow_of(a.qk_rq, nqk) && narrow_of(a.pv_rq, npv);
+#define IVIT_ATT(TAPS_, BIAS_, MASK_, FAST_, TFIX_)                                                                         \
+    hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, MASK_, FAST_, TFIX_>), dim3(grid), dim3(ATT_THREADS), 0, s,     \
+                       a.qkv, a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items, split, a.T, a.C, a.H, a.qk_rq, \
+                       a.sm, a.pv_rq, nqk, npv, a.tap_scores, a.tap_probs)
+    // the production paths are <no taps, fast>, with the 24-bit requantisation when both pairs allow it; everything else
+    // shares one fully general instantiation per bias / mask combination (a mask is always compiled with the bias code,
+    // which tests the bias pointer)
     const bool masked = a.mask != nullptr;
-    if (D == 32 && NKT == 4 && a.T == 49 && !taps && fast && bias) {          // the windowed models' shape
-        if (masked)
-            hipLaunchKernelGGL((attention_kernel<D, NKT, false, true, true, true, (D == 32 && NKT == 4) ? 49 : 0>), dim3(grid),
-                               dim3(ATT_THREADS), 0, s, a.qkv, a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items,
-                               split, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs);
-        else
-            hipLaunchKernelGGL((attention_kernel<D, NKT, false, true, false, true, (D == 32 && NKT == 4) ? 49 : 0>), dim3(grid),
-                               dim3(ATT_THREADS), 0, s, a.qkv, a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items,
-                               split, a.T, a.C, a.H, a.qk_rq, a.sm, a.pv_rq, a.tap_scores, a.tap_probs);
+    constexpr int T49 = (D == 32 && NKT == 4) ? 49 : 0;                        // the windowed models' shape
+    if (T49 && a.T == 49 && !taps && fast && bias) {
+        if (masked) { if (narrow) IVIT_ATT(false, true, true, 2, T49); else IVIT_ATT(false, true, true, 1, T49); }
+        else { if (narrow) IVIT_ATT(false, true, false, 2, T49); else IVIT_ATT(false, true, false, 1, T49); }
     } else if (!taps && fast) {
-        if (masked) IVIT_ATT(false, true, true, true);
-        else if (bias) IVIT_ATT(false, true, false, true);
-        else IVIT_ATT(false, false, false, true);
+        if (masked) { if (narrow) IVIT_ATT(false, true, true, 2, 0); else IVIT_ATT(false, true, true, 1, 0); }
+        else if (bias) { if (narrow) IVIT_ATT(false, true, false, 2, 0); else IVIT_ATT(false, true, false, 1, 0); }
+        else { if (narrow) IVIT_ATT(false, false, false, 2, 0); else IVIT_ATT(false, false, false, 1, 0); }
     } else {
-        if (masked) IVIT_ATT(true, true, true, false);
-        else if (bias) IVIT_ATT(true, true, false, false);
-        else IVIT_ATT(true, false, false, false);
+        if (masked) IVIT_ATT(true, true, true, 0, 0);
+        else if (bias) IVIT_ATT(true, true, false, 0, 0);
+        else IVIT_ATT(true, false, false, 0, 0);
     }
 #undef IVIT_ATT
 }

@@ -298,14 +298,28 @@ def test_attention(ivit, name, B, over):
     assert_same(host(o2), o_ref, "attention out (no taps)")
 
 
-def test_attention_general_dyadic_pairs(ivit):
+@pytest.mark.parametrize("qk,pv", [
+    ((1200000007, 38), (40000, 15)),            # beyond 32 bits: the general 64-bit requantisation
+    ((4700011, 30), (9000001, 31)),             # c above 24: the 32-bit form
+    ((2 ** 14 - 1, 15), (20011, 22)),           # b just below 2^(c-1) / an ordinary pair: the 24-bit form
+    ((2 ** 14, 15), (20011, 22)),               # b = 2^(c-1): just outside the 24-bit form
+    ((3, 24), (24001, 21)),                     # bounds of the 24-bit form beyond 24 bits (tiny multiplier)
+    ((37, 10), (5, 4)),                         # small shifts
+])
+def test_attention_dyadic_pair_regimes(ivit, qk, pv):
     cfg = synth.CONFIGS["c0_tiny"]
     d = synth.dims_of(cfg, 2)
-    qkv = synth.make_rows(3, 2 * cfg["T"], 3 * cfg["C"], "normal", 32.0)
-    qk, pv, sm = (1200000007, 38), (40000, 15), synth.shift_params(12)
+    qkv = synth.make_rows(3, 2 * cfg["T"], 3 * cfg["C"], "normal", 50.0)
+    qkv[:4] = 127; qkv[4:8] = -127              # saturating dot products on both sides
+    sm = synth.shift_params(12)
+    want, _, pr_ref = orc.attention(qkv, d, qk, sm, pv, want_taps=True)
     o = empty((2 * cfg["T"], cfg["C"]))
     ivit.ivit_attention(dev(qkv), o, d, qk, sm, pv)
-    assert_same(host(o), orc.attention(qkv, d, qk, sm, pv), "attention general pairs")
+    assert_same(host(o), want, "attention, pair regime")
+    pr = empty(pr_ref.shape)
+    ivit.ivit_attention(dev(qkv), o, d, qk, sm, pv, tap_probs=pr)
+    assert_same(host(pr), pr_ref, "attention probabilities, pair regime")
+    assert_same(host(o), want, "attention with taps, pair regime")
 
 
 # ------------------------------------------------------------------ encoder block with every intermediate tensor
