@@ -41,7 +41,7 @@ __device__ __forceinline__ int vt_pos(int k) {
 // result in its top byte.  Valid for c <= 24, b < 2^(c-1) and bounds inside 24 bits (narrow_of() decides).
 struct Narrow { int32_t lo, hi, mb, ad; };
 
-// FAST: 0 general 64-bit requantisation, 1 pairs that fit 32 bits, 2 the 24-bit form above.
+// FAST: 0 general 64-bit requantisation, 1 pairs that fit 32 bits, 2 the 24-bit form above (and the 24-bit IntDiv).
 template <int FAST>
 __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d, Narrow n) {
     if (FAST == 2) {
@@ -298,7 +298,16 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
             for (int t = 0; t < NKC * 4; ++t) pk[t] = 0u;
 #pragma unroll
-            for (int t = 0; t < NKT; ++t)
+            for (int t = 0; t < NKT; ++t) {
+                if (FAST == 2 && !TAPS) {
+                    // M - (k_out - 1) = 24 here: inv < 2^24 and the ShiftExp values are below 2^16, so inv * e (at most
+                    // 2^31) is one 24-bit multiply and the quotient is its top byte
+                    uint32_t pr[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) pr[r] = __umul24(inv, (uint32_t)sc[t][r]);
+                    pk[t] = __builtin_amdgcn_perm(pr[1], pr[0], 0x0c0c0703u) | __builtin_amdgcn_perm(pr[3], pr[2], 0x07030c0cu);
+                    continue;
+                }
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     if (TAPS) {
@@ -313,6 +322,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                         pk[t] |= p << (8 * r);
                     }
                 }
+            }
             if (!TAPS) {
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) pk[t] -= (pk[t] >> (sm.k_out - 1)) & 0x01010101u;   // bytewise min(p, 2^(k_out-1) - 1)
@@ -364,7 +374,8 @@ template <int D, int NKT>
 static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, int split, bool taps, bool bias, bool fast) {
     const int n_items = a.B * a.H;
     Narrow nqk{}, npv{};
-    const bool narrow = narrow_of(a.qk_rq, nqk) && narrow_of(a.pv_rq, npv);
+    // the 24-bit forms: both requantisations, and IntDiv with its quotient in the top byte of a 24-bit product
+    const bool narrow = narrow_of(a.qk_rq, nqk) && narrow_of(a.pv_rq, npv) && a.sm.m_bits - (a.sm.k_out - 1) == 24;
 #define IVIT_ATT(TAPS_, BIAS_, MASK_, FAST_, TFIX_)                                                                         \
     hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, MASK_, FAST_, TFIX_>), dim3(grid), dim3(ATT_THREADS), 0, s,     \
                        a.qkv, a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items, split, a.T, a.C, a.H, a.qk_rq, \
