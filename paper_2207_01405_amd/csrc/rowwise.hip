@@ -289,7 +289,7 @@ __device__ __forceinline__ uint32_t group_allreduce(uint32_t v, OP op) {
 
 // DUP: the number of leading bytes of a row's last lane that belong to its neighbour, 16 ceil(cols / 16) - cols,
 // when it is one of the instantiated values (0; 11 for 197 columns; 15 for 49 and 65), else -1 = taken at run time.
-template <int LPR, int UNR, bool FAST, int DUP>
+template <int LPR, int UNR, int FAST, int DUP>
 __global__ __launch_bounds__(256) void shiftmax_vec_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y,
                                                            int64_t rows, int cols, int ld, ShiftParams p) {
     __shared__ uint16_t lut[256];                    // ShiftExp(-delta), delta = max - value in [0, 255]
@@ -344,11 +344,20 @@ __global__ __launch_bounds__(256) void shiftmax_vec_kernel(const int8_t* __restr
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
                 uint32_t w = 0;
+                if (FAST == 2) {
+                    // M - (k_out - 1) = 24: inv < 2^24, e < 2^16 and inv e <= 2^31, so the quotient is the top byte of one
+                    // 24-bit multiply
+                    uint32_t pr[4];
 #pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const uint32_t ek = e[4 * d + b];
-                    const uint32_t q = FAST ? __umulhi(invs, ek) : (inv * ek) >> sh;
-                    w |= q << (8 * b);                                   // q <= 2^(k_out-1) fits a byte
+                    for (int b = 0; b < 4; ++b) pr[b] = __umul24(inv, e[4 * d + b]);
+                    w = __builtin_amdgcn_perm(pr[1], pr[0], 0x0c0c0703u) | __builtin_amdgcn_perm(pr[3], pr[2], 0x07030c0cu);
+                } else {
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const uint32_t ek = e[4 * d + b];
+                        const uint32_t q = FAST ? __umulhi(invs, ek) : (inv * ek) >> sh;
+                        w |= q << (8 * b);                               // q <= 2^(k_out-1) fits a byte
+                    }
                 }
                 out[d] = w - ((w >> (p.k_out - 1)) & 0x01010101u);       // bytewise min(q, 2^(k_out-1) - 1)
             }
@@ -371,10 +380,12 @@ static void launch_shiftmax_vec(hipStream_t s, const int8_t* x, int8_t* y, int64
     const int dup = 16 * ((cols + 15) / 16) - cols;
     const dim3 g(grid), b(256);
 #define IVIT_SM(FAST_, DUP_) hipLaunchKernelGGL((shiftmax_vec_kernel<LPR, UNR, FAST_, DUP_>), g, b, 0, s, x, y, rows, cols, ld, p)
-    if (fast) {
-        if (dup == 0) IVIT_SM(true, 0); else if (dup == 11) IVIT_SM(true, 11); else if (dup == 15) IVIT_SM(true, 15); else IVIT_SM(true, -1);
+    if (fast && sh == 24) {
+        if (dup == 0) IVIT_SM(2, 0); else if (dup == 11) IVIT_SM(2, 11); else if (dup == 15) IVIT_SM(2, 15); else IVIT_SM(2, -1);
+    } else if (fast) {
+        IVIT_SM(1, -1);
     } else {
-        IVIT_SM(false, -1);
+        IVIT_SM(0, -1);
     }
 #undef IVIT_SM
 }
