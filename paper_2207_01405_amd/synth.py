@@ -202,6 +202,8 @@ SWIN = {
                            B=2, seed=11),
     "swin_t": dict(grid=56, window=7, C=96, heads=(3, 6, 12, 24), depths=(2, 2, 6, 2), patch_dim=48, n_classes=1000,
                    B=128, seed=12),
+    "swin_s": dict(grid=56, window=7, C=96, heads=(3, 6, 12, 24), depths=(2, 2, 18, 2), patch_dim=48, n_classes=1000,
+                   B=128, seed=13),
 }
 
 for _name, _cfg in SWIN.items():

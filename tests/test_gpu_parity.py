@@ -669,7 +669,7 @@ def _gpu_swin(ivit, cfg, model, patches, B):
     return host(logits)
 
 
-@pytest.mark.parametrize("name,B", [("swin_tiny_test", 2), ("swin_tiny_test", 7), ("swin_t", 2)])
+@pytest.mark.parametrize("name,B", [("swin_tiny_test", 2), ("swin_tiny_test", 7), ("swin_t", 2), ("swin_s", 1)])
 def test_forward_swin_patches_to_logits(ivit, name, B):
     cfg = synth.SWIN[name]
     model = synth.make_swin_model(cfg)
