@@ -3,7 +3,7 @@
 // add of Eq. 1-2 or with ShiftGELU (Sec. 3.4, Algorithm 2) and its rescale.
 //
 // One workgroup (256 threads = 4 wavefronts as 2 x 2) computes a 128-token x 128-channel output tile.  K is
-// consumed in 64-byte steps through two LDS buffers; the global loads of the next TWO steps are in flight
+// consumed in 128-byte steps through two LDS buffers; the global loads of the next TWO steps are in flight
 // (in two register sets) while the current step is multiplied, because with K of a few hundred bytes the
 // kernel is bound by load latency, not by the matrix cores.  Each wavefront owns 64 tokens x 64 channels =
 // 2 x 2 tiles of v_mfma_i32_32x32x32_i8 (the int8 instruction that reaches the matrix-core peak on gfx950).
@@ -22,7 +22,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 #ifndef IVIT_GEMM_BK
-#define IVIT_GEMM_BK 64
+#define IVIT_GEMM_BK 128
 #endif
 #ifndef IVIT_GEMM_WGS_PER_CU
 #define IVIT_GEMM_WGS_PER_CU 2
