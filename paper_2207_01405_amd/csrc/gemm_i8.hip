@@ -14,6 +14,7 @@
 // Workgroup ids are remapped so that each XCD (own L2) works on a contiguous range of tiles.
 #include "ivit_kernels.hpp"
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 namespace ivit {
@@ -585,6 +586,87 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Kernel for few rows (small batches, the classifier head): latency, not throughput, is what counts there.  One
+// workgroup of four wavefronts computes one 32-token x 32-channel tile; the wavefronts split K between them (k-steps
+// w, w + 4, ...), read both operands straight from memory in MFMA layout (16 bytes per lane and k-step; nothing is
+// staged or reused, the whole problem is a few hundred tiles), add their partial tiles through LDS, and the first
+// wavefront requantises with the general 64-bit formulas and writes the 32 x 32 outputs.
+constexpr int SM_WAVES = 4, SM_MAXSTEPS = 8;            // k-steps whose loads are in flight together per wavefront
+
+template <int EPI>
+__global__ __launch_bounds__(64 * SM_WAVES) void gemm_small_kernel(GemmParams P) {
+    __shared__ int32_t part[SM_WAVES - 1][16][64];      // partial tiles of wavefronts 1..3, [register][lane]
+    __shared__ int8_t gelu_lut[256];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    const int K = P.K, N = P.N;
+    const int64_t M = P.M;
+    const int tiles_n = (N + 31) / 32;
+    const int64_t tile = blockIdx.x;
+    const int64_t m0 = (tile / tiles_n) * 32;
+    const int n0 = (int)(tile % tiles_n) * 32;
+    if (EPI == EPI_GELU) {
+        const int32_t I = (int32_t)(int8_t)tid;
+        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
+    }
+    // rows past the end repeat the last one (their results are not stored); K % 32 == 16: the upper half of the last step is zero
+    const int8_t* xr = P.x + min<int64_t>(m0 + li, M - 1) * P.ldx + 16 * lg;
+    const int8_t* wr = P.w + (int64_t)min(n0 + li, N - 1) * K + 16 * lg;
+    const int nsteps = (K + 31) / 32;
+    // the first wavefront's requantisation constants are requested before the operands, not after the multiply
+    int32_t qb[16], qc[16], qbias[16];
+    if (wv == 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int n = min(n0 + 8 * (i >> 2) + 4 * lg + (i & 3), N - 1);
+            qb[i] = P.rq_b[n]; qc[i] = P.rq_c[n]; qbias[i] = P.bias ? P.bias[n] : 0;
+        }
+    }
+    v16i acc = {};
+    for (int s0 = wv; s0 < nsteps; s0 += SM_WAVES * SM_MAXSTEPS) {
+        v4i xf[SM_MAXSTEPS], wf[SM_MAXSTEPS];
+#pragma unroll
+        for (int u = 0; u < SM_MAXSTEPS; ++u) {
+            const int ks = s0 + u * SM_WAVES;
+            const bool in = ks < nsteps && 32 * ks + 16 * lg < K;
+            const int off = in ? 32 * ks : 0;
+            const v4i xv = *reinterpret_cast<const v4i*>(xr + off - (in ? 0 : 16 * lg));
+            const v4i wv4 = *reinterpret_cast<const v4i*>(wr + off - (in ? 0 : 16 * lg));
+            xf[u] = in ? xv : v4i{0, 0, 0, 0};
+            wf[u] = in ? wv4 : v4i{0, 0, 0, 0};
+        }
+#pragma unroll
+        for (int u = 0; u < SM_MAXSTEPS; ++u) acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf[u], xf[u], acc, 0, 0, 0);
+    }
+    if (wv > 0) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) part[wv - 1][i][lane] = acc[i];
+    }
+    __syncthreads();
+    if (wv > 0) return;
+    // lane (li, lg): token m0 + li; register i = 4 q + r is channel n0 + 8 q + 4 lg + r
+    const int64_t tok = m0 + li;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = 4 * q + r;
+            const int n = n0 + 8 * q + 4 * lg + r;
+            int32_t a = acc[i] + part[0][i][lane] + part[1][i][lane] + part[2][i][lane];
+            if (tok < M && n < N) {
+                a += qbias[i];
+                const int64_t r64 = rnd_shift64(a, qb[i], qc[i]);
+                int32_t v;
+                if (EPI == EPI_RESIDUAL) v = clamp8_64(r64 + rnd_shift64(P.residual[tok * N + n], P.res_rq.b, P.res_rq.c));
+                else v = clamp8_64(r64);
+                if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
+                P.y[tok * N + n] = (int8_t)v;
+            }
+        }
+    }
+}
+
 static bool ws_plan(const LinearArgs& a, int& ncb, int& unit, int& nunits, int& pitch, size_t& lds_bytes) {
     if ((a.N & 15) != 0 || (a.K & 15) != 0) return false;
     unit = a.K % (3 * WS_CHUNK) == 0 ? 3 : 1;
@@ -643,6 +725,21 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int64_t bytes = a.M * a.K + (int64_t)a.N * a.K + a.M * a.N * (a.residual ? 2 : 1) + 8LL * a.N + (a.bias ? 4LL * a.N : 0);
     TraceScope trace(s, a.residual ? KIND_GEMM_RESIDUAL : (a.gelu ? KIND_GEMM_GELU : KIND_GEMM), 2 * a.M * a.N * a.K, bytes);
+    // few rows: one workgroup per 32 x 32 tile
+    // (IVIT_DENSE_PATH=large in the environment keeps such shapes on the kernels for many rows: a switch for tests)
+    const int64_t small_tiles = ((a.M + 31) / 32) * ((a.N + 31) / 32);
+    const char* path = getenv("IVIT_DENSE_PATH");
+    // measured on patches-to-logits forwards at batch 1 and 8: up to one tile per CU it always wins (batch 1: DeiT-S 0.77 ->
+    // 0.66 ms, ViT-B 1.11 -> 0.74 ms), beyond that only when K is long enough for the split over the four wavefronts to pay
+    // (a single image of a wide model: at most 256 rows)
+    const int64_t small_limit = (int64_t)num_cus() * (a.K >= 768 && a.M <= 256 ? 3 : 1);
+    if (small_tiles <= small_limit && !(path && path[0] == 'l')) {
+        const dim3 g((unsigned)small_tiles), b(64 * SM_WAVES);
+        if (a.residual) hipLaunchKernelGGL(gemm_small_kernel<EPI_RESIDUAL>, g, b, 0, s, P);
+        else if (a.gelu) hipLaunchKernelGGL(gemm_small_kernel<EPI_GELU>, g, b, 0, s, P);
+        else hipLaunchKernelGGL(gemm_small_kernel<EPI_PLAIN>, g, b, 0, s, P);
+        return hipGetLastError();
+    }
     int ncb, unit, nunits, pitch; size_t lds_bytes;
     if (ws_plan(a, ncb, unit, nunits, pitch, lds_bytes)) {
         WsParams W;

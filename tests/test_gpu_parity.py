@@ -172,9 +172,20 @@ LIN_SHAPES = [(0, 64, 64), (1, 1, 16), (5, 7, 80), (65, 192, 64), (130, 40, 256)
               (3, 16, 65536), (70001, 16, 16)]
 
 
+@pytest.fixture(params=["auto", "large"])
+def dense_path(request, monkeypatch):
+    """Shapes with few rows take a kernel of their own; "large" keeps them on the kernels for many rows (an environment
+    switch the library reads at every call), so that the small test shapes exercise both."""
+    if request.param == "large":
+        monkeypatch.setenv("IVIT_DENSE_PATH", "large")
+    else:
+        monkeypatch.delenv("IVIT_DENSE_PATH", raising=False)
+    return request.param
+
+
 @pytest.mark.parametrize("M,N,K", LIN_SHAPES)
 @pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
-def test_linear_requant(ivit, M, N, K, epi):
+def test_linear_requant(ivit, dense_path, M, N, K, epi):
     x = synth.make_rows(M + N + K, M, K, "normal", 32.0)
     w, bias, rq_b, rq_c = synth.make_linear(M * 7 + N, N, K)
     kw_o, kw_g = {}, {}
@@ -188,7 +199,7 @@ def test_linear_requant(ivit, M, N, K, epi):
     assert_same(host(y), orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o), "linear %s" % epi)
 
 
-def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit):
+def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit, dense_path):
     """Multipliers and shifts outside the 15-bit fast range take the 64-bit path, channel by channel."""
     rng = np.random.default_rng(42)
     M, N, K = 200, 96, 128
@@ -210,7 +221,7 @@ def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit):
         assert np.abs(want.astype(np.int32)).mean() > 2
 
 
-def test_linear_requant_largest_accumulators(ivit):
+def test_linear_requant_largest_accumulators(ivit, dense_path):
     """K = 65536 with every operand at +-127: the dot products reach +-65536 * 127^2 = +-1.057e9, the largest an int32
     accumulator of this entry point ever holds; shifts chosen so that results spread over the int8 range."""
     M, N, K = 8, 32, 65536
@@ -229,7 +240,7 @@ def test_linear_requant_largest_accumulators(ivit):
 
 
 @pytest.mark.parametrize("K", [128, 1536])
-def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, K):
+def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K):
     """Per-channel parameters at and around the limits of the 24-bit requantisation (shift 1..24, multiplier just
     below and at 2^(c-1), biases that push the clamp bounds to and past 24 bits), on operands that drive the
     accumulators to both saturated ends (K * 127^2 exceeds 2^23 for the larger K) and through the whole range.

@@ -55,8 +55,19 @@ def _dense_params(rng, N, K, regime):
     return b.astype(np.int32), c.astype(np.int32), bias.astype(np.int32)
 
 
+@pytest.fixture(params=["auto", "large"])
+def dense_path(request, monkeypatch):
+    """Few-row shapes have a kernel of their own; "large" (an environment switch read at every call) keeps them on the
+    kernels for many rows, so both see the random shapes."""
+    if request.param == "large":
+        monkeypatch.setenv("IVIT_DENSE_PATH", "large")
+    else:
+        monkeypatch.delenv("IVIT_DENSE_PATH", raising=False)
+    return request.param
+
+
 @pytest.mark.parametrize("seed", range(36))
-def test_linear_random(ivit, seed):
+def test_linear_random(ivit, dense_path, seed):
     rng = np.random.default_rng(1000 + seed)
     K = 16 * int(rng.choice([1, 2, 3, 5, 6, 8, 12, 16, 24, 25, 48, 96, 100, 192]))
     N = int(rng.choice([16, 48, 64, 80, 128, 144, 256, 400, 1000, 7, 33])) if seed % 3 else 16 * int(rng.integers(1, 60))
@@ -154,7 +165,7 @@ def test_rowwise_random(ivit, seed):
 
 
 @pytest.mark.parametrize("seed", range(8))
-def test_block_random(ivit, seed):
+def test_block_random(ivit, dense_path, seed):
     """Whole blocks on random widths, with every intermediate tensor."""
     import torch
     rng = np.random.default_rng(4000 + seed)
