@@ -26,6 +26,9 @@
  *  - Integer semantics: ">>" is an arithmetic shift (floor); round(v, c) =
  *    (v + 2^(c-1)) >> c; clamp8(v) = min(max(v, -127), 127);
  *    requant(v; b, c) = clamp8(round(b * v, c)) with the product in 64 bits.
+ *  - Environment: IVIT_LOG (any value) prints the HIP error text behind an IVIT_ERR_HIP to stderr;
+ *    IVIT_DENSE_PATH=large keeps Dense layers with few rows off the kernel written for them (a switch for tests:
+ *    results are identical either way).
  *  - Values in device parameter arrays cannot be checked on the host: rq_b must
  *    hold 1 <= b < 2^31 and rq_c must hold 1 <= c <= 46; other values give
  *    unspecified results (never a fault).
