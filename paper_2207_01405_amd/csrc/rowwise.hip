@@ -87,13 +87,13 @@ __global__ __launch_bounds__(256) void ilayernorm_kernel(const int8_t* __restric
     }
 }
 
-// I-LayerNorm, tiled form for C a multiple of 16 with 64 <= C <= 1024.  A workgroup takes R = RP * J
+// I-LayerNorm, tiled form for C a multiple of 16 with 64 <= C <= GBN (1024, or 2048 for the few wide rows of patch merging).  A workgroup takes R = RP * J
 // consecutive rows, where CPR = C / 16 threads cover one row with 16 bytes each and RP = 256 / CPR rows are
 // covered per pass.  Thread (rgrp, cc) keeps chunk cc of rows rgrp, rgrp + RP, ... in registers, so gamma / beta
 // of its 16 channels are loaded once.  The per-row scalar work (integer mean, variance, ten-step square
 // root, reciprocal) would idle 63 of 64 lanes if done per wavefront, so the 4-way dot-product partial sums
 // go through LDS and every thread then does the scalar work of a DIFFERENT row.
-template <int J>
+template <int J, int GBN = 1024>
 __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __restrict__ x,
                                                                const int32_t* __restrict__ gamma_q,
                                                                const int32_t* __restrict__ beta_q,
@@ -118,10 +118,10 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
     }
     // gamma and beta + 2^(c-1) go through LDS: read once per workgroup with coalesced loads instead of 128 bytes per
     // thread; each thread picks up its 16 channels after the first barrier
-    __shared__ __align__(16) int32_t gb[2 * 1024];
+    __shared__ __align__(16) int32_t gb[2 * GBN];
     for (int i = tid; i < C; i += 256) {
         gb[i] = gamma_q[i];
-        gb[1024 + i] = (int32_t)((uint32_t)beta_q[i] + (uint32_t)half);
+        gb[GBN + i] = (int32_t)((uint32_t)beta_q[i] + (uint32_t)half);
     }
 #pragma unroll
     for (int j = 0; j < J; ++j) {
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         const v4i gv = *reinterpret_cast<const v4i*>(&gb[(active ? 16 * cc : 0) + 4 * q]);
-        const v4i bv = *reinterpret_cast<const v4i*>(&gb[1024 + (active ? 16 * cc : 0) + 4 * q]);
+        const v4i bv = *reinterpret_cast<const v4i*>(&gb[GBN + (active ? 16 * cc : 0) + 4 * q]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) { g[4 * q + e] = gv[e]; bt[4 * q + e] = bv[e]; }
     }
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
 hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
                              int8_t* y, int64_t rows, int C, int f_bits, int c_shift) {
     if (rows == 0) return hipSuccess;
-    if ((C & 15) == 0 && C >= 64 && C <= 1024 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma_q | (uintptr_t)beta_q) & 15) == 0) {
+    if ((C & 15) == 0 && C >= 64 && C <= 2048 && (((uintptr_t)x | (uintptr_t)y | (uintptr_t)gamma_q | (uintptr_t)beta_q) & 15) == 0) {
         // rows per workgroup = (256 / (C / 16)) * J
         const int rp = 256 / (C >> 4);
         // the smallest J whose workgroups are all resident at once (8 per CU): one round of the three dependent phases
@@ -190,6 +190,15 @@ hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamm
         if (grid <= 0x7fffffffLL) {
             TraceScope trace(s, KIND_ILAYERNORM, 0, 2 * rows * C + 8LL * C);
             const dim3 g((unsigned)grid), b(256);
+            if (C > 1024) {
+                switch (J) {
+                    case 8: hipLaunchKernelGGL((ilayernorm_tiled_kernel<8, 2048>), g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+                    case 4: hipLaunchKernelGGL((ilayernorm_tiled_kernel<4, 2048>), g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+                    case 2: hipLaunchKernelGGL((ilayernorm_tiled_kernel<2, 2048>), g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+                    default: hipLaunchKernelGGL((ilayernorm_tiled_kernel<1, 2048>), g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
+                }
+                return hipGetLastError();
+            }
             switch (J) {
                 case 8: hipLaunchKernelGGL(ilayernorm_tiled_kernel<8>, g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
                 case 4: hipLaunchKernelGGL(ilayernorm_tiled_kernel<4>, g, b, 0, s, x, gamma_q, beta_q, y, rows, C, f_bits, c_shift); break;
