@@ -416,9 +416,9 @@ hipError_t launch_attention(hipStream_t s, const AttentionArgs& a) {
     if (n_items == 0) return hipSuccess;
     const int nkt = (a.T + 15) / 16;
     // With fewer (window, head) pairs than compute units, several workgroups share a pair (each takes every split-th
-    // query tile) so that the device is filled: about two workgroups per CU, at least one tile per wavefront.  With
+    // query tile) so that the device is filled: about two workgroups per CU, down to one tile per wavefront.  With
     // more pairs than that sharing only adds staging work (measured: 768 pairs, 30 us unshared, 33 us shared by two).
-    const int split = (int)std::max<int64_t>(1, std::min<int64_t>(2 * (int64_t)num_cus() / n_items, nkt / ATT_WAVES));
+    const int split = (int)std::max<int64_t>(1, std::min<int64_t>(2 * (int64_t)num_cus() / n_items, (nkt + ATT_WAVES - 1) / ATT_WAVES));
     // workgroups per CU: windows of at most 64 tokens need little LDS and few registers, and their short items are
     // bound by latency, so many more workgroups are kept in flight (8192 windows x 3 heads: 86 us with 4, 72 us with 16)
     // (up to 16 per CU, as long as each still loops over about four items, which keeps the rounds even)
