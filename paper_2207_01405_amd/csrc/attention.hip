@@ -304,7 +304,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                     // 2^31) is one 24-bit multiply and the quotient is its top byte
                     uint32_t pr[4];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) pr[r] = __umul24(inv, (uint32_t)sc[t][r]);
+                    for (int r = 0; r < 4; ++r) pr[r] = mul_u24(inv, (uint32_t)sc[t][r]);
                     pk[t] = __builtin_amdgcn_perm(pr[1], pr[0], 0x0c0c0703u) | __builtin_amdgcn_perm(pr[3], pr[2], 0x07030c0cu);
                     continue;
                 }

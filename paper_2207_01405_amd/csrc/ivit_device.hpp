@@ -113,6 +113,14 @@ __device__ __forceinline__ uint32_t shiftexp_small(int32_t I, int32_t i0, int32_
     return q > 31 ? 0u : (((uint32_t)Ib << n_shift) >> q);
 }
 
+// Low 32 bits of the product of the low 24 bits of a and b, as the one full-rate instruction.  Written out because the
+// compiler falls back to the quarter-rate 32-bit multiply when an operand's range was established in another block.
+__device__ __forceinline__ uint32_t mul_u24(uint32_t a, uint32_t b) {
+    uint32_t r;
+    asm("v_mul_u32_u24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // Tenth iterate of I <- (I + floor(v / I)) >> 1 from I = 2^floor(bitlen(v) / 2) (Eq. 20); 0 for v = 0.
 __device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
     if (v == 0) return 0;

@@ -358,7 +358,7 @@ __global__ __launch_bounds__(256) void shiftmax_vec_kernel(const int8_t* __restr
                     // 24-bit multiply
                     uint32_t pr[4];
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) pr[b] = __umul24(inv, e[4 * d + b]);
+                    for (int b = 0; b < 4; ++b) pr[b] = mul_u24(inv, e[4 * d + b]);
                     w = __builtin_amdgcn_perm(pr[1], pr[0], 0x0c0c0703u) | __builtin_amdgcn_perm(pr[3], pr[2], 0x07030c0cu);
                 } else {
 #pragma unroll
