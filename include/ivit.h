@@ -160,7 +160,8 @@ int ivit_shiftgelu_rowmax(void* stream, const int8_t* x, int8_t* y, int64_t rows
  * gamma_q, beta_q [C] int32 carry the output scale (folded by the host).
  * Requirements: rows >= 0, 4 <= C <= 2048, C % 4 == 0, 1 <= f_bits <= 20, 1 <= c_shift <= 31,
  * x and y 4-byte aligned; |gamma_q| < 2^15 and |(x - mean) * f * gamma_q + beta_q| < 2^31 - 2^(c_shift-1)
- * (a precondition on device data; otherwise the result wraps modulo 2^32).
+ * (a precondition on device data: the two products are taken with 24-bit factors; outside it the values are
+ * unspecified, nothing faults).
  * Errors: NULL, SHAPE, PARAM, ALIGN, HIP. */
 int ivit_ilayernorm(void* stream, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
                     int8_t* y, int64_t rows, int32_t C, int32_t f_bits, int32_t c_shift);

@@ -121,6 +121,13 @@ __device__ __forceinline__ uint32_t mul_u24(uint32_t a, uint32_t b) {
     return r;
 }
 
+// The same for signed factors: low 32 bits of the product of the sign-extended low 24 bits of a and b.
+__device__ __forceinline__ int32_t mul_i24(int32_t a, int32_t b) {
+    int32_t r;
+    asm("v_mul_i32_i24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
 // Tenth iterate of I <- (I + floor(v / I)) >> 1 from I = 2^floor(bitlen(v) / 2) (Eq. 20); 0 for v = 0.
 __device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
     if (v == 0) return 0;

@@ -78,8 +78,8 @@ __global__ __launch_bounds__(256) void ilayernorm_kernel(const int8_t* __restric
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int32_t xe = (int32_t)(int8_t)(xv[t] >> (8 * e));
-                const int32_t dg = (xe - mean) * g[t][e];                         // |.| < 2^23
-                const int32_t v = (int32_t)((uint32_t)dg * (uint32_t)f + (uint32_t)bt[t][e]);
+                const int32_t dg = mul_i24(xe - mean, g[t][e]);                   // |.| < 2^23: 24-bit factors, see below
+                const int32_t v = __mul24(dg, f) + bt[t][e];
                 out |= ((uint32_t)clamp8(v >> c_shift) & 0xffu) << (8 * e);
             }
             if (idx < ndw) yr[idx] = out;
@@ -165,8 +165,10 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int32_t xe = (int32_t)(int8_t)((uint32_t)xv[j][d] >> (8 * e));
-                const int32_t dg = (xe - mf.x) * g[4 * d + e];                       // |.| < 2^23
-                const int32_t v = (int32_t)((uint32_t)dg * (uint32_t)mf.y + (uint32_t)bt[4 * d + e]);
+                // |x - mean| <= 255, |gamma_q| < 2^15 and f <= 2^20: both products have 24-bit factors, so the
+                // full-rate 24-bit multiply (low 32 bits of the product) gives what the 32-bit one would
+                const int32_t dg = mul_i24(xe - mf.x, g[4 * d + e]);                 // |.| < 2^23
+                const int32_t v = __mul24(dg, mf.y) + bt[4 * d + e];
                 o |= ((uint32_t)clamp8(v >> c_shift) & 0xffu) << (8 * e);
             }
             outw[d] = o;
