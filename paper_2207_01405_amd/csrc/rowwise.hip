@@ -491,6 +491,7 @@ hipError_t launch_shiftgelu(hipStream_t s, const int8_t* x, int8_t* y8, int16_t*
 // finds m with one pass over its registers, tabulates the 256 results for this m in LDS (four entries per lane:
 // ShiftExp of I_p - m, IntDiv with a 64-bit reciprocal since this form needs M above 31, requantisation) and
 // looks every element up.  Entries for inputs above the maximum cannot occur and are skipped.
+constexpr int RM_ROWS = 8;                                   // consecutive rows per wavefront
 template <int NT>
 __global__ __launch_bounds__(256) void shiftgelu_rowmax_kernel(const int8_t* __restrict__ x, int8_t* __restrict__ y,
                                                                int64_t rows, int cols, ShiftParams p, Dyadic rq) {
@@ -503,22 +504,34 @@ __global__ __launch_bounds__(256) void shiftgelu_rowmax_kernel(const int8_t* __r
     const int sh = p.m_bits - (p.k_out - 1);
     auto ip_of = [](int32_t I) { return I + (I >> 1) + (I >> 3) + (I >> 4); };
     const double two_m = (double)((uint64_t)1 << p.m_bits);
-    for (int64_t row = wave; row < rows; row += nwaves) {
+    int32_t table_mx = INT32_MIN;                                // row maximum the wavefront's table was built for (none yet)
+    // a wavefront takes RM_ROWS consecutive rows at a time: step `it` is row it % RM_ROWS of its (it / RM_ROWS)-th group
+    for (int64_t it = 0;; ++it) {
+        const int64_t row = (wave + (it / RM_ROWS) * nwaves) * RM_ROWS + it % RM_ROWS;
+        if (row >= rows) break;                                  // rows only grow with `it`
         const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + row * cols);
         uint32_t xv[NT];
-        int32_t mx = -128;
+        // the maximum is taken on sign-flipped bytes, two at a time as packed 16-bit lanes (even and odd bytes)
+        u16x2 m2 = {0, 0};
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const int idx = lane + 64 * t;
             xv[t] = idx < ndw ? xr[idx] : 0x80808080u;           // padding: -128, never the maximum of a real row
-#pragma unroll
-            for (int e = 0; e < 4; ++e) mx = max(mx, (int32_t)(int8_t)(xv[t] >> (8 * e)));
+            const uint32_t xf = xv[t] ^ 0x80808080u;
+            m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(u16x2, xf & 0x00ff00ffu));
+            m2 = __builtin_elementwise_max(m2, __builtin_bit_cast(u16x2, (xf >> 8) & 0x00ff00ffu));
         }
-        mx = wave_max(mx);                                       // I_p is increasing in I: the row maximum of I_p is I_p(max I)
+        // I_p is increasing in I: the row maximum of I_p is I_p(max I)
+        const int32_t mx = wave_max((int32_t)max((uint32_t)m2[0], (uint32_t)m2[1])) - 128;
+        // the table depends on the row only through its maximum: a row with the maximum of the wavefront's previous row
+        // (saturated activations: often 127) reuses that row's table
+        const bool rebuild = mx != table_mx;
+        table_mx = mx;
         const int32_t m = max(ip_of(mx), 0);
         const uint32_t e2 = shiftexp_small(-m, p.i0, p.n_shift);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
+            if (!rebuild) break;
             const int32_t I = (int32_t)(int8_t)(lane + 64 * k);  // the value whose low byte is the table index
             int32_t out = 0;
             if (I <= mx) {
@@ -550,7 +563,8 @@ __global__ __launch_bounds__(256) void shiftgelu_rowmax_kernel(const int8_t* __r
 hipError_t launch_shiftgelu_rowmax(hipStream_t s, const int8_t* x, int8_t* y, int64_t rows, int cols, ShiftParams p,
                                    Dyadic rq) {
     if (rows == 0) return hipSuccess;
-    const int grid = (int)std::min<int64_t>((rows + 3) / 4, (int64_t)num_cus() * 16);
+    // one workgroup per 4 RM_ROWS consecutive rows: the workgroups in flight cover a compact window of memory
+    const int grid = (int)std::min<int64_t>((rows + 4 * RM_ROWS - 1) / (4 * RM_ROWS), 0x7fffffffLL);
     const int nt = (cols / 4 + 63) / 64;
     TraceScope trace(s, KIND_SHIFTGELU, 0, 2 * rows * cols);
 #define IVIT_RM(NT_) hipLaunchKernelGGL(shiftgelu_rowmax_kernel<NT_>, dim3(grid), dim3(256), 0, s, x, y, rows, cols, p, rq)
