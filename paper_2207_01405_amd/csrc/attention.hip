@@ -251,8 +251,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 }
                 __builtin_amdgcn_sched_barrier(0);     // keep the 64-bit temporaries of one tile at a time
             }
-            mx = max(mx, __shfl_xor(mx, 16, kWave));
-            mx = max(mx, __shfl_xor(mx, 32, kWave));
+            mx = rows_allreduce(mx, [](int32_t a, int32_t b) { return max(a, b); });
             // ---- ShiftExp by table, row sum.  The byte offset 2 (max - a) of the table entry is one 24-bit multiply-add.
             int32_t sum = 0;
             const int32_t mx2 = 2 * mx;
@@ -289,8 +288,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 }
                 if (t & 1) __builtin_amdgcn_sched_barrier(0);
             }
-            sum += __shfl_xor(sum, 16, kWave);
-            sum += __shfl_xor(sum, 32, kWave);
+            sum = rows_allreduce(sum, [](int32_t a, int32_t b) { return a + b; });
             // ---- IntDiv and packing: the four keys of tile t become one word of the "B" operand
             const uint32_t inv = (1u << sm.m_bits) / (uint32_t)sum;
             const uint32_t inv_hi = FAST ? inv << (32 - sh) : 0u;      // FAST: inv < 2^sh, 1 <= sh <= 31

@@ -167,4 +167,16 @@ __device__ __forceinline__ int32_t wave_sum(int32_t v) {
            __builtin_amdgcn_readlane(v, 48);
 }
 
+// All-reduce over the four rows of 16 lanes of a wavefront (lanes l, l + 16, l + 32, l + 48), every lane getting the
+// result, without a trip through LDS: v_permlane16_swap exchanges the odd rows of its first operand with the even rows
+// of its second, v_permlane32_swap the upper half of the first with the lower half of the second; given two copies of
+// v, each leaves a lane's own value and its partner's side by side.
+template <class OP>
+__device__ __forceinline__ int32_t rows_allreduce(int32_t v, OP op) {
+    const auto a = __builtin_amdgcn_permlane16_swap((uint32_t)v, (uint32_t)v, false, false);
+    v = op((int32_t)a[0], (int32_t)a[1]);
+    const auto b = __builtin_amdgcn_permlane32_swap((uint32_t)v, (uint32_t)v, false, false);
+    return op((int32_t)b[0], (int32_t)b[1]);
+}
+
 }  // namespace ivit
