@@ -188,6 +188,7 @@ hipError_t launch_ilayernorm(hipStream_t s, const int8_t* x, const int32_t* gamm
         const int64_t resident = (int64_t)num_cus() * 8;
         int J = 1;
         while (J < 8 && (rows + rp * J - 1) / (rp * J) > resident) J <<= 1;
+        while (J > 1 && rp * J > 256) J >>= 1;       // at most one row of scalar work per thread (narrow rows: C < 128)
         const int64_t grid = (rows + rp * J - 1) / (rp * J);
         if (grid <= 0x7fffffffLL) {
             TraceScope trace(s, KIND_ILAYERNORM, 0, 2 * rows * C + 8LL * C);
