@@ -45,6 +45,10 @@ struct Narrow { int32_t lo, hi, mb, ad; };
 template <int FAST>
 __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d, Narrow n) {
     if (FAST == 2) {
+        // The median of three as the one instruction, by hand because the compiler cannot know lo <= hi.  The compiler
+        // does not see what an asm statement reads and puts no wait states between it and the producer of v: v must
+        // have been written long before (here: MFMA results of a whole tile sweep), never by the instruction just
+        // before (a dot product feeding this directly was seen to read a stale register).
         int32_t m;
         asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(v), "v"(n.lo), "v"(n.hi));
         return (__mul24(m, n.mb) + n.ad) >> 24;

@@ -468,6 +468,8 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
                     uint32_t o[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
+                        // (an asm statement gets no wait states from the compiler: its input must not come from the
+                        // instruction just before; the accumulators were written at least one MFMA group earlier)
                         int32_t m;
                         asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(acc[cb][4 * w4 + r]), "v"(lo[r]), "v"(hi[r]));
                         o[r] = (uint32_t)(__mul24(m, mb[r]) + ad[r]);             // result in the top byte

@@ -115,6 +115,8 @@ __device__ __forceinline__ uint32_t shiftexp_small(int32_t I, int32_t i0, int32_
 
 // Low 32 bits of the product of the low 24 bits of a and b, as the one full-rate instruction.  Written out because the
 // compiler falls back to the quarter-rate 32-bit multiply when an operand's range was established in another block.
+// (The compiler inserts no wait states for what an asm statement reads: the operands must come from ordinary vector
+// instructions or loads, not directly from a dot-product, matrix or transcendental instruction.)
 __device__ __forceinline__ uint32_t mul_u24(uint32_t a, uint32_t b) {
     uint32_t r;
     asm("v_mul_u32_u24 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
