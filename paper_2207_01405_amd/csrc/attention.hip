@@ -209,6 +209,14 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                     if ((t & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            // requant8 reads the MFMA results through an asm statement, which gets no hazard wait states from the
+            // compiler: the last MFMA above (8 passes: 10 wait states) is given its time by hand
+            if (FAST == 2) {
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_nop(7);
+                __builtin_amdgcn_s_nop(3);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // ---- requantise, add the bias, row maximum.  Lane (li, lg) holds keys 16 t + 4 lg + r.
             const int64_t tap_row = ((int64_t)item * T + qc) * T;
             // BIAS: a relative-position bias and / or the shifted-window mask.  A masked key gets -100 I_0 (the -100
@@ -344,6 +352,12 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 __builtin_amdgcn_sched_barrier(0);
             }
             // ---- requantise and store: lane holds features lg (D/4) + 4 n + r of query q
+            if (FAST == 2) {                       // as above: asm readers of fresh MFMA results
+                __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_s_nop(7);
+                __builtin_amdgcn_s_nop(3);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             uint32_t ow[ND];
 #pragma unroll
             for (int n = 0; n < ND; ++n) {

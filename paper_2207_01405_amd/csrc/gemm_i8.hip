@@ -456,6 +456,14 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         const int64_t tok = cgrp * 32 + li;
         const int nl = 16 * NCB * lg;                   // slab-local first channel of the lane
         if (EPI != EPI_RESIDUAL && fast24) {
+            // The asm statements below read the accumulators and get no hazard wait states from the compiler: make
+            // sure by hand that the last MFMA (16 passes: 18 wait states) has written them, whatever the scheduler
+            // placed in between.  Three instructions per token group.
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_nop(7);
+            __builtin_amdgcn_s_nop(7);
+            __builtin_amdgcn_s_nop(3);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
                 v4i outv;
