@@ -134,12 +134,22 @@ __device__ __forceinline__ int32_t mul_i24(int32_t a, int32_t b) {
 __device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
     if (v == 0) return 0;
     uint32_t x = 1u << ((32 - __clz(v)) >> 1);
+    // An iterate that repeats is a fixed point of the map, so every later iterate equals it: stopping there gives the
+    // tenth iterate with fewer steps (an oscillating sequence simply runs all ten).
     if (v < (1u << 22)) {
 #pragma unroll 1
-        for (int it = 0; it < 10; ++it) x = (x + div_small(v, x)) >> 1;
+        for (int it = 0; it < 10; ++it) {
+            const uint32_t xn = (x + div_small(v, x)) >> 1;
+            if (xn == x) break;
+            x = xn;
+        }
     } else {
 #pragma unroll 1
-        for (int it = 0; it < 10; ++it) x = (x + v / x) >> 1;  // x stays >= 1 for v >= 1
+        for (int it = 0; it < 10; ++it) {
+            const uint32_t xn = (x + v / x) >> 1;               // x stays >= 1 for v >= 1
+            if (xn == x) break;
+            x = xn;
+        }
     }
     return x;
 }
