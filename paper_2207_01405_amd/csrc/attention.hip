@@ -213,8 +213,8 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             // compiler: the last MFMA above (8 passes: 10 wait states) is given its time by hand
             if (FAST == 2) {
                 __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_nop(7);
-                __builtin_amdgcn_s_nop(3);
+                asm volatile("s_nop 7");
+                asm volatile("s_nop 3");
                 __builtin_amdgcn_sched_barrier(0);
             }
             // ---- requantise, add the bias, row maximum.  Lane (li, lg) holds keys 16 t + 4 lg + r.
@@ -354,8 +354,8 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             // ---- requantise and store: lane holds features lg (D/4) + 4 n + r of query q
             if (FAST == 2) {                       // as above: asm readers of fresh MFMA results
                 __builtin_amdgcn_sched_barrier(0);
-                __builtin_amdgcn_s_nop(7);
-                __builtin_amdgcn_s_nop(3);
+                asm volatile("s_nop 7");
+                asm volatile("s_nop 3");
                 __builtin_amdgcn_sched_barrier(0);
             }
             uint32_t ow[ND];

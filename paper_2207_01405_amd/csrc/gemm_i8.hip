@@ -460,9 +460,9 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             // sure by hand that the last MFMA (16 passes: 18 wait states) has written them, whatever the scheduler
             // placed in between.  Three instructions per token group.
             __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_nop(7);
-            __builtin_amdgcn_s_nop(7);
-            __builtin_amdgcn_s_nop(3);
+            asm volatile("s_nop 7");
+            asm volatile("s_nop 7");
+            asm volatile("s_nop 3");
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
