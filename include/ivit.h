@@ -104,6 +104,11 @@ typedef struct { const int32_t *gamma, *beta; int32_t f_bits, c_shift; } ivit_fi
 /* Text for a status code (static storage, never NULL). */
 const char* ivit_strerror(int status);
 
+/* Identifier of the sources this library was built from: a digest over the kernel sources and this header, set by
+ * the build script ("unknown" when built by other means).  Host memory, static; never NULL.  The Python binding
+ * compares it with the sources next to it and refuses a library built from other ones. */
+const char* ivit_build_id(void);
+
 /* Dense / MatMul with the dyadic pipeline (Sec. 3.2, Eq. 7-10), optionally fused
  * with the residual add of Eq. 1-2 or with ShiftGELU (Eq. 5, Algorithm 2).
  *   acc[m][j] = sum_k x[m][k] * w[j][k] + bias[j]                      (exact, int32)

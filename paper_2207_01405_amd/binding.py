@@ -8,13 +8,14 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libivit.so")
+_DEFAULT_LIB = os.path.join(_HERE, "libivit.so")
+LIB_PATH = _DEFAULT_LIB     # tests of build variants may point this elsewhere before load()
 
 IVIT_OK = 0
 IVIT_ERR_NULL, IVIT_ERR_SHAPE, IVIT_ERR_PARAM, IVIT_ERR_ALIGN, IVIT_ERR_WORKSPACE, IVIT_ERR_HIP = -1, -2, -3, -4, -5, -6
 ERRORS = {"NULL": -1, "SHAPE": -2, "PARAM": -3, "ALIGN": -4, "WORKSPACE": -5, "HIP": -6}
 
-EXPORTS = ("ivit_strerror", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftgelu", "ivit_shiftgelu_raw",
+EXPORTS = ("ivit_strerror", "ivit_build_id", "ivit_linear_requant", "ivit_shiftmax", "ivit_shiftgelu", "ivit_shiftgelu_raw",
            "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward",
            "ivit_trace_begin", "ivit_trace_end", "ivit_quantize_symmetric", "ivit_dyadic_from_float",
            "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
@@ -103,6 +104,14 @@ def load():
         raise RuntimeError("libivit.so is not built (%s); run `python -m paper_2207_01405_amd.build`" % LIB_PATH)
     lib = C.CDLL(LIB_PATH)
     i32, i64 = C.c_int32, C.c_int64
+    # a library built from other sources than the ones next to this file (a failed or forgotten rebuild) is refused
+    lib.ivit_build_id.restype = C.c_char_p; lib.ivit_build_id.argtypes = []
+    if LIB_PATH == _DEFAULT_LIB and os.path.isdir(os.path.join(_HERE, "csrc")):
+        from . import build as _build
+        have, want = lib.ivit_build_id().decode(), _build.source_id()
+        if have != want:
+            raise RuntimeError("libivit.so (build id %s) was not built from the present sources (%s); "
+                               "run `python -m paper_2207_01405_amd.build`" % (have, want))
     lib.ivit_strerror.restype = C.c_char_p; lib.ivit_strerror.argtypes = [C.c_int]
     lib.ivit_linear_requant.restype = C.c_int
     lib.ivit_linear_requant.argtypes = [_P, _P, _P, _P, _P, _P, _P, Dyadic, C.POINTER(ShiftParams), Dyadic, _P, i64, i32, i32]

@@ -155,6 +155,11 @@ hipError_t run_block(hipStream_t s, const int8_t* x, int8_t* y, const ivit_block
 
 extern "C" {
 
+#ifndef IVIT_BUILD_ID
+#define IVIT_BUILD_ID "unknown"
+#endif
+const char* ivit_build_id(void) { return IVIT_BUILD_ID; }
+
 const char* ivit_strerror(int status) {
     switch (status) {
         case IVIT_OK: return "ok";

@@ -296,3 +296,11 @@ def test_forward_swin_validation(lib):
     for cfg in synth.SWIN.values():                     # the synthetic windowed models fit
         sp2, k3 = _fake_swin(cfg["grid"], cfg["window"], cfg["C"], cfg["heads"], cfg["depths"])
         assert lib.ivit_swin_workspace_bytes(C.byref(sp2), cfg["B"]) > 0
+
+
+def test_library_was_built_from_the_present_sources():
+    """The build script stamps the library with a digest of its sources; the binding refuses a stale library.  A
+    library that does not match means a rebuild was forgotten or failed."""
+    from paper_2207_01405_amd import build
+    lib = binding.load()
+    assert lib.ivit_build_id().decode() == build.source_id()
