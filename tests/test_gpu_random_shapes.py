@@ -14,6 +14,9 @@ from paper_2207_01405_amd import synth
 
 pytestmark = pytest.mark.gpu
 
+# IVIT_TEST_SEED_OFFSET=n shifts every seed by n: further draws of the same generators for a longer run
+SEED_OFFSET = int(__import__("os").environ.get("IVIT_TEST_SEED_OFFSET", "0"))
+
 
 def dev(a):
     import torch
@@ -68,6 +71,7 @@ def dense_path(request, monkeypatch):
 
 @pytest.mark.parametrize("seed", range(36))
 def test_linear_random(ivit, dense_path, seed):
+    seed += SEED_OFFSET
     rng = np.random.default_rng(1000 + seed)
     K = 16 * int(rng.choice([1, 2, 3, 5, 6, 8, 12, 16, 24, 25, 48, 96, 100, 192]))
     N = int(rng.choice([16, 48, 64, 80, 128, 144, 256, 400, 1000, 7, 33])) if seed % 3 else 16 * int(rng.integers(1, 60))
@@ -95,6 +99,7 @@ def test_linear_random(ivit, dense_path, seed):
 
 @pytest.mark.parametrize("seed", range(24))
 def test_attention_random(ivit, seed):
+    seed += SEED_OFFSET
     rng = np.random.default_rng(2000 + seed)
     D = int(rng.choice([32, 64]))
     H = int(rng.choice([1, 2, 3, 5]))
@@ -127,6 +132,7 @@ def test_attention_random(ivit, seed):
 
 @pytest.mark.parametrize("seed", range(16))
 def test_rowwise_random(ivit, seed):
+    seed += SEED_OFFSET
     rng = np.random.default_rng(3000 + seed)
     rows = int(rng.choice([1, 2, 63, 64, 65, 1000, 4097]))
     # I-LayerNorm
@@ -166,6 +172,7 @@ def test_rowwise_random(ivit, seed):
 
 @pytest.mark.parametrize("seed", range(8))
 def test_block_random(ivit, dense_path, seed):
+    seed += SEED_OFFSET
     """Whole blocks on random widths, with every intermediate tensor."""
     import torch
     rng = np.random.default_rng(4000 + seed)
