@@ -378,20 +378,38 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
         // (-128 2^c, 128 2^c) and T 2^(24-c) fits 32 bits with the result in its top byte: one median of three against
         // [Ln - bias, Lp - bias], one 24-bit multiply-add by b 2^(24-c) (the addend, taken modulo 2^32, carries bias and
         // rounding), no shift and no final clamp.  Needs c <= 24, b 2^(24-c) < 2^23 and bounds that fit 24 bits;
-        // anything else takes the 64-bit paths below.
+        // anything else takes the 64-bit paths below.  (Residual layers: the same with wider bounds and the result one
+        // bit lower, see below.)
+        // Residual layers: the first term only has to be exact within +-(127 + R2), R2 the largest magnitude of the
+        // (per-tensor) residual term, because beyond that the clamped sum is +-127 whatever the residual adds.  With
+        // R2 <= 128 the limited first term needs nine bits: it is kept one bit lower, in bits 23..31.
+        int64_t wlim = 127;
+        int sh24 = 24;
         bool chan_24 = true;
+        if (EPI == EPI_RESIDUAL) {
+            const int64_t br = P.res_rq.b, cr = P.res_rq.c;
+            bool res_ok = br >= 1 && br < (1 << 23) && cr >= 1 && cr <= 30;
+            if (res_ok) {
+                const int64_t hr = (int64_t)1 << (cr - 1);
+                const int64_t r2 = max((127 * br + hr) >> cr, -((-128 * br + hr) >> cr));
+                res_ok = r2 <= 128;
+                wlim = 127 + r2;
+            }
+            sh24 = 23;
+            chan_24 = res_ok;
+        }
         if (tid < NS) {
             int32_t lo = 0, hi = 0, mb = 0, ad = 0;
-            if (n0 + tid < N) {
-                chan_24 = pc >= 1 && pc <= 24 && pb >= 1 && pb < (1 << ((pc - 1) & 31));
+            if (n0 + tid < N && chan_24) {
+                chan_24 = pc >= 1 && pc <= sh24 && pb >= 1 && pb < (1 << ((pc - 1) & 31));
                 if (chan_24) {
                     const int64_t half = (int64_t)1 << (pc - 1), two_c = (int64_t)1 << pc;
-                    const int64_t Lp = (127 * two_c - half + pb - 1) / pb;
-                    const int64_t Ln = -((127 * two_c - half + 1 + pb - 1) / pb);
+                    const int64_t Lp = (wlim * two_c - half + pb - 1) / pb;
+                    const int64_t Ln = -((wlim * two_c - half + 1 + pb - 1) / pb);
                     const int64_t l = Ln - pbias, h = Lp - pbias;
                     chan_24 = l >= -(1 << 23) && h < (1 << 23);
-                    lo = (int32_t)l; hi = (int32_t)h; mb = pb << (24 - pc);
-                    ad = (int32_t)(uint32_t)((uint64_t)((int64_t)pbias * pb + half) << (24 - pc));
+                    lo = (int32_t)l; hi = (int32_t)h; mb = pb << (sh24 - pc);
+                    ad = (int32_t)(uint32_t)((uint64_t)((int64_t)pbias * pb + half) << (sh24 - pc));
                 }
             }
             lo_s[tid] = lo; hi_s[tid] = hi; mb_s[tid] = mb; ad_s[tid] = ad;
@@ -402,7 +420,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     }
     if (!has_work) return;
     const bool fast = !slow_any && (EPI != EPI_RESIDUAL || dyadic_fits32(P.res_rq.b, P.res_rq.c));
-    const bool fast24 = EPI != EPI_RESIDUAL && !wide_any;
+    const bool fast24 = !wide_any;
 
     // The accumulators hold the bare dot products: the first MFMA group of a token group takes C = 0, and the bias
     // enters through the 64-bit addend of the requantisation (general path: added explicitly).
@@ -486,6 +504,42 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
                     // top (GELU: low) bytes of o[0..3] -> one word
                     const uint32_t p01 = __builtin_amdgcn_perm(o[1], o[0], EPI == EPI_GELU ? 0x0c0c0400u : 0x0c0c0703u);
                     const uint32_t p23 = __builtin_amdgcn_perm(o[3], o[2], EPI == EPI_GELU ? 0x04000c0cu : 0x07030c0cu);
+                    outv[w4] = (int)(p01 | p23);
+                }
+                *reinterpret_cast<v4i*>(stage + li * SP + nl + 16 * cb) = outv;
+            }
+        } else if (EPI == EPI_RESIDUAL && fast24) {
+            // first term limited and taken from bits 23..31 of one 24-bit multiply-add (see the prologue), residual term
+            // by a second one (|residual| <= 128, b_r < 2^23), then the sum is clamped
+            __builtin_amdgcn_sched_barrier(0);          // as above: asm readers of fresh MFMA results
+            asm volatile("s_nop 7");
+            asm volatile("s_nop 7");
+            asm volatile("s_nop 3");
+            __builtin_amdgcn_sched_barrier(0);
+            const int32_t rb = P.res_rq.b, rc = P.res_rq.c, rh = 1 << ((P.res_rq.c - 1) & 31);
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                const int64_t rt = min<int64_t>(tok, M - 1);
+                const v4i resv = *reinterpret_cast<const v4i*>(P.residual + rt * N + min(n0 + nl + 16 * cb, N - 16));
+                v4i outv;
+#pragma unroll
+                for (int w4 = 0; w4 < 4; ++w4) {
+                    const v4i lo = *reinterpret_cast<const v4i*>(&lo_s[nl + 16 * cb + 4 * w4]);
+                    const v4i hi = *reinterpret_cast<const v4i*>(&hi_s[nl + 16 * cb + 4 * w4]);
+                    const v4i mb = *reinterpret_cast<const v4i*>(&mb_s[nl + 16 * cb + 4 * w4]);
+                    const v4i ad = *reinterpret_cast<const v4i*>(&ad_s[nl + 16 * cb + 4 * w4]);
+                    uint32_t o[4];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        int32_t m;
+                        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(acc[cb][4 * w4 + r]), "v"(lo[r]), "v"(hi[r]));
+                        const int32_t t1 = (__mul24(m, mb[r]) + ad[r]) >> 23;
+                        const int32_t res = (int32_t)(int8_t)((uint32_t)resv[w4] >> (8 * r));
+                        const int32_t t2 = (__mul24(res, rb) + rh) >> rc;
+                        o[r] = (uint32_t)clamp8(t1 + t2);
+                    }
+                    const uint32_t p01 = __builtin_amdgcn_perm(o[1], o[0], 0x0c0c0400u);
+                    const uint32_t p23 = __builtin_amdgcn_perm(o[3], o[2], 0x04000c0cu);
                     outv[w4] = (int)(p01 | p23);
                 }
                 *reinterpret_cast<v4i*>(stage + li * SP + nl + 16 * cb) = outv;

@@ -282,6 +282,16 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
         assert_same(host(y), want, "linear at the limits of the narrow path" + (" + gelu" if kw else ""))
     plain = orc.linear_requant(x, w, bias, b, c)
     assert (plain == 127).mean() > 0.02 and (plain == -127).mean() > 0.02 and (np.abs(plain) < 127).mean() > 0.3
+    # the residual layers' 24-bit form (shift <= 23, residual multiplier below 2^23, residual term at most 128 in
+    # magnitude) at and past its limits; the residual holds -128 as well, and saturated rows on both sides
+    res = synth.make_rows(K + 2, M, N, "uniform")
+    res[0:4] = 127; res[4:8] = -128; res[8:12] = -127; res[12:16] = 127; res[16:20] = -128
+    for rq in ((2 ** 15, 15), (2 ** 15 - 1, 15), (2 ** 15 + 1, 15), (33000, 15), (2 ** 23 - 1, 23), (2 ** 23, 23),
+               (2 ** 23 - 1, 30), (5, 31), (1, 1), (3, 2), (23456, 15)):
+        y = empty((M, N))
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, residual=dev(res), res_rq=rq)
+        want = orc.linear_requant(x, w, bias, b, c, residual=res, res_rq=rq)
+        assert_same(host(y), want, "linear + residual at the limits of the narrow path, residual pair %s" % (rq,))
 
 
 # ------------------------------------------------------------------ fused attention
