@@ -157,7 +157,7 @@ __device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
 // Reductions over the 64 lanes of a wavefront; every lane gets the result.  Inside each row of 16 lanes four DPP
 // exchanges (lane pairs, quad pairs, half-row mirror, row mirror: all of them read existing lanes, so "bound_ctrl with
 // old = 0" only serves to let the compiler fold the move into the operation); the four row results are then combined
-// through scalar registers.
+// through scalar registers.  To be called where all 64 lanes are active (an inactive source lane would read as 0).
 template <int CTRL>
 __device__ __forceinline__ int32_t dpp_i32(int32_t v) {
     return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
