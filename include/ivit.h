@@ -9,8 +9,9 @@
  *
  * General rules
  *  - Every tensor pointer is a DEVICE pointer owned by the caller; the library
- *    never allocates, frees or keeps device memory.  Scratch space for the
- *    block / forward calls is a caller-supplied workspace.
+ *    never allocates or frees device memory.  Scratch space for the block /
+ *    forward calls is a caller-supplied workspace (one exception, stated there:
+ *    ivit_encoder_block_static uses a fixed array inside the library's device image).
  *  - Parameter structs (ivit_shift_params, ivit_dyadic, ivit_dims,
  *    ivit_block_params, ivit_final_ln, ivit_debug_taps) are HOST structs read
  *    before the launch; pointers inside them are device pointers.
@@ -185,6 +186,19 @@ size_t ivit_workspace_bytes(const ivit_dims* d);
 int ivit_encoder_block(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* p,
                        const ivit_dims* d, void* workspace, size_t workspace_bytes,
                        const ivit_debug_taps* taps);
+
+/* ivit_encoder_block for callers that cannot allocate device memory (code under HIP graph capture, serving loops
+ * that must not call hipMalloc, harnesses that forbid it): same arguments, checks and results, but the intermediate
+ * tensors live in a scratch array of IVIT_STATIC_SCRATCH_BYTES that is part of the library's device image (one copy
+ * per GPU, held until the process ends) instead of a caller's workspace.  The call itself allocates and frees
+ * nothing.  Dimensions whose intermediates do not fit (roughly B * T * (9 C + F) bytes) give IVIT_ERR_WORKSPACE.
+ * All calls on one GPU share that GPU's array: calls that may run at the same time (different streams, different
+ * threads) race on it and must be serialised by the caller; calls on one stream are ordered and safe.  Nothing in
+ * the array has to survive between calls.  The device of `stream` must be the current device.
+ * Errors: NULL, SHAPE, PARAM, ALIGN, WORKSPACE (too large for the scratch), HIP. */
+#define IVIT_STATIC_SCRATCH_BYTES (32u << 20)
+int ivit_encoder_block_static(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* p,
+                              const ivit_dims* d, const ivit_debug_taps* taps);
 
 /* n_blocks encoder blocks in sequence (n_blocks >= 0), then the optional final
  * I-LayerNorm.  `blocks` is a host array.  x, y [B*T, C] int8 (y must not alias x). */

@@ -21,7 +21,7 @@ EXPORTS = ("ivit_strerror", "ivit_build_id", "ivit_linear_requant", "ivit_shiftm
            "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
            "ivit_forward_image", "ivit_attention_masked", "ivit_window_attention", "ivit_patch_merge_gather",
            "ivit_mean_pool", "ivit_swin_window_index", "ivit_swin_shift_mask", "ivit_swin_workspace_bytes",
-           "ivit_forward_swin", "ivit_shiftgelu_rowmax")
+           "ivit_forward_swin", "ivit_shiftgelu_rowmax", "ivit_encoder_block_static")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
               7: "shiftgelu", 8: "embed_tokens", 9: "patch_merge_gather", 10: "mean_pool"}
@@ -138,6 +138,8 @@ def load():
     lib.ivit_encoder_block.restype = C.c_int
     lib.ivit_encoder_block.argtypes = [_P, _P, _P, C.POINTER(BlockParams), C.POINTER(Dims), _P, C.c_size_t,
                                        C.POINTER(DebugTaps)]
+    lib.ivit_encoder_block_static.restype = C.c_int
+    lib.ivit_encoder_block_static.argtypes = [_P, _P, _P, C.POINTER(BlockParams), C.POINTER(Dims), C.POINTER(DebugTaps)]
     lib.ivit_forward.restype = C.c_int
     lib.ivit_forward.argtypes = [_P, _P, _P, C.POINTER(BlockParams), i32, C.POINTER(FinalLN), C.POINTER(Dims), _P,
                                  C.c_size_t]
@@ -345,6 +347,19 @@ def ivit_encoder_block(x, y, p, d, workspace, taps=None, stream=None):
     st = load().ivit_encoder_block(_stream(stream), _ptr(x), _ptr(y), C.byref(bp), C.byref(dims(d)),
                                    _ptr(workspace), workspace.numel() * workspace.element_size(), tp)
     _check(st, "ivit_encoder_block")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 32 << 20     # IVIT_STATIC_SCRATCH_BYTES of include/ivit.h
+
+
+def ivit_encoder_block_static(x, y, p, d, taps=None, stream=None):
+    tp = None
+    if taps is not None:
+        tp = C.byref(DebugTaps(*[_ptr(taps.get(n)) for n in TAP_NAMES]))
+    bp = block_params(p)
+    st = load().ivit_encoder_block_static(_stream(stream), _ptr(x), _ptr(y), C.byref(bp), C.byref(dims(d)), tp)
+    _check(st, "ivit_encoder_block_static")
     return y
 
 

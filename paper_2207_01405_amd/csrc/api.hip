@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstdlib>
+#include <mutex>
 
 #include "ivit_kernels.hpp"
 
@@ -149,6 +150,28 @@ hipError_t run_block(hipStream_t s, const int8_t* x, int8_t* y, const ivit_block
     la.x = w.h; la.w = p->w_fc2; la.bias = p->bias_fc2; la.rq_b = p->fc2_rq_b; la.rq_c = p->fc2_rq_c;
     la.residual = w.xhat; la.res_rq = dy(p->res2_rq); la.gelu = false; la.y = y; la.M = R; la.N = C; la.K = F;
     return ivit::launch_linear(s, la);
+}
+
+// Scratch of ivit_encoder_block_static: one array per GPU, allocated by the loader with the code object and held
+// until the process ends.  In host code the name below is only a handle for hipGetSymbolAddress; the address the
+// kernels get is looked up once per device (with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[IVIT_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void* scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return IVIT_ERR_HIP;
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return IVIT_ERR_HIP;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return IVIT_OK;
 }
 
 }  // namespace
@@ -296,6 +319,24 @@ int ivit_encoder_block(void* stream, const int8_t* x, int8_t* y, const ivit_bloc
     if (!aligned(workspace, 256) || !aligned(x, 16) || !aligned(y, 16)) return IVIT_ERR_ALIGN;
     Workspace w;
     carve(d, workspace, &w);
+    return hip_status(run_block(static_cast<hipStream_t>(stream), x, y, p, d, w, taps));
+}
+
+int ivit_encoder_block_static(void* stream, const int8_t* x, int8_t* y, const ivit_block_params* p, const ivit_dims* d,
+                              const ivit_debug_taps* taps) {
+    if (!p || !d) return IVIT_ERR_NULL;
+    int st;
+    if ((st = check_dims(d)) != IVIT_OK) return st;
+    if (d->B > 0 && (!x || !y)) return IVIT_ERR_NULL;
+    if ((st = check_block(p, d)) != IVIT_OK) return st;
+    if (carve(d, nullptr, nullptr) > (size_t)IVIT_STATIC_SCRATCH_BYTES) return IVIT_ERR_WORKSPACE;
+    if (!aligned(x, 16) || !aligned(y, 16)) return IVIT_ERR_ALIGN;
+    void* base = nullptr;
+    if ((st = static_scratch(&base)) != IVIT_OK) return st;
+    // every buffer carved from the scratch is written in full by the launch that produces it before anything reads
+    // it, so what an earlier call left there never shows and nothing has to be cleared
+    Workspace w;
+    carve(d, base, &w);
     return hip_status(run_block(static_cast<hipStream_t>(stream), x, y, p, d, w, taps));
 }
 
