@@ -27,9 +27,8 @@
  *  - Integer semantics: ">>" is an arithmetic shift (floor); round(v, c) =
  *    (v + 2^(c-1)) >> c; clamp8(v) = min(max(v, -127), 127);
  *    requant(v; b, c) = clamp8(round(b * v, c)) with the product in 64 bits.
- *  - Environment: IVIT_LOG (any value) prints the HIP error text behind an IVIT_ERR_HIP to stderr;
- *    IVIT_DENSE_PATH=large keeps Dense layers with few rows off the kernel written for them (a switch for tests:
- *    results are identical either way).
+ *  - The library reads no environment variables.  After an IVIT_ERR_HIP, ivit_last_hip_error() gives the
+ *    hipError_t behind the calling thread's most recent one.
  *  - Values in device parameter arrays cannot be checked on the host: rq_b must
  *    hold 1 <= b < 2^31 and rq_c must hold 1 <= c <= 46; other values give
  *    unspecified results (never a fault).
@@ -127,6 +126,25 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
                         const int8_t* residual, ivit_dyadic res_rq,
                         const ivit_shift_params* gelu, ivit_dyadic gelu_rq,
                         int8_t* y, int64_t M, int32_t N, int32_t K);
+
+/* ivit_linear_requant with options (opt == NULL: exactly ivit_linear_requant).
+ *   kernel  which Dense kernel runs; results are identical for every choice (Sec. 3.2 fixes the arithmetic, not
+ *           the schedule), so this is a switch for tests and measurements:
+ *           IVIT_KERNEL_AUTO            chosen from the shape;
+ *           IVIT_KERNEL_MANY_ROWS       never the kernel written for few rows;
+ *           IVIT_KERNEL_REG_STATIONARY  the kernel that keeps the weights in registers; it takes K = 384 or 768
+ *                                       with N % 32 == 0 only, other shapes give IVIT_ERR_SHAPE.
+ * Errors: as ivit_linear_requant; PARAM for an unknown option value. */
+enum { IVIT_KERNEL_AUTO = 0, IVIT_KERNEL_MANY_ROWS = 1, IVIT_KERNEL_REG_STATIONARY = 2 };
+typedef struct { int32_t kernel; } ivit_linear_options;
+int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias,
+                           const int32_t* rq_b, const int32_t* rq_c,
+                           const int8_t* residual, ivit_dyadic res_rq,
+                           const ivit_shift_params* gelu, ivit_dyadic gelu_rq,
+                           int8_t* y, int64_t M, int32_t N, int32_t K, const ivit_linear_options* opt);
+
+/* The hipError_t (as an int) behind the most recent IVIT_ERR_HIP returned to the calling thread; 0 if there was none. */
+int ivit_last_hip_error(void);
 
 /* Shiftmax (Sec. 3.3, Algorithm 1) on each row: subtract the row maximum, ShiftExp,
  * IntDiv by the row sum, limit to 2^(k_out-1) - 1.

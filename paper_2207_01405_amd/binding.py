@@ -21,7 +21,8 @@ EXPORTS = ("ivit_strerror", "ivit_build_id", "ivit_linear_requant", "ivit_shiftm
            "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
            "ivit_forward_image", "ivit_attention_masked", "ivit_window_attention", "ivit_patch_merge_gather",
            "ivit_mean_pool", "ivit_swin_window_index", "ivit_swin_shift_mask", "ivit_swin_workspace_bytes",
-           "ivit_forward_swin", "ivit_shiftgelu_rowmax", "ivit_encoder_block_static")
+           "ivit_forward_swin", "ivit_shiftgelu_rowmax", "ivit_encoder_block_static", "ivit_linear_requant_ex",
+           "ivit_last_hip_error")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
               7: "shiftgelu", 8: "embed_tokens", 9: "patch_merge_gather", 10: "mean_pool"}
@@ -33,6 +34,13 @@ class ShiftParams(C.Structure):
 
 class Dyadic(C.Structure):
     _fields_ = [("b", C.c_int32), ("c", C.c_int32)]
+
+
+class LinearOptions(C.Structure):
+    _fields_ = [("kernel", C.c_int32)]
+
+
+KERNELS = {"auto": 0, "many_rows": 1, "reg_stationary": 2}
 
 
 class Dims(C.Structure):
@@ -115,6 +123,9 @@ def load():
     lib.ivit_strerror.restype = C.c_char_p; lib.ivit_strerror.argtypes = [C.c_int]
     lib.ivit_linear_requant.restype = C.c_int
     lib.ivit_linear_requant.argtypes = [_P, _P, _P, _P, _P, _P, _P, Dyadic, C.POINTER(ShiftParams), Dyadic, _P, i64, i32, i32]
+    lib.ivit_linear_requant_ex.restype = C.c_int
+    lib.ivit_linear_requant_ex.argtypes = lib.ivit_linear_requant.argtypes + [C.POINTER(LinearOptions)]
+    lib.ivit_last_hip_error.restype = C.c_int; lib.ivit_last_hip_error.argtypes = []
     lib.ivit_shiftmax.restype = C.c_int
     lib.ivit_shiftmax.argtypes = [_P, _P, _P, i32, i32, _P, i64, i32, i32, ShiftParams]
     lib.ivit_shiftgelu.restype = C.c_int; lib.ivit_shiftgelu.argtypes = [_P, _P, _P, i64, ShiftParams, Dyadic]
@@ -240,13 +251,18 @@ def dims(d):
 
 
 # ------------------------------------------------------------------ entry points (same names as the C ABI)
-def ivit_linear_requant(x, w, bias, rq_b, rq_c, y, residual=None, res_rq=None, gelu=None, gelu_rq=None, stream=None):
+def ivit_linear_requant(x, w, bias, rq_b, rq_c, y, residual=None, res_rq=None, gelu=None, gelu_rq=None, stream=None,
+                        kernel=None):
+    """kernel: None -> ivit_linear_requant; "auto" / "many_rows" / "reg_stationary" -> ivit_linear_requant_ex."""
     M, K = x.shape
     N = w.shape[0]
     g = None if gelu is None else C.byref(shift_params(gelu))
-    st = load().ivit_linear_requant(_stream(stream), _ptr(x), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c),
-                                    _ptr(residual), dyadic(res_rq), g, dyadic(gelu_rq), _ptr(y), M, N, K)
-    _check(st, "ivit_linear_requant")
+    args = (_stream(stream), _ptr(x), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c), _ptr(residual), dyadic(res_rq), g,
+            dyadic(gelu_rq), _ptr(y), M, N, K)
+    if kernel is None:
+        _check(load().ivit_linear_requant(*args), "ivit_linear_requant")
+    else:
+        _check(load().ivit_linear_requant_ex(*args, C.byref(LinearOptions(KERNELS[kernel]))), "ivit_linear_requant_ex")
     return y
 
 

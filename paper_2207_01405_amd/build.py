@@ -15,7 +15,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libivit.so")
-SOURCES = ["api.hip", "trace.hip", "rowwise.hip", "gemm_i8.hip", "attention.hip", "host_helpers.hip"]
+SOURCES = ["api.hip", "trace.hip", "rowwise.hip", "gemm_i8.hip", "gemm_rs.hip", "attention.hip", "host_helpers.hip"]
+# gemm_rs.hip: MFMA results in ordinary vector registers (the epilogue reads them with vector instructions; the
+# weights sit in the accumulation registers instead)
+EXTRA_FLAGS = {"gemm_rs.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions are kept out of every code object of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -43,7 +46,8 @@ def hipcc():
 
 def _compile(src):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
-    cmd = [hipcc(), *FLAGS, '-DIVIT_BUILD_ID="%s"' % source_id(), "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [hipcc(), *FLAGS, *EXTRA_FLAGS.get(src, []), '-DIVIT_BUILD_ID="%s"' % source_id(), "-c", os.path.join(CSRC, src),
+           "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))

@@ -34,9 +34,10 @@ inline int check_ln(int32_t C, int32_t f_bits, int32_t c_shift) {
 
 inline ShiftParams sp(const ivit_shift_params& p) { return ShiftParams{p.i0, p.n_shift, p.m_bits, p.k_out}; }
 inline Dyadic dy(ivit_dyadic d) { return Dyadic{d.b, d.c}; }
+thread_local int last_hip_error = 0;      // hipError_t behind the calling thread's last IVIT_ERR_HIP
 inline int hip_status(hipError_t e) {
     if (e == hipSuccess) return IVIT_OK;
-    if (getenv("IVIT_LOG")) fprintf(stderr, "ivit: HIP error %d (%s)\n", (int)e, hipGetErrorString(e));
+    last_hip_error = (int)e;
     return IVIT_ERR_HIP;
 }
 
@@ -196,9 +197,18 @@ const char* ivit_strerror(int status) {
     }
 }
 
+int ivit_last_hip_error(void) { return last_hip_error; }
+
 int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias, const int32_t* rq_b,
                         const int32_t* rq_c, const int8_t* residual, ivit_dyadic res_rq, const ivit_shift_params* gelu,
                         ivit_dyadic gelu_rq, int8_t* y, int64_t M, int32_t N, int32_t K) {
+    return ivit_linear_requant_ex(stream, x, w, bias, rq_b, rq_c, residual, res_rq, gelu, gelu_rq, y, M, N, K, nullptr);
+}
+
+int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias, const int32_t* rq_b,
+                           const int32_t* rq_c, const int8_t* residual, ivit_dyadic res_rq, const ivit_shift_params* gelu,
+                           ivit_dyadic gelu_rq, int8_t* y, int64_t M, int32_t N, int32_t K, const ivit_linear_options* opt) {
+    if (opt && (opt->kernel < IVIT_KERNEL_AUTO || opt->kernel > IVIT_KERNEL_REG_STATIONARY)) return IVIT_ERR_PARAM;
     if (M < 0 || N < 1 || K < 16 || K > 65536 || (K & 15)) return IVIT_ERR_SHAPE;
     if (M > 0 && (!x || !y)) return IVIT_ERR_NULL;             // an empty tensor may have no storage
     if (!w || !rq_b || !rq_c) return IVIT_ERR_NULL;
@@ -215,6 +225,8 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
     a.gelu = gelu != nullptr;
     if (gelu) { a.gelu_p = sp(*gelu); a.gelu_rq = dy(gelu_rq); }
     a.y = y; a.M = M; a.N = N; a.K = K;
+    a.kernel = opt ? opt->kernel : ivit::LINEAR_AUTO;
+    if (a.kernel == ivit::LINEAR_REG_STATIONARY && M > 0 && !ivit::linear_rs_takes(a)) return IVIT_ERR_SHAPE;
     return hip_status(ivit::launch_linear(static_cast<hipStream_t>(stream), a));
 }
 

@@ -14,7 +14,6 @@
 // Workgroup ids are remapped so that each XCD (own L2) works on a contiguous range of tiles.
 #include "ivit_kernels.hpp"
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 namespace ivit {
@@ -789,21 +788,25 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     if (grid > 0x7fffffffLL) return hipErrorInvalidValue;
     const int64_t bytes = a.M * a.K + (int64_t)a.N * a.K + a.M * a.N * (a.residual ? 2 : 1) + 8LL * a.N + (a.bias ? 4LL * a.N : 0);
     TraceScope trace(s, a.residual ? KIND_GEMM_RESIDUAL : (a.gelu ? KIND_GEMM_GELU : KIND_GEMM), 2 * a.M * a.N * a.K, bytes);
-    // few rows: one workgroup per 32 x 32 tile
-    // (IVIT_DENSE_PATH=large in the environment keeps such shapes on the kernels for many rows: a switch for tests)
+    // few rows: one workgroup per 32 x 32 tile (a.kernel can keep such shapes on the kernels for many rows)
     const int64_t small_tiles = ((a.M + 31) / 32) * ((a.N + 31) / 32);
-    const char* path = getenv("IVIT_DENSE_PATH");
     // measured on patches-to-logits forwards at batch 1 and 8: up to one tile per CU it always wins (batch 1: DeiT-S 0.77 ->
     // 0.66 ms, ViT-B 1.11 -> 0.74 ms), beyond that only when K is long enough for the split over the four wavefronts to pay
     // (a single image of a wide model: at most 256 rows)
     const int64_t small_limit = (int64_t)num_cus() * (a.K >= 768 && a.M <= 256 ? 3 : 1);
-    if (small_tiles <= small_limit && !(path && path[0] == 'l')) {
+    if (small_tiles <= small_limit && a.kernel == LINEAR_AUTO) {
         const dim3 g((unsigned)small_tiles), b(64 * SM_WAVES);
         if (a.residual) hipLaunchKernelGGL(gemm_small_kernel<EPI_RESIDUAL>, g, b, 0, s, P);
         else if (a.gelu) hipLaunchKernelGGL(gemm_small_kernel<EPI_GELU>, g, b, 0, s, P);
         else hipLaunchKernelGGL(gemm_small_kernel<EPI_PLAIN>, g, b, 0, s, P);
         return hipGetLastError();
     }
+    // weights in registers: K = 384 / 768 and enough rows for every workgroup to amortise loading them; measured against
+    // the kernels below on the DeiT-S and ViT-B shapes it wins on the layers without a residual (QKV 27.1 -> 23.0 us,
+    // fc1 35.5 -> 29.6 us at K = 384; 122 -> 92 us and 199 -> 149 us at K = 768) and loses on the projection, whose
+    // residual epilogue costs it more instructions per output (16.0 -> 21.2 us, 52 -> 60 us)
+    if (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && linear_rs_takes(a) && !a.residual && a.M >= 4096))
+        return launch_linear_rs(s, a);
     int ncb, unit, nunits, pitch; size_t lds_bytes;
     if (ws_plan(a, ncb, unit, nunits, pitch, lds_bytes)) {
         WsParams W;

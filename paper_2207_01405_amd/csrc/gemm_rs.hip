@@ -1,0 +1,634 @@
+// Dense layers with K of a few hundred bytes (I-ViT, arXiv 2207.01405, Sec. 3.2, Eq. 7-10; residual add of Eq. 1-2;
+// ShiftGELU of Sec. 3.4, Algorithm 2): the weights stay in REGISTERS for the whole kernel.
+//
+// A workgroup has GR groups of four wavefronts (one wavefront of each group per SIMD).  Wavefront w of a group owns
+// NCB tiles of 32 output channels and keeps their weights (all of K) in accumulation registers as the MFMA "B"
+// operand, so the matrix cores read no weights from LDS; the groups hold the same channels and work on different
+// token tiles.  The workgroup walks over stages of GR tiles of 32 tokens: the activations of a stage are fetched
+// straight from global memory into LDS (LDS-direct loads, no register pass) two stages ahead, and every wavefront
+// reads its group's tile from there as the "A" operand, one 1 KB fragment per NCB MFMAs.  (With K = 384 two
+// wavefronts per SIMD fit the register file, and a single wavefront cannot issue instructions fast enough to keep
+// its matrix core busy: the second one fills the gaps.  With K = 768 the weights leave room for one.)  The accumulator of a lane is then ONE
+// channel and 16 tokens, so the four requantisation constants of a channel live in four registers for the whole
+// kernel: the epilogue reads no tables.  There are two sets of accumulators; while token tile t is multiplied, the
+// results of tile t - 1 are requantised between the MFMAs of the same wavefront (an issued MFMA executes in the
+// background; with one wavefront per SIMD nothing else could fill the gaps).  Everything else a tile needs (one
+// barrier, the loads of a later tile, the stores of an earlier one) is spread over the k-steps in the same way.
+// The int8 results (16 tokens of a channel per lane) are turned into token rows through wavefront-private LDS with
+// the transposing LDS read of gfx950 (ds_read_b64_tr_b8) and leave as 16-byte pieces of contiguous row segments; the
+// residual operand comes in by the mirror image of that path.
+#include "ivit_kernels.hpp"
+#include <algorithm>
+
+namespace ivit {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+namespace {
+
+enum Epilogue { EPI_PLAIN = 0, EPI_RESIDUAL = 1, EPI_GELU = 2 };
+constexpr int NXCD = 8;
+constexpr int OP = 48;                       // pitch (bytes) of a channel row of the output staging tile: 32 tokens + padding
+constexpr int WCK = 384;                     // bytes of K per weight chunk of the prologue
+constexpr int WPITCH = WCK + 16;             // its row pitch in LDS
+constexpr int WWI = 4 * 32 * (WPITCH / 16) / 64;    // load instructions (64 lanes x 16 bytes) per chunk: [4 wavefronts][32 channels][WPITCH]
+
+struct RsParams {
+    const int8_t* x; const int8_t* w; const int32_t* bias; const int32_t* rq_b; const int32_t* rq_c;
+    const int8_t* residual; Dyadic res_rq; ShiftParams gelu_p; Dyadic gelu_rq;
+    int8_t* y; int64_t M; int N; int64_t ldx;
+    int slabs, q;                            // channel slabs (4 NCB tiles each), workgroups per slab
+    int64_t stages;                          // stages of GR token tiles of 32
+};
+
+__device__ __forceinline__ uint32_t lds_offset(const int8_t* p) {
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) int8_t*)p;
+}
+__device__ __forceinline__ const int8_t* uniform_ptr(const int8_t* p) {          // a pointer every lane agrees on -> scalar registers
+    const uint64_t v = (uint64_t)p;
+    // (the builtin returns a signed int: each half goes through uint32_t so that nothing is sign-extended into the other)
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (const int8_t*)(((uint64_t)hi << 32) | (uint64_t)lo);
+}
+
+// 16 bytes per lane from global memory straight into LDS: lane l's piece, read at base + off, lands at lds + 16 l
+// (base and lds are the same for all lanes).  Written as asm statements so that the compiler does not make every
+// later LDS read wait for all such loads; the waits are placed by hand (s_waitcnt vmcnt) where the data is first read.
+__device__ __forceinline__ void dma16(const int8_t* base, uint32_t off, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 : : "s"(__builtin_amdgcn_readfirstlane(lds_wave_base)), "v"(off), "s"(base) : "memory", "m0");
+}
+__device__ __forceinline__ void wait_vm0() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ int32_t med3(int32_t v, int32_t lo, int32_t hi) {
+    int32_t m;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(v), "v"(lo), "v"(hi));
+    return m;
+}
+
+// Token of the tile that sits in row i of the MFMA "A" operand.  Accumulator register e = 4 q + r of lane group g is
+// row 8 q + 4 g + r of the product; with this assignment it is token 16 g + e: a lane holds 16 consecutive tokens.
+__device__ __forceinline__ int token_of_row(int i) { return 16 * ((i >> 2) & 1) + 4 * (i >> 3) + (i & 3); }
+
+template <int KS, int NCB, int EPI, int GR>
+struct RsLayout {
+    static constexpr int NW = 4 * GR, NT = 64 * NW;               // wavefronts, threads
+    static constexpr int K = 32 * KS;
+    static constexpr int P16 = 2 * KS + 1, PITCH = 16 * P16;       // activation row in LDS: K bytes + one 16-byte pad piece
+    static constexpr int NWI = (32 * GR * P16 + 63) / 64;          // load instructions (64 lanes x 16 bytes) per stage
+    static constexpr int NI = (NWI + NW - 1) / NW;                 // ... per wavefront at most
+    static constexpr int XT = NWI * 1024;                          // bytes of a stage
+    static constexpr int OT = 32 * NCB * OP;                       // output staging tile of a wavefront
+    static constexpr int RP = 32 * NCB + 16, RS16 = RP / 16;       // residual staging: pitch of a token row, 16-byte slots in it
+    static constexpr int RNI = (32 * RS16 + 63) / 64;              // residual load instructions per lane and tile
+    static constexpr int RT = RNI * 1024;
+    static constexpr int XS = 0, OUT = 3 * XT, RES = OUT + NW * OT;
+    static constexpr int LUT = RES + (EPI == EPI_RESIDUAL ? NW * 2 * RT : 0);
+    static constexpr int MAIN = LUT + 256;
+    static constexpr int NCHUNK = NCB * (K / WCK);                 // weight chunks of the prologue
+    static constexpr int WNI = (WWI + NW - 1) / NW;                // load instructions per wavefront and chunk
+    static constexpr int WCHUNK = WNI * NW * 1024;                 // LDS bytes of a chunk (whole rounds of all wavefronts)
+    static constexpr int STAGING = (NCHUNK > 1 ? 2 : 1) * WCHUNK;  // the chunks pass through the same memory, before the main loop
+    static constexpr int TOTAL = MAIN > STAGING ? MAIN : STAGING;
+    static_assert(K % WCK == 0, "K must be a whole number of weight chunks");
+    static_assert(TOTAL + 1024 <= 160 * 1024, "LDS");
+};
+
+#ifdef IVIT_RS_TIMING
+__device__ long long rs_stamps[2048][32];
+#define RS_STAMP(i) do { if (lane == 0) rs_stamps[blockIdx.x * NW + wv][(i) < 31 ? (i) : 31] = clock64(); } while (0)
+#else
+#define RS_STAMP(i) do { } while (0)
+#endif
+
+template <int EPI, int KS, int NCB, int GR>
+__global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
+    using LY = RsLayout<KS, NCB, EPI, GR>;
+    constexpr int NW = LY::NW, NT = LY::NT;
+    constexpr int K = LY::K, PITCH = LY::PITCH, P16 = LY::P16, NWI = LY::NWI, NI = LY::NI, XT = LY::XT, OT = LY::OT;
+    constexpr int RP = LY::RP, RS16 = LY::RS16, RNI = LY::RNI, RT = LY::RT, WNI = LY::WNI, WCHUNK = LY::WCHUNK;
+#ifdef IVIT_RS_RG
+    constexpr int RG = GR == 2 ? IVIT_RS_RG : 3;
+#else
+    constexpr int RG = (KS % 3 == 0) ? 3 : 4;                  // ring of A fragments: RG - 1 k-steps of prefetch distance
+#endif
+    constexpr int NU = 4 * NCB;                                // epilogue units (4 outputs each) per token tile and lane
+    constexpr int SYNC = KS / 2;                               // k-step of the barrier
+    static_assert(KS % RG == 0, "ring must align with the tile");
+    static_assert(SYNC >= 2 && SYNC <= KS - RG, "the first fragments of the next tile are read after the barrier");
+    static_assert(KS - SYNC >= NI && KS - SYNC >= RNI && KS - SYNC >= NCB + 1, "the work after the barrier is spread over its k-steps");
+
+    extern __shared__ __align__(1024) int8_t lds[];
+    int8_t* Xs = lds + LY::XS;                                 // [3][XT]
+    int8_t* Out = lds + LY::OUT;                               // [waves][OT]
+    int8_t* Res = lds + LY::RES;                               // [waves][2][RT]   (residual layers only)
+    int8_t* gelu_lut = lds + LY::LUT;                          // [256]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register: what depends on it stays scalar
+    const int wq = wv & 3, grp = wv >> 2;                      // owner of channels (SIMD), group
+    const int lj = lane & 31, lg = lane >> 5;
+    const int N = P.N;
+    const int64_t M = P.M;
+    const int Nt = N >> 5;
+    RS_STAMP(0);
+
+    // workgroups of one XCD (block id modulo 8) get consecutive logical ids, so the slabs that share a token tile,
+    // and therefore read the same activations, sit on the same L2
+    const int G = gridDim.x, xcd = blockIdx.x % NXCD;
+    const int L = xcd * (G / NXCD) + min(xcd, G % NXCD) + blockIdx.x / NXCD;
+    const int slab = L % P.slabs, wi = L / P.slabs;
+    const int tile0 = (slab * 4 + wq) * NCB;                   // first channel tile of this wavefront
+    const int n0w = tile0 * 32;                                // its first channel
+    const int64_t ntile = wi < P.stages ? (P.stages - wi + P.q - 1) / P.q : 0;  // stages of this workgroup; stage k is wi + k q
+    if (ntile == 0) return;                                    // (the same for all wavefronts of a workgroup)
+
+    // ---- requantisation parameters of this lane's channels: requested first, used after the weights are in place
+    int32_t pb[NCB], pc[NCB], pbias[NCB];
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        const int ch = min(tile0 + cb, Nt - 1) * 32 + lj;      // channel tiles past the last one repeat it; never stored
+        pb[cb] = P.rq_b[ch]; pc[cb] = P.rq_c[ch]; pbias[cb] = P.bias ? P.bias[ch] : 0;
+    }
+
+    // ---- weights.  Lane (lj, lg) needs, for channel tile cb and k-step ks, bytes 32 ks + 16 lg .. + 15 of the row of
+    // channel 32 cb + lj: read like that from global memory, every load instruction would touch 32 rows.  Instead the
+    // workgroup brings them through LDS in chunks of [4 wavefronts][32 channels][384 bytes of K] with LDS-direct loads
+    // of whole rows (two chunks in flight), and every wavefront picks its fragments out of its part of the chunk.
+    v4i W[NCB][KS];
+    {
+        constexpr int NCHUNK = LY::NCHUNK, KH = K / WCK, W16 = WPITCH / 16;
+        const uint32_t stg = lds_offset(lds);
+        auto issue_chunk = [&](int c) __attribute__((always_inline)) {
+            const int cb = c / KH, kh = c % KH;
+#pragma unroll
+            for (int i = 0; i < WNI; ++i) {                     // (instructions past the chunk repeat its last row into the slack)
+                const int s = 64 * (i * NW + wv) + lane;
+                const int row = min(s / W16, 4 * 32 - 1), piece = min(s % W16, WCK / 16 - 1);
+                const int ch = min((slab * 4 + (row >> 5)) * NCB + cb, Nt - 1) * 32 + (row & 31);
+                dma16(uniform_ptr(P.w), (uint32_t)(ch * K + kh * WCK + 16 * piece), stg + (c & 1) * WCHUNK + (i * NW + wv) * 1024);
+            }
+        };
+        issue_chunk(0);
+        if (NCHUNK > 1) issue_chunk(1);
+#pragma unroll
+        for (int c = 0; c < NCHUNK; ++c) {
+            // loads complete in order: all but the WNI of the following chunk
+            if (c + 1 < NCHUNK) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WNI) : "memory"); else wait_vm0();
+            __syncthreads();
+            const int cb = c / KH, kh = c % KH;
+            const int8_t* src = lds + (c & 1) * WCHUNK + (wq * 32 + lj) * WPITCH + 16 * lg;
+#pragma unroll
+            for (int s = 0; s < WCK / 32; ++s) {
+                W[cb][kh * (WCK / 32) + s] = *reinterpret_cast<const v4i*>(src + 32 * s);
+                // the weights are only ever read by MFMAs, which take this operand from the accumulation registers just
+                // as well: pinning them there leaves the ordinary vector registers to the accumulators and the epilogue
+                asm volatile("" : "+a"(W[cb][kh * (WCK / 32) + s]));
+            }
+            __syncthreads();                                    // everyone has read the chunk: its memory is free again
+            if (c + 2 < NCHUNK) issue_chunk(c + 2);
+        }
+    }
+
+    // ---- activation loads: load instruction n (64 lanes x 16 bytes, n = i NW + wavefront) of a stage covers slots
+    // 64 n .. 64 n + 63; slot s is piece s % P16 of LDS row s / P16, and LDS row r holds token token_of_row(r % 32) of
+    // tile r / 32 of the stage, so that the lanes of an MFMA "A" read sit in consecutive LDS rows (the pad piece repeats
+    // the last one; slots past the last row repeat it and land in the slack of the stage).  The address of a piece is
+    // a scalar base (the stage) plus a 32-bit offset per lane, computed once; only a ragged last stage, whose missing
+    // rows repeat the last row of the matrix, computes offsets of its own.  What a stage or tile needs beyond that
+    // (its base pointer, how many of its rows exist) is scalar state that moves on by a fixed step per tile.
+    constexpr int SR = 32 * GR;                                // rows of a stage
+    const uint32_t xs_off = lds_offset(Xs) + wv * 1024;
+    int ld_row[NI], ld_col[NI];
+    uint32_t ld_off[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int s = 64 * (i * NW + wv) + lane;
+        const int r = min(s / P16, SR - 1);
+        ld_row[i] = 32 * (r >> 5) + token_of_row(r & 31);
+        ld_col[i] = 16 * min(s % P16, 2 * KS - 1);
+        ld_off[i] = (uint32_t)(ld_row[i] * (int)P.ldx + ld_col[i]);
+    }
+    const int64_t row_step = (int64_t)P.q * SR;                // rows between two stages of this workgroup
+    struct Cursor {                                            // a stage (or this group's tile of it) some steps ahead
+        const int8_t* p;                                       // its first row
+        int64_t rows;                                          // rows of the matrix from there on (<= 0: past the end)
+        int left;                                              // steps until it has reached the workgroup's last stage
+    };
+    auto cursor = [&](const int8_t* base, int64_t row_bytes, int64_t ahead, int row_in_stage) __attribute__((always_inline)) -> Cursor {
+        const int64_t k = min<int64_t>(ahead, ntile - 1);
+        const int64_t row0 = (wi + k * P.q) * SR + row_in_stage;
+        return Cursor{base + row0 * row_bytes, M - row0, (int)min<int64_t>(ntile - 1 - k, 1 << 30)};
+    };
+    auto advance = [&](Cursor& c, int64_t step_bytes) __attribute__((always_inline)) {      // past the end: the last stage again
+        if (c.left > 0) { --c.left; c.p += step_bytes; c.rows -= row_step; }
+    };
+    const int64_t x_step = row_step * P.ldx, n_step = row_step * N;
+    // one load instruction of a stage: base and rows are the stage's (scalars), rows >= 1
+    auto issue_act_one = [&](const int8_t* base, int rows, uint32_t dst, int i) __attribute__((always_inline)) {
+        if ((i + 1) * NW > NWI && i * NW + wv >= NWI) return;  // the stage ends inside the last round of instructions
+        if (rows >= SR) dma16(base, ld_off[i], dst + i * (NW * 1024));
+        else dma16(base, (uint32_t)(min(ld_row[i], rows - 1) * (int)P.ldx + ld_col[i]), dst + i * (NW * 1024));
+    };
+
+    // ---- residual tile of a wavefront: [32 tokens][RP] bytes, slot s = 64 i + lane = piece s % RS16 of token s / RS16
+    int8_t* out_w = Out + wv * OT;
+    int8_t* res_w = Res + wv * 2 * RT;
+    static_assert(NT >= 256, "the ShiftGELU table is filled by threads 0 .. 255");
+    const uint32_t res_off = lds_offset(res_w);
+    int rs_col[RNI], rs_row[RNI];
+    uint32_t rs_off[RNI];
+    if (EPI == EPI_RESIDUAL) {
+#pragma unroll
+        for (int i = 0; i < RNI; ++i) {
+            const int s = 64 * i + lane;
+            rs_row[i] = min(s / RS16, 31);
+            rs_col[i] = min(n0w + 16 * min(s % RS16, 2 * NCB - 1), N - 16);
+            rs_off[i] = (uint32_t)(rs_row[i] * N + rs_col[i]);
+        }
+    }
+    const int8_t* res_last = P.residual ? P.residual + (M - 1) * N : nullptr;     // a tile past the matrix reads its last row
+    auto issue_res_one = [&](const int8_t* base, int rows, uint32_t dst, int i) __attribute__((always_inline)) {      // rows >= 1
+        if (rows >= 32) dma16(base, rs_off[i], dst + i * 1024);
+        else dma16(base, (uint32_t)(min(rs_row[i], rows - 1) * N + rs_col[i]), dst + i * 1024);
+    };
+    // transposing read of the residual tile: in every block of 16 lanes the even lanes name eight 8-byte rows and lanes
+    // 0-7 receive their columns, the odd lanes name eight more and lanes 8-15 receive theirs.  Lane L = 16 B + j is to
+    // get channel (16 B + j) % 32 of tile cb, tokens 16 (B / 2) + 8 h + 0..7: source lane 16 B + 2 b + o names token
+    // 16 (B / 2) + 8 h + b, channels 16 (B % 2) + 8 o + 0..7.
+    const int rr_base = ((lane >> 5) * 16 + ((lane & 15) >> 1)) * RP + 16 * ((lane >> 4) & 1) + 8 * (lane & 1);
+    auto read_res = [&](int par, v2i (&rw)[NCB][2]) __attribute__((always_inline)) {
+        const int8_t* t = res_w + par * RT + rr_base;
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                rw[cb][h] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(t + 8 * h * RP + 32 * cb));
+    };
+
+    RS_STAMP(24);
+    {
+        const Cursor c0 = cursor(P.x, P.ldx, 0, 0), c1 = cursor(P.x, P.ldx, 1, 0);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            issue_act_one(uniform_ptr(c0.p), (int)min<int64_t>(c0.rows, SR), xs_off, i);
+            issue_act_one(uniform_ptr(c1.p), (int)min<int64_t>(c1.rows, SR), xs_off + XT, i);
+        }
+        if (EPI == EPI_RESIDUAL) {
+            const Cursor r0 = cursor(P.residual, N, 0, 32 * grp);
+#pragma unroll
+            for (int i = 0; i < RNI; ++i)
+                issue_res_one(uniform_ptr(r0.rows > 0 ? r0.p : res_last), (int)max<int64_t>(1, min<int64_t>(r0.rows, 32)), res_off, i);
+        }
+    }
+
+    // ---- requantisation constants (while the first activations are on their way).  With v = dot + bias the int8 result
+    // clamp8((v b + 2^(c-1)) >> c) is the same for all v >= Lp (127) and all v <= Ln (-127), Lp / Ln being the first v
+    // that reach +-127; so the dot product is limited to [Ln - bias, Lp - bias] first (one median of three), after
+    // which T = v b + 2^(c-1) lies in (-128 2^c, 128 2^c), T 2^(24-c) fits 32 bits and its top byte is the result: one
+    // 24-bit multiply-add by b 2^(24-c), the addend (modulo 2^32) carrying bias and rounding.  Needs c <= 24,
+    // b < 2^(c-1) and bounds within 24 bits.  Residual layers: the first term only has to be exact within
+    // +-(127 + R2), R2 the largest magnitude of the residual term (<= 128 required), because beyond that the clamped
+    // sum is +-127 whatever is added; it then needs nine bits and is kept one bit lower.  A workgroup with a channel
+    // outside these conditions takes the general 64-bit form for all of its channels.
+    int32_t c_lo[NCB], c_hi[NCB], c_mb[NCB], c_ad[NCB];
+    bool chan_24 = true;
+    int64_t wlim = 127;
+    int sh24 = 24;
+    if (EPI == EPI_RESIDUAL) {
+        const int64_t br = P.res_rq.b, cr = P.res_rq.c;
+        bool res_ok = br >= 1 && br < (1 << 23) && cr >= 1 && cr <= 30;
+        if (res_ok) {
+            const int64_t hr = (int64_t)1 << (cr - 1);
+            const int64_t r2 = max((127 * br + hr) >> cr, -((-128 * br + hr) >> cr));
+            res_ok = r2 <= 128;
+            wlim = 127 + r2;
+        }
+        sh24 = 23;
+        chan_24 = res_ok;
+    }
+#pragma unroll
+    for (int cb = 0; cb < NCB; ++cb) {
+        int32_t lo = 0, hi = 0, mb = 0, ad = 0;
+        bool ok = chan_24 && pc[cb] >= 1 && pc[cb] <= sh24 && pb[cb] >= 1 && pb[cb] < (1 << ((pc[cb] - 1) & 31));
+        if (ok) {
+            const int64_t half = (int64_t)1 << (pc[cb] - 1), two_c = (int64_t)1 << pc[cb];
+            const int64_t Lp = (wlim * two_c - half + pb[cb] - 1) / pb[cb];
+            const int64_t Ln = -((wlim * two_c - half + 1 + pb[cb] - 1) / pb[cb]);
+            const int64_t l = Ln - pbias[cb], h = Lp - pbias[cb];
+            ok = l >= -(1 << 23) && h < (1 << 23);
+            lo = (int32_t)l; hi = (int32_t)h; mb = pb[cb] << (sh24 - pc[cb]);
+            ad = (int32_t)(uint32_t)((uint64_t)((int64_t)pbias[cb] * pb[cb] + half) << (sh24 - pc[cb]));
+        }
+        chan_24 = chan_24 && ok;
+        c_lo[cb] = lo; c_hi[cb] = hi; c_mb[cb] = mb; c_ad[cb] = ad;
+    }
+    if (EPI == EPI_GELU && tid < 256) {
+        const int32_t I = (int32_t)(int8_t)tid;
+        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
+    }
+    RS_STAMP(1);
+    wait_vm0();
+    const bool fast24 = __syncthreads_and(chan_24) != 0;
+    RS_STAMP(2);        // also: tiles 0 and 1 (and residual tile 0) are in LDS
+    if (!fast24) {                                              // the general form keeps the raw parameters instead
+#pragma unroll
+        for (int cb = 0; cb < NCB; ++cb) { c_lo[cb] = pb[cb]; c_hi[cb] = pc[cb]; c_mb[cb] = pbias[cb]; c_ad[cb] = 0; }
+    }
+
+    // ---- output: a lane's 16 results of channel tile cb (tokens 16 lg .. 16 lg + 15 of channel lj) are one 16-byte
+    // write into row 32 cb + lj of the staging tile; store instruction s then covers eight half-blocks of 8 tokens x 16
+    // channels, half-block 8 s + 2 B + o = 2 NCB tb + cg being tokens 8 tb .. + 7, channels 16 cg .. + 15: lane
+    // L = 16 B + 8 o + j receives token 8 tb + j (two transposing reads: channels 16 cg + 0..7, + 8..15) and stores 16
+    // bytes of a row of y.
+    int st_src[NCB], st_tok[NCB];
+    uint32_t st_dst[NCB];
+#pragma unroll
+    for (int s = 0; s < NCB; ++s) {
+        const int B = lane >> 4, o_src = lane & 1, b = (lane & 15) >> 1, o_dst = (lane >> 3) & 1, j = lane & 7;
+        const int hs = 8 * s + 2 * B + o_src, hd = 8 * s + 2 * B + o_dst;
+        st_src[s] = (16 * (hs % (2 * NCB)) + b) * OP + 8 * (hs / (2 * NCB));
+        // token of the tile this lane stores; 64 (never below the number of rows left) for channel tiles past the last one
+        st_tok[s] = n0w + 16 * (hd % (2 * NCB)) < N ? 8 * (hd / (2 * NCB)) + j : 64;
+        st_dst[s] = (uint32_t)((8 * (hd / (2 * NCB)) + j) * N + 16 * (hd % (2 * NCB)));
+    }
+    auto store_read = [&](int s, v2i& a, v2i& b) __attribute__((always_inline)) {
+        a = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(out_w + st_src[s]));
+        b = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(out_w + st_src[s] + 8 * OP));
+    };
+    typedef v4i __attribute__((address_space(1))) gv4i;
+    // base: first row of the tile in y, at this wavefront's first channel (scalar); rows: rows of the tile that exist
+    auto store_write = [&](int8_t* base, int rows, int s, const v2i& a, const v2i& b) __attribute__((always_inline)) {
+        if (st_tok[s] < rows) *(gv4i*)(base + st_dst[s]) = v4i{a[0], a[1], b[0], b[1]};
+    };
+
+    const int32_t rb = P.res_rq.b, rc = P.res_rq.c, rh = 1 << ((P.res_rq.c - 1) & 31);
+
+    // one epilogue unit: the four outputs e = 4 d .. 4 d + 3 of channel tile cb -> one packed word
+    auto unit_fast = [&](const v16i& a, int cb, int d, const v2i (&rw)[NCB][2]) __attribute__((always_inline)) -> int {
+        uint32_t o[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int32_t m = med3(a[4 * d + r], c_lo[cb], c_hi[cb]);
+            if (EPI == EPI_RESIDUAL) {
+                const int32_t t1 = (__mul24(m, c_mb[cb]) + c_ad[cb]) >> 23;
+                const int32_t res = (int32_t)(int8_t)((uint32_t)rw[cb][d >> 1][d & 1] >> (8 * r));
+                const int32_t t2 = (__mul24(res, rb) + rh) >> rc;
+                o[r] = (uint32_t)clamp8(t1 + t2);
+            } else {
+                o[r] = (uint32_t)(__mul24(m, c_mb[cb]) + c_ad[cb]);              // result in the top byte
+                if (EPI == EPI_GELU) o[r] = (uint32_t)gelu_lut[o[r] >> 24];        // result in the low byte
+            }
+        }
+        const bool low = EPI != EPI_PLAIN;
+        const uint32_t p01 = __builtin_amdgcn_perm(o[1], o[0], low ? 0x0c0c0400u : 0x0c0c0703u);
+        const uint32_t p23 = __builtin_amdgcn_perm(o[3], o[2], low ? 0x04000c0cu : 0x07030c0cu);
+        return (int)(p01 | p23);
+    };
+    auto unit_general = [&](const v16i& a, int cb, int d, const v2i (&rw)[NCB][2]) __attribute__((always_inline)) -> int {
+        uint32_t o[4];
+        const int32_t b = c_lo[cb], c = c_hi[cb], bias = c_mb[cb];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int64_t r64 = rnd_shift64(a[4 * d + r] + bias, b, c);
+            if (EPI == EPI_RESIDUAL) {
+                const int32_t res = (int32_t)(int8_t)((uint32_t)rw[cb][d >> 1][d & 1] >> (8 * r));
+                r64 += rnd_shift64(res, P.res_rq.b, P.res_rq.c);
+            }
+            int32_t v = clamp8_64(r64);
+            if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
+            o[r] = (uint32_t)v;
+        }
+        const uint32_t p01 = __builtin_amdgcn_perm(o[1], o[0], 0x0c0c0400u);
+        const uint32_t p23 = __builtin_amdgcn_perm(o[3], o[2], 0x04000c0cu);
+        return (int)(p01 | p23);
+    };
+    auto put_out = [&](int cb, const v4i& w4) __attribute__((always_inline)) {
+        *reinterpret_cast<v4i*>(out_w + (32 * cb + lj) * OP + 16 * lg) = w4;
+    };
+
+    // The stage of token tile k is buffer k % 3.  One barrier per tile, before the first fragments of tile k + 1 are
+    // read: wait for this wavefront's loads (all requested most of a tile earlier), barrier (now every wavefront's
+    // loads of stage k + 1 have landed and nobody reads stage k - 1 any more); in the k-steps after it, one piece per
+    // step: the stores of tile k - 1, the requests of stage k + 2 (into the buffer of k - 1) and of residual tile k + 1.
+    const int a_base = (32 * grp + lj) * PITCH + 16 * lg;       // this lane's A fragment of k-step ks: + 32 ks
+    v4i af[RG];
+    {
+        const int8_t* xa = Xs + a_base;
+#pragma unroll
+        for (int i = 0; i < RG - 1; ++i) af[i] = *reinterpret_cast<const v4i*>(xa + 32 * i);
+    }
+
+    v16i accA[NCB], accB[NCB];
+    v2i rw[NCB][2] = {};
+    Cursor c_req, c_res, c_out, c_prev;                         // stage being requested, residual tile being requested, tile k, tile k - 1
+    int par = 0;                                                // residual tile k is in half `par` of the residual staging
+
+    // Token tile k in buffer b0 (b1 holds stage k + 1, b2 is free for stage k + 2): multiply into `cur`.  With one
+    // wavefront per SIMD (GR == 1) there are two sets of accumulators and, when `ep`, `prev` (tile k - 1) is requantised
+    // between the MFMAs, in the k-steps before the barrier, and stored after it.
+    // With two wavefronts per SIMD (GR == 2) there is a single set: tile k is requantised right after its multiply, and
+    // `ep` only says whether tile k - 1 is there to be stored.  The two wavefronts of a SIMD are kept half a period
+    // apart: group 0 (PH == 0) meets the barrier of stage k in the middle of its multiply of tile k, group 1 (PH == 1)
+    // in the middle of its requantisation of tile k, having multiplied all of it already; its multiply of tile k
+    // therefore runs after barrier k - 1 and carries that barrier's follow-up work (requests of stage k + 1).
+    constexpr bool TWO_SETS = GR == 1;
+    auto tile_step = [&]<bool ep, bool fast, int PH>(int b0, int b1, int b2, v16i (&cur)[NCB], const v16i (&prev)[NCB]) __attribute__((always_inline)) {
+        v4i ow[NCB];
+        v2i sa = {}, sb = {};
+        if (EPI == EPI_RESIDUAL && ep && TWO_SETS) read_res(par ^ 1, rw);
+        constexpr int FIRST = PH == 0 ? SYNC : 0;              // k-step of the first piece of the work that follows a barrier
+        const int8_t* xa = Xs + b0 * XT + a_base;
+        const int8_t* xb = Xs + b1 * XT + a_base;
+        // this tile's scalars, pinned in scalar registers (recomputing them at every use would cost more instructions
+        // than the loads and stores themselves)
+        const auto sc = [](int64_t v) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane((int)v); };
+        const int8_t* q_base = uniform_ptr(c_req.p);
+        int q_rows = sc(min<int64_t>(c_req.rows, SR));
+        uint32_t q_dst = (uint32_t)sc(xs_off + (PH == 0 ? b2 : b1) * XT);
+        const int8_t* r_base = EPI == EPI_RESIDUAL ? uniform_ptr(c_res.rows > 0 ? c_res.p : res_last) : nullptr;
+        int r_rows = sc(max<int64_t>(1, min<int64_t>(c_res.rows, 32)));
+        uint32_t r_dst = (uint32_t)sc(res_off + (par ^ 1) * RT);
+        int8_t* y_base = const_cast<int8_t*>(uniform_ptr(c_prev.p + n0w));
+        int y_rows = sc(max<int64_t>(0, min<int64_t>(c_prev.rows, 32)));
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (PH == 0 && ks == SYNC) {
+                wait_vm0();
+                __syncthreads();
+            }
+            // fragment ks + RG - 1: of the next tile once this one runs out (valid since the barrier of this tile)
+            if (ks + RG - 1 < KS) af[(ks + RG - 1) % RG] = *reinterpret_cast<const v4i*>(xa + 32 * (ks + RG - 1));
+            else if (PH == 0) af[(ks + RG - 1) % RG] = *reinterpret_cast<const v4i*>(xb + 32 * (ks + RG - 1 - KS));
+#pragma unroll
+            for (int cb = 0; cb < NCB; ++cb) {
+                if (ks == 0) {
+                    const v16i zero = {};
+                    cur[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[ks % RG], W[cb][ks], zero, 0, 0, 0);
+                } else {
+                    cur[cb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[ks % RG], W[cb][ks], cur[cb], 0, 0, 0);
+                }
+            }
+            // epilogue units of the previous tile, spread over k-steps 1 .. SYNC - 1 (not in step 0: the asm statements
+            // that read the accumulators get no hazard wait states from the compiler, and the last MFMA of the previous
+            // tile has only just been issued there)
+            if (TWO_SETS && ep && ks >= 1 && ks < SYNC) {
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    if (1 + u * (SYNC - 1) / NU != ks) continue;
+                    const int cb = u >> 2, d = u & 3;
+                    ow[cb][d] = fast ? unit_fast(prev[cb], cb, d, rw) : unit_general(prev[cb], cb, d, rw);
+                    if (d == 3) put_out(cb, ow[cb]);
+                }
+            }
+            if (ks >= FIRST) {
+                const int j = ks - FIRST;
+                if (ep && j >= 1 && j <= NCB) store_write(y_base, y_rows, j - 1, sa, sb);
+                if (ep && j < NCB) store_read(j, sa, sb);
+                if (j < NI) issue_act_one(q_base, q_rows, q_dst, j);
+                if (EPI == EPI_RESIDUAL && j < RNI) issue_res_one(r_base, r_rows, r_dst, j);     // past the last tile: a repeat, never used
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (!TWO_SETS) {
+            if (EPI == EPI_RESIDUAL) read_res(par, rw);         // residual tile k landed before barrier k - 1 (PH 1) or k (PH 0)
+            asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");      // the last MFMAs have written the accumulators
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                if (PH == 1 && u == NU / 2) {
+                    wait_vm0();
+                    __syncthreads();
+#pragma unroll
+                    for (int i = 0; i < RG - 1; ++i) af[i] = *reinterpret_cast<const v4i*>(xb + 32 * i);      // first fragments of the next tile
+                }
+                const int cb = u >> 2, d = u & 3;
+                ow[cb][d] = fast ? unit_fast(cur[cb], cb, d, rw) : unit_general(cur[cb], cb, d, rw);
+                if (d == 3) put_out(cb, ow[cb]);
+            }
+        }
+        // on to tile k + 1
+        c_prev = c_out;
+        c_out.p += n_step; c_out.rows -= row_step;
+        advance(c_req, x_step);
+        advance(c_res, n_step);
+        par ^= 1;
+    };
+
+    // the results of the last tile (tile ntile - 1 went into accA when ntile is odd)
+    auto drain = [&]<bool fast>(const v16i (&last)[NCB]) __attribute__((always_inline)) {
+        if (TWO_SETS) {
+            v4i ow[NCB];
+            if (EPI == EPI_RESIDUAL) { wait_vm0(); read_res(par ^ 1, rw); }
+            __builtin_amdgcn_sched_barrier(0);
+            asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");      // the last MFMAs have written the accumulators
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int cb = u >> 2, d = u & 3;
+                ow[cb][d] = fast ? unit_fast(last[cb], cb, d, rw) : unit_general(last[cb], cb, d, rw);
+                if (d == 3) put_out(cb, ow[cb]);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < NCB; ++s) {
+            v2i a, b;
+            store_read(s, a, b);
+            store_write(const_cast<int8_t*>(uniform_ptr(c_prev.p)) + n0w, (int)max<int64_t>(0, min<int64_t>(c_prev.rows, 32)), s, a, b);
+        }
+    };
+    auto start = [&](int ahead) __attribute__((always_inline)) {
+        c_req = cursor(P.x, P.ldx, ahead, 0);
+        c_res = cursor(P.residual, N, 1, 32 * grp);
+        c_out = cursor(P.y, N, 0, 32 * grp);
+        c_prev = c_out;
+        par = 0;
+    };
+    auto run_one_set = [&]<bool fast, int PH>() __attribute__((always_inline)) {
+        start(PH == 0 ? 2 : 1);
+        tile_step.template operator()<false, fast, PH>(0, 1, 2, accA, accA);
+        RS_STAMP(3);
+        int b0 = 1, b1 = 2, b2 = 0;
+        for (int64_t k = 1; k < ntile; ++k) {
+            tile_step.template operator()<true, fast, PH>(b0, b1, b2, accA, accA);
+            RS_STAMP(3 + k);
+            const int t = b0; b0 = b1; b1 = b2; b2 = t;
+        }
+        drain.template operator()<fast>(accA);
+        RS_STAMP(30);
+    };
+    auto run = [&]<bool fast>() __attribute__((always_inline)) {
+        if (!TWO_SETS) {
+            run_one_set.template operator()<fast, 0>();
+            return;
+        }
+        start(2);
+        tile_step.template operator()<false, fast, 0>(0, 1, 2, accA, accB);
+        RS_STAMP(3);
+        int b0 = 1, b1 = 2, b2 = 0;
+        for (int64_t k = 1; k < ntile; k += 2) {
+            tile_step.template operator()<true, fast, 0>(b0, b1, b2, accB, accA);
+            RS_STAMP(3 + k);
+            { const int t = b0; b0 = b1; b1 = b2; b2 = t; }
+            if (k + 1 < ntile) {
+                tile_step.template operator()<true, fast, 0>(b0, b1, b2, accA, accB);
+                RS_STAMP(4 + k);
+                const int t = b0; b0 = b1; b1 = b2; b2 = t;
+            }
+        }
+        if (ntile & 1) drain.template operator()<fast>(accA); else drain.template operator()<fast>(accB);
+        RS_STAMP(30);
+    };
+    if (fast24) run.template operator()<true>(); else run.template operator()<false>();
+    wait_vm0();            // LDS-direct loads still in flight (repeats of the last stage) must land before the LDS is released
+}
+
+template <int EPI, int KS, int NCB, int GR>
+hipError_t launch_rs(hipStream_t s, const RsParams& P, int grid) {
+    constexpr size_t lds_bytes = RsLayout<KS, NCB, EPI, GR>::TOTAL;
+    hipLaunchKernelGGL((gemm_rs_kernel<EPI, KS, NCB, GR>), dim3(grid), dim3(256 * GR), lds_bytes, s, P);
+    return hipGetLastError();
+}
+
+template <int KS, int NCB, int GR>
+hipError_t launch_rs_epi(hipStream_t s, RsParams& P, const LinearArgs& a) {
+    const int nt = a.N / 32;
+    P.slabs = (nt + 4 * NCB - 1) / (4 * NCB);
+    P.stages = (a.M + 32 * GR - 1) / (32 * GR);
+    P.q = (int)std::max<int64_t>(1, std::min<int64_t>(P.stages, num_cus() / P.slabs));
+    const int grid = P.q * P.slabs;
+    if (a.residual) return launch_rs<EPI_RESIDUAL, KS, NCB, GR>(s, P, grid);
+    if (a.gelu) return launch_rs<EPI_GELU, KS, NCB, GR>(s, P, grid);
+    return launch_rs<EPI_PLAIN, KS, NCB, GR>(s, P, grid);
+}
+
+}  // namespace
+
+// Shapes this kernel takes: K = 384 or 768 (the weights of a wavefront must fit its registers, and the k-steps are
+// unrolled), N a multiple of 32, dense rows; offsets inside the weight matrix and inside a token tile are 32-bit.
+bool linear_rs_takes(const LinearArgs& a) {
+    if (a.K != 384 && a.K != 768) return false;
+    if ((int64_t)a.N * a.K > 0x7fffffffLL) return false;
+    return (a.N & 31) == 0 && (a.ldx == 0 || a.ldx == a.K) && a.M >= 1;
+}
+
+#ifdef IVIT_RS_TIMING
+extern "C" int ivit_rs_read_stamps(long long* out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(rs_stamps), sizeof(long long) * 2048 * 32);
+}
+#endif
+
+hipError_t launch_linear_rs(hipStream_t s, const LinearArgs& a) {
+    RsParams P;
+    P.x = a.x; P.w = a.w; P.bias = a.bias; P.rq_b = a.rq_b; P.rq_c = a.rq_c;
+    P.residual = a.residual; P.res_rq = a.res_rq; P.gelu_p = a.gelu_p; P.gelu_rq = a.gelu_rq;
+    P.y = a.y; P.M = a.M; P.N = a.N; P.ldx = a.K;
+    // K = 384: 64 channels per wavefront leave room for two wavefronts per SIMD; K = 768: one
+    if (a.K == 384) return launch_rs_epi<12, 2, 2>(s, P, a);
+    return launch_rs_epi<24, 2, 1>(s, P, a);
+}
+
+}  // namespace ivit

@@ -26,8 +26,13 @@ struct LinearArgs {
     bool gelu; ShiftParams gelu_p; Dyadic gelu_rq;
     int8_t* y; int64_t M; int N; int K;
     int64_t ldx;                         // bytes between rows of x; 0 means K (dense rows)
+    int kernel;                          // 0: chosen from the shape; otherwise one of LinearKernel, forced (tests, measurements)
 };
+enum LinearKernel { LINEAR_AUTO = 0, LINEAR_MANY_ROWS = 1, LINEAR_REG_STATIONARY = 2 };
 hipError_t launch_linear(hipStream_t s, const LinearArgs& a);
+// Register-stationary kernel (gemm_rs.hip): whether it takes this shape at all, and its launch.
+bool linear_rs_takes(const LinearArgs& a);
+hipError_t launch_linear_rs(hipStream_t s, const LinearArgs& a);
 hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos, Dyadic tok_rq,
                                Dyadic pos_rq, int8_t* tokens, int B, int P, int C);
 

@@ -172,14 +172,10 @@ LIN_SHAPES = [(0, 64, 64), (1, 1, 16), (5, 7, 80), (65, 192, 64), (130, 40, 256)
               (3, 16, 65536), (70001, 16, 16)]
 
 
-@pytest.fixture(params=["auto", "large"])
-def dense_path(request, monkeypatch):
-    """Shapes with few rows take a kernel of their own; "large" keeps them on the kernels for many rows (an environment
-    switch the library reads at every call), so that the small test shapes exercise both."""
-    if request.param == "large":
-        monkeypatch.setenv("IVIT_DENSE_PATH", "large")
-    else:
-        monkeypatch.delenv("IVIT_DENSE_PATH", raising=False)
+@pytest.fixture(params=[None, "many_rows"])
+def dense_path(request):
+    """Shapes with few rows take a kernel of their own; "many_rows" (an option of ivit_linear_requant_ex) keeps them on
+    the kernels for many rows, so that the small test shapes exercise both.  None calls ivit_linear_requant itself."""
     return request.param
 
 
@@ -195,7 +191,7 @@ def test_linear_requant(ivit, dense_path, M, N, K, epi):
     elif epi == "gelu":
         kw_o = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)); kw_g = dict(kw_o)
     y = empty((M, N))
-    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, **kw_g)
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, kernel=dense_path, **kw_g)
     assert_same(host(y), orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o), "linear %s" % epi)
 
 
@@ -215,7 +211,7 @@ def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit, dense_path):
     for kw_o, kw_g in (({}, {}), (dict(residual=res, res_rq=(2 ** 31 - 1, 31)), dict(residual=dev(res), res_rq=(2 ** 31 - 1, 31))),
                        (dict(residual=res, res_rq=(3, 1)), dict(residual=dev(res), res_rq=(3, 1))), (gl, gl)):
         y = empty((M, N))
-        ivit.ivit_linear_requant(dev(x), dev(w), None, dev(rq_b), dev(rq_c), y, **kw_g)
+        ivit.ivit_linear_requant(dev(x), dev(w), None, dev(rq_b), dev(rq_c), y, kernel=dense_path, **kw_g)
         want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
         assert_same(host(y), want, "linear general")
         assert np.abs(want.astype(np.int32)).mean() > 2
@@ -232,19 +228,22 @@ def test_linear_requant_largest_accumulators(ivit, dense_path):
     rq_b = np.full(N, 3, np.int32); rq_b[8:16] = 200; rq_b[16:24] = 2 ** 17 + 1; rq_b[24:] = 1
     for kw_o, kw_g in (({}, {}), (dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)),) * 2):
         y = empty((M, N))
-        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, **kw_g)
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, kernel=dense_path, **kw_g)
         want = orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o)
         assert_same(host(y), want, "linear with the largest accumulators")
     plain = orc.linear_requant(x, w, bias, rq_b, rq_c)
     assert (np.abs(plain) == 127).any() and (np.abs(plain) < 127).mean() > 0.3
 
 
-@pytest.mark.parametrize("K", [128, 1536])
+@pytest.mark.parametrize("K", [128, 1536, 384, 768])
 def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K):
     """Per-channel parameters at and around the limits of the 24-bit requantisation (shift 1..24, multiplier just
     below and at 2^(c-1), biases that push the clamp bounds to and past 24 bits), on operands that drive the
     accumulators to both saturated ends (K * 127^2 exceeds 2^23 for the larger K) and through the whole range.
-    Slabs of 64 channels share one regime each, so both the narrow path and its fallbacks run."""
+    Slabs of 64 channels share one regime each, so both the narrow path and its fallbacks run.  K = 384 and 768 are
+    run on the kernel that keeps the weights in registers as well (its workgroups span 384 or 256 channels)."""
+    if K in (384, 768) and dense_path == "many_rows":
+        dense_path = "reg_stationary"
     rng = np.random.default_rng(K)
     M, N = 333, 64 * 10
     x = synth.make_rows(K, M, K, "uniform")
@@ -277,7 +276,7 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
     gl = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21))
     for kw in ({}, gl):
         y = empty((M, N))
-        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, **kw)
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, kernel=dense_path, **kw)
         want = orc.linear_requant(x, w, bias, b, c, **kw)
         assert_same(host(y), want, "linear at the limits of the narrow path" + (" + gelu" if kw else ""))
     plain = orc.linear_requant(x, w, bias, b, c)
@@ -289,9 +288,63 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
     for rq in ((2 ** 15, 15), (2 ** 15 - 1, 15), (2 ** 15 + 1, 15), (33000, 15), (2 ** 23 - 1, 23), (2 ** 23, 23),
                (2 ** 23 - 1, 30), (5, 31), (1, 1), (3, 2), (23456, 15)):
         y = empty((M, N))
-        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, residual=dev(res), res_rq=rq)
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, residual=dev(res), res_rq=rq, kernel=dense_path)
         want = orc.linear_requant(x, w, bias, b, c, residual=res, res_rq=rq)
         assert_same(host(y), want, "linear + residual at the limits of the narrow path, residual pair %s" % (rq,))
+
+
+# the kernel that keeps the weights in registers (K = 384 / 768): row counts around the 32-token tiles and around the
+# number of workgroups, channel counts that fill, underfill and overfill the workgroups' slabs (384 channels at
+# K = 384, 256 at K = 768), every epilogue; forced through the option so that small row counts reach it too
+RS_SHAPES = [(1, 32, 384), (31, 384, 384), (32, 96, 384), (33, 1152, 384), (197, 384, 384), (1000, 1536, 384), (2500, 416, 384),
+             (8203, 384, 384), (9000, 1152, 384), (64, 768, 768), (333, 256, 768), (1577, 2304, 768), (300, 3072, 768),
+             (8300, 768, 768), (95, 160, 768)]
+
+
+@pytest.mark.parametrize("M,N,K", RS_SHAPES)
+@pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
+def test_linear_requant_weights_in_registers(ivit, M, N, K, epi):
+    x = synth.make_rows(M + N + K, M, K, "normal", 32.0)
+    x[0, :7] = -128                                    # the ABI takes any int8
+    w, bias, rq_b, rq_c = synth.make_linear(M * 7 + N, N, K)
+    w[0, :5] = -128
+    kw_o, kw_g = {}, {}
+    if epi == "residual":
+        res = synth.make_rows(N + 1, M, N, "uniform")
+        res[-1, ::3] = -128
+        kw_o = dict(residual=res, res_rq=(23456, 15)); kw_g = dict(residual=dev(res), res_rq=(23456, 15))
+    elif epi == "gelu":
+        kw_o = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)); kw_g = dict(kw_o)
+    y = empty((M, N))
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, kernel="reg_stationary", **kw_g)
+    assert_same(host(y), orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o), "linear (weights in registers) %s" % epi)
+
+
+def test_linear_requant_weights_in_registers_general_pairs_and_refusals(ivit):
+    """Pairs outside the 24-bit form (shifts up to 46, 31-bit multipliers, no bias) on the kernel that keeps the weights
+    in registers: a workgroup with such a channel takes the 64-bit form for all of its channels.  Shapes the kernel
+    does not take are refused."""
+    rng = np.random.default_rng(7)
+    M, N, K = 700, 448, 384
+    x = synth.make_rows(1, M, K, "uniform")
+    w = synth.make_rows(2, N, K, "uniform")
+    rq_c = rng.integers(1, 47, size=N).astype(np.int32)
+    rq_b = np.array([int(rng.integers(2 ** max(0, min(29, c - 13)), 2 ** max(1, min(31, c - 11)))) for c in rq_c], np.int32)
+    rq_b[:8] = 2 ** 31 - 1; rq_c[:8] = 46
+    res = synth.make_rows(3, M, N, "uniform")
+    gl = dict(gelu=synth.shift_params(20), gelu_rq=(2 ** 31 - 1, 38))
+    for kw_o, kw_g in (({}, {}), (dict(residual=res, res_rq=(2 ** 31 - 1, 31)), dict(residual=dev(res), res_rq=(2 ** 31 - 1, 31))),
+                       (dict(residual=res, res_rq=(3, 1)), dict(residual=dev(res), res_rq=(3, 1))), (gl, gl)):
+        y = empty((M, N))
+        ivit.ivit_linear_requant(dev(x), dev(w), None, dev(rq_b), dev(rq_c), y, kernel="reg_stationary", **kw_g)
+        want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
+        assert_same(host(y), want, "linear general (weights in registers)")
+        assert np.abs(want.astype(np.int32)).mean() > 2
+    for Mb, Nb, Kb in ((64, 64, 128), (64, 48, 384), (64, 1000, 768)):
+        with pytest.raises(ivit.IvitError) as err:
+            ivit.ivit_linear_requant(empty((Mb, Kb)), empty((Nb, Kb)), None, dev(rq_b[:1].repeat(Nb)), dev(rq_c[:1].repeat(Nb)),
+                                     empty((Mb, Nb)), kernel="reg_stationary")
+        assert err.value.status == ivit.IVIT_ERR_SHAPE
 
 
 # ------------------------------------------------------------------ fused attention

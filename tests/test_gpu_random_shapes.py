@@ -58,14 +58,10 @@ def _dense_params(rng, N, K, regime):
     return b.astype(np.int32), c.astype(np.int32), bias.astype(np.int32)
 
 
-@pytest.fixture(params=["auto", "large"])
-def dense_path(request, monkeypatch):
-    """Few-row shapes have a kernel of their own; "large" (an environment switch read at every call) keeps them on the
+@pytest.fixture(params=[None, "many_rows"])
+def dense_path(request):
+    """Few-row shapes have a kernel of their own; "many_rows" (an option of ivit_linear_requant_ex) keeps them on the
     kernels for many rows, so both see the random shapes."""
-    if request.param == "large":
-        monkeypatch.setenv("IVIT_DENSE_PATH", "large")
-    else:
-        monkeypatch.delenv("IVIT_DENSE_PATH", raising=False)
     return request.param
 
 
@@ -74,7 +70,11 @@ def test_linear_random(ivit, dense_path, seed):
     seed += SEED_OFFSET
     rng = np.random.default_rng(1000 + seed)
     K = 16 * int(rng.choice([1, 2, 3, 5, 6, 8, 12, 16, 24, 25, 48, 96, 100, 192]))
+    if seed % 6 == 5 and dense_path == "many_rows":      # a sixth of the draws: the kernel with the weights in registers
+        K, dense_path = int(rng.choice([384, 768])), "reg_stationary"
     N = int(rng.choice([16, 48, 64, 80, 128, 144, 256, 400, 1000, 7, 33])) if seed % 3 else 16 * int(rng.integers(1, 60))
+    if dense_path == "reg_stationary":
+        N = 32 * int(rng.integers(1, 40))
     M = int(rng.choice([1, 31, 32, 33, 255, 700, 2049, 5000]))
     M = max(1, min(M, int(4e8 / (N * K))))                   # keeps the oracle's triple loop under a second
     regime = ("narrow", "fits32", "general")[seed % 3] if seed % 4 else "narrow"
@@ -92,7 +92,7 @@ def test_linear_random(ivit, dense_path, seed):
         i0 = int(rng.choice([4, 11, 32, 64, 200]))
         kw_o = dict(gelu=synth.shift_params(i0), gelu_rq=(int(rng.integers(2 ** 14, 2 ** 15)), int(rng.integers(19, 23)))); kw_g = dict(kw_o)
     y = empty((M, N))
-    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias) if use_bias else None, dev(b), dev(c), y, **kw_g)
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias) if use_bias else None, dev(b), dev(c), y, kernel=dense_path, **kw_g)
     want = orc.linear_requant(x, w, bias if use_bias else None, b, c, **kw_o)
     same(host(y), want, "linear M=%d N=%d K=%d %s %s" % (M, N, K, regime, epi))
 
@@ -171,7 +171,7 @@ def test_rowwise_random(ivit, seed):
 
 
 @pytest.mark.parametrize("seed", range(8))
-def test_block_random(ivit, dense_path, seed):
+def test_block_random(ivit, seed):
     seed += SEED_OFFSET
     """Whole blocks on random widths, with every intermediate tensor."""
     import torch
