@@ -185,10 +185,18 @@ int ivit_shiftgelu_rowmax(void* stream, const int8_t* x, int8_t* y, int64_t rows
  * Requirements: rows >= 0, 4 <= C <= 2048, C % 4 == 0, 1 <= f_bits <= 20, 1 <= c_shift <= 31,
  * x and y 4-byte aligned; |gamma_q| < 2^15 and |(x - mean) * f * gamma_q + beta_q| < 2^31 - 2^(c_shift-1)
  * (a precondition on device data: the two products are taken with 24-bit factors; outside it the values are
- * unspecified, nothing faults).
+ * unspecified, nothing faults; ivit_ilayernorm_limits gives parameter bounds that satisfy it for every row).
  * Errors: NULL, SHAPE, PARAM, ALIGN, HIP. */
 int ivit_ilayernorm(void* stream, const int8_t* x, const int32_t* gamma_q, const int32_t* beta_q,
                     int8_t* y, int64_t rows, int32_t C, int32_t f_bits, int32_t c_shift);
+
+/* Host helper for the precondition of ivit_ilayernorm: bounds on the device parameters under which its 32-bit
+ * arithmetic is exact for EVERY possible row (Sec. 3.5 normalises by an integer standard deviation, so
+ * |x - mean| * f never exceeds 2 sqrt(C) 2^f_bits).  With |gamma_q| <= *gamma_max and |beta_q| <= *beta_max
+ * (2^30, one less at c_shift = 31) no row can overflow; parameters beyond these bounds may still be fine for the rows
+ * actually seen (the bound is reached only by rows that are constant but for a few spikes).  *gamma_max == 0 means that no gamma is safe for all rows.
+ * Errors: SHAPE, PARAM (as ivit_ilayernorm), NULL. */
+int ivit_ilayernorm_limits(int32_t C, int32_t f_bits, int32_t c_shift, int32_t* gamma_max, int32_t* beta_max);
 
 /* Bytes of workspace ivit_encoder_block / ivit_forward need for these dimensions
  * (0 if the dimensions are invalid). */
@@ -380,6 +388,17 @@ int ivit_forward_swin(void* stream, const int8_t* patches, int8_t* logits, const
  * Pure host code on HOST pointers; nothing is launched.  They realise Sec. 3.1 Eq. 6 (symmetric uniform
  * quantisation), the dyadic number of Sec. 3.2 and the I_0 of Algorithm 1, with the readings the kernels use
  * (symmetric integer range, round to nearest with ties away from zero on the host). */
+
+/* Measurement helper (no part of the method): launches, on `stream`, a kernel that does nothing but issue
+ * v_mfma_i32_32x32x32_i8 (one wavefront per SIMD on every compute unit, 16 `iters` MFMAs each), with constant operands
+ * or, if random_operands != 0, pseudo-random ones.  *int8_ops receives the integer operations the launch performs
+ * (2 per multiply-accumulate); the caller times the launch with events on the same stream and so gets the rate the
+ * matrix cores sustain, the practical ceiling the Dense kernels (Sec. 3.2) are compared with besides the vendor peak.
+ * After completion the first 8 bytes of scratch hold the shader clock cycles the loop took on one wavefront (int64).
+ * scratch: device memory, 256-byte aligned, at least 256 + 1024 * (number of compute units) bytes.
+ * Errors: NULL, PARAM (iters outside 1 .. 2^24), WORKSPACE, ALIGN, HIP. */
+int ivit_probe_mfma_rate(void* stream, int32_t random_operands, int32_t iters, void* scratch, size_t scratch_bytes,
+                         int64_t* int8_ops);
 
 /* q[i] = clamp(round(r[i] / S), -(2^(k-1) - 1), 2^(k-1) - 1) with S = m / (2^(k-1) - 1) (Eq. 6 with the
  * symmetric range); *scale (nullable) receives S.  n >= 0, m > 0 and finite, 2 <= k <= 8.  NaN inputs give 0.

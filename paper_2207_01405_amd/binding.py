@@ -22,7 +22,7 @@ EXPORTS = ("ivit_strerror", "ivit_build_id", "ivit_linear_requant", "ivit_shiftm
            "ivit_forward_image", "ivit_attention_masked", "ivit_window_attention", "ivit_patch_merge_gather",
            "ivit_mean_pool", "ivit_swin_window_index", "ivit_swin_shift_mask", "ivit_swin_workspace_bytes",
            "ivit_forward_swin", "ivit_shiftgelu_rowmax", "ivit_encoder_block_static", "ivit_linear_requant_ex",
-           "ivit_last_hip_error")
+           "ivit_last_hip_error", "ivit_probe_mfma_rate", "ivit_ilayernorm_limits")
 
 KIND_NAMES = {1: "ilayernorm", 2: "gemm", 3: "gemm_residual", 4: "gemm_gelu", 5: "attention", 6: "shiftmax",
               7: "shiftgelu", 8: "embed_tokens", 9: "patch_merge_gather", 10: "mean_pool"}
@@ -126,6 +126,10 @@ def load():
     lib.ivit_linear_requant_ex.restype = C.c_int
     lib.ivit_linear_requant_ex.argtypes = lib.ivit_linear_requant.argtypes + [C.POINTER(LinearOptions)]
     lib.ivit_last_hip_error.restype = C.c_int; lib.ivit_last_hip_error.argtypes = []
+    lib.ivit_ilayernorm_limits.restype = C.c_int
+    lib.ivit_ilayernorm_limits.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.ivit_probe_mfma_rate.restype = C.c_int
+    lib.ivit_probe_mfma_rate.argtypes = [_P, i32, i32, _P, C.c_size_t, C.POINTER(i64)]
     lib.ivit_shiftmax.restype = C.c_int
     lib.ivit_shiftmax.argtypes = [_P, _P, _P, i32, i32, _P, i64, i32, i32, ShiftParams]
     lib.ivit_shiftgelu.restype = C.c_int; lib.ivit_shiftgelu.argtypes = [_P, _P, _P, i64, ShiftParams, Dyadic]
@@ -188,6 +192,21 @@ def ivit_trace_end(capacity):
     _check(load().ivit_trace_end(ms, kind, ops, nbytes, capacity, C.byref(count)), "ivit_trace_end")
     n = min(capacity, count.value)
     return [(ms[i], kind[i], ops[i], nbytes[i]) for i in range(n)]
+
+
+def ivit_probe_mfma_rate(random_operands, iters, scratch, stream=None):
+    """Launches the MFMA-only loop; returns the integer operations of the launch (time it with events on the stream)."""
+    ops = C.c_int64(0)
+    _check(load().ivit_probe_mfma_rate(_stream(stream), int(bool(random_operands)), int(iters), _ptr(scratch),
+                                       scratch.numel() * scratch.element_size(), C.byref(ops)), "ivit_probe_mfma_rate")
+    return ops.value
+
+
+def ivit_ilayernorm_limits(Cc, f_bits, c_shift):
+    """Host helper: (gamma_max, beta_max) under which ivit_ilayernorm is exact for every possible row."""
+    g, b = C.c_int32(0), C.c_int32(0)
+    _check(load().ivit_ilayernorm_limits(int(Cc), int(f_bits), int(c_shift), C.byref(g), C.byref(b)), "ivit_ilayernorm_limits")
+    return g.value, b.value
 
 
 def ivit_quantize_symmetric(r, m, k=8):
@@ -380,7 +399,8 @@ def ivit_encoder_block_static(x, y, p, d, taps=None, stream=None):
 
 
 def ivit_forward(x, y, blocks, d, workspace, final_ln=None, stream=None):
-    arr = (BlockParams * max(1, len(blocks)))(*[block_params(p) for p in blocks])
+    # a ctypes array of BlockParams is taken as it is (marshalled once by the caller, e.g. outside a timed loop)
+    arr = blocks if isinstance(blocks, C.Array) else (BlockParams * max(1, len(blocks)))(*[block_params(p) for p in blocks])
     fl = None
     if final_ln is not None:
         fl = C.byref(FinalLN(_ptr(final_ln["gamma"]), _ptr(final_ln["beta"]), int(final_ln["f_bits"]),
@@ -420,7 +440,8 @@ def image_params(p):
 
 
 def ivit_forward_image(patches, logits, image, blocks, d, workspace, final_ln, stream=None):
-    arr = (BlockParams * max(1, len(blocks)))(*[block_params(p) for p in blocks])
+    # a ctypes array of BlockParams is taken as it is (marshalled once by the caller, e.g. outside a timed loop)
+    arr = blocks if isinstance(blocks, C.Array) else (BlockParams * max(1, len(blocks)))(*[block_params(p) for p in blocks])
     fl = FinalLN(_ptr(final_ln["gamma"]), _ptr(final_ln["beta"]), int(final_ln["f_bits"]), int(final_ln["c_shift"]))
     ip = image if isinstance(image, ImageParams) else image_params(image)
     st = load().ivit_forward_image(_stream(stream), _ptr(patches), _ptr(logits), C.byref(ip), arr, len(blocks), C.byref(fl),

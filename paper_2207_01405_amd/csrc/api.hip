@@ -423,13 +423,28 @@ size_t ivit_image_workspace_bytes(const ivit_dims* d) {
 int ivit_forward_image(void* stream, const int8_t* patches, int8_t* logits, const ivit_image_params* ip,
                        const ivit_block_params* blocks, int32_t n_blocks, const ivit_final_ln* final_ln,
                        const ivit_dims* d, void* workspace, size_t workspace_bytes) {
-    if (!ip || !d || !final_ln) return IVIT_ERR_NULL;
+    // everything that can be checked on the host is checked before the first launch: a failed call launches nothing
+    if (!ip || !d || !final_ln || (n_blocks > 0 && !blocks)) return IVIT_ERR_NULL;
+    if (n_blocks < 0) return IVIT_ERR_SHAPE;
     int st;
     if ((st = check_dims(d)) != IVIT_OK) return st;
-    if (ip->patch_dim < 16 || (ip->patch_dim & 15) || ip->n_classes < 1) return IVIT_ERR_SHAPE;
+    if (ip->patch_dim < 16 || ip->patch_dim > 65536 || (ip->patch_dim & 15) || ip->n_classes < 1) return IVIT_ERR_SHAPE;
     if (d->B > 0 && (!patches || !logits)) return IVIT_ERR_NULL;
+    if (!ip->w_patch || !ip->patch_rq_b || !ip->patch_rq_c || !ip->w_head || !ip->head_rq_b || !ip->head_rq_c) return IVIT_ERR_NULL;
+    if (d->B > 0 && (!ip->cls || !ip->pos)) return IVIT_ERR_NULL;
+    if ((st = check_dyadic(ip->tok_rq)) != IVIT_OK || (st = check_dyadic(ip->pos_rq)) != IVIT_OK) return st;
+    for (int l = 0; l < n_blocks; ++l)
+        if ((st = check_block(&blocks[l], d)) != IVIT_OK) return st;
+    if (!final_ln->gamma || !final_ln->beta) return IVIT_ERR_NULL;
+    if ((st = check_ln(d->C, final_ln->f_bits, final_ln->c_shift)) != IVIT_OK) return st;
     if (!workspace || workspace_bytes < ivit_image_workspace_bytes(d)) return IVIT_ERR_WORKSPACE;
-    if (!aligned(workspace, 256)) return IVIT_ERR_ALIGN;
+    if (!aligned(workspace, 256) || !aligned(patches, 16) || !aligned(logits, 16) || !aligned(ip->w_patch, 16) ||
+        !aligned(ip->cls, 16) || !aligned(ip->pos, 16) || !aligned(ip->w_head, 16))
+        return IVIT_ERR_ALIGN;
+    const void* i32s[] = {ip->bias_patch, ip->patch_rq_b, ip->patch_rq_c, ip->bias_head, ip->head_rq_b, ip->head_rq_c,
+                          final_ln->gamma, final_ln->beta};
+    for (const void* q : i32s)
+        if (!aligned(q, 4)) return IVIT_ERR_ALIGN;
     const size_t act = ((size_t)d->B * d->T * d->C + 255) / 256 * 256;
     int8_t* base = static_cast<int8_t*>(workspace);
     int8_t* patch_tok = base;
@@ -437,9 +452,10 @@ int ivit_forward_image(void* stream, const int8_t* patches, int8_t* logits, cons
     int8_t* tok_out = base + 2 * act;
     void* inner = base + 3 * act;
     const int P = d->T - 1;
-    st = ivit_linear_requant(stream, patches, ip->w_patch, ip->bias_patch, ip->patch_rq_b, ip->patch_rq_c, nullptr,
-                             ivit_dyadic{1, 1}, nullptr, ivit_dyadic{1, 1}, patch_tok, (int64_t)d->B * P, d->C, ip->patch_dim);
-    if (st != IVIT_OK && !(P == 0 && st == IVIT_ERR_SHAPE)) return st;
+    if (P > 0 && (st = ivit_linear_requant(stream, patches, ip->w_patch, ip->bias_patch, ip->patch_rq_b, ip->patch_rq_c, nullptr,
+                                           ivit_dyadic{1, 1}, nullptr, ivit_dyadic{1, 1}, patch_tok, (int64_t)d->B * P, d->C,
+                                           ip->patch_dim)) != IVIT_OK)
+        return st;
     if ((st = ivit_embed_tokens(stream, patch_tok, ip->cls, ip->pos, ip->tok_rq, ip->pos_rq, tok_in, d->B, P, d->C)) != IVIT_OK) return st;
     if ((st = ivit_forward(stream, tok_in, tok_out, blocks, n_blocks, final_ln, d, inner, workspace_bytes - 3 * act)) != IVIT_OK) return st;
     return ivit_classifier_head(stream, tok_out, d->T, ip->w_head, ip->bias_head, ip->head_rq_b, ip->head_rq_c, logits,

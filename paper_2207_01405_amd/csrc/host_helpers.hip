@@ -1,5 +1,6 @@
 // Host-side helpers of the C ABI: float parameters of a quantised model -> integers (I-ViT, arXiv 2207.01405:
 // Sec. 3.1 Eq. 6, the dyadic number of Sec. 3.2, I_0 of Algorithm 1).  No device code in this file.
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
 
@@ -97,6 +98,26 @@ int ivit_swin_shift_mask(int32_t g, int32_t window, int32_t shift, int8_t* mask)
                     m[i * T + j] = (band(yi) != band(yj) || band(xi) != band(xj)) ? 1 : 0;
                 }
         }
+    return IVIT_OK;
+}
+
+int ivit_ilayernorm_limits(int32_t C, int32_t f_bits, int32_t c_shift, int32_t* gamma_max, int32_t* beta_max) {
+    if (C < 4 || C > 2048 || (C & 3)) return IVIT_ERR_SHAPE;
+    if (f_bits < 1 || f_bits > 20 || c_shift < 1 || c_shift > 31) return IVIT_ERR_PARAM;
+    if (!gamma_max || !beta_max) return IVIT_ERR_NULL;
+    // |x - mean| f <= 2 sqrt(C) 2^F for every row: sum (x - mean)^2 < C (var + 1), std >= max(1, floor(sqrt(var))),
+    // whose ratio peaks at var = 3, and f <= 2^F / std.  s = ceil(sqrt(4 C)).
+    int64_t s = (int64_t)std::sqrt(4.0 * C);
+    while (s * s < 4LL * C) ++s;
+    while ((s - 1) * (s - 1) >= 4LL * C) --s;
+    const int64_t U = s << f_bits;
+    const int64_t half = 1LL << (c_shift - 1);
+    const int64_t bmax = std::min<int64_t>(1LL << 30, (1LL << 31) - 1 - half);
+    const int64_t room = (1LL << 31) - 1 - bmax - half;
+    int64_t g = room > 0 ? room / U : 0;
+    if (g > (1 << 15) - 1) g = (1 << 15) - 1;              // the first product is a 24-bit multiply: 255 |gamma| < 2^23
+    *gamma_max = (int32_t)g;
+    *beta_max = (int32_t)bmax;
     return IVIT_OK;
 }
 

@@ -49,14 +49,27 @@ __device__ __forceinline__ int32_t floordiv(int32_t a, int32_t b) {
     return q - ((a % b != 0) && (a < 0));
 }
 
-// ShiftExp (Algorithm 1): I <= 0 -> I_exp with (S / 2^N) I_exp ~ exp(S I).  I_b << (N - q) is
-// evaluated as (I_b << N) >> q so that q > N shifts the value out instead of shifting by a negative count.
+// floor(v / x) for 1 <= x and v < 2^22: the quotient from a single-precision reciprocal is off by at most one,
+// which one multiply and two compares repair (the general unsigned division does the same with more steps).  An
+// implementation of integer division, not arithmetic of the method.
+__device__ __forceinline__ uint32_t div_small(uint32_t v, uint32_t x) {
+    uint32_t q = (uint32_t)((float)v * __builtin_amdgcn_rcpf((float)x));
+    const int32_t r = (int32_t)(v - q * x);
+    q += (r >= (int32_t)x);
+    q -= (r < 0);
+    return q;
+}
+
+// ShiftExp (Sec. 3.3, Eq. 13-15, Algorithm 1) of an argument I <= 0: the value E with (S / 2^N) E ~ exp(S I).
+// t = -(I + (I >> 1) - (I >> 4)) >= 0 is the magnitude of I log2(e) in units of S; it splits as t = q I_0 + r with
+// 0 <= r < I_0: q whole powers of two to shift out, and the fraction -r / I_0, whose power of two is taken as
+// 1 - r / (2 I_0), i.e. the integer I_0 - ceil(r / 2).  The left pre-shift N comes first so that q > N shifts the
+// value out instead of asking for a negative shift count.
 __device__ __forceinline__ uint32_t shiftexp(int32_t I, int32_t i0, int32_t n_shift) {
-    int32_t Ip = I + (I >> 1) - (I >> 4);
-    int32_t q = (-Ip) / i0;                   // Ip <= 0: floor(Ip / -i0) = (-Ip) / i0
-    int32_t r = -Ip - q * i0;                 // in [0, i0)
-    int32_t Ib = ((-r) >> 1) + i0;
-    return q > 31 ? 0u : (((uint32_t)Ib << n_shift) >> q);
+    const uint32_t t = (uint32_t)(-(I + (I >> 1) - (I >> 4)));
+    const uint32_t q = t < (1u << 22) ? div_small(t, (uint32_t)i0) : t / (uint32_t)i0;
+    const uint32_t r = t - q * (uint32_t)i0;
+    return q > 31 ? 0u : ((((uint32_t)i0 - ((r + 1) >> 1)) << n_shift) >> q);
 }
 
 // IntDiv (Eq. 16) with the reciprocal floor(2^M / sum) already formed; M <= 31 and e <= sum, so the
@@ -82,35 +95,15 @@ __device__ __forceinline__ uint32_t recip_pow2_small(uint32_t sum, int32_t m_bit
     return q;
 }
 
-// ShiftGELU on one int8 value (Algorithm 2, maximum taken per element as max(I_p, 0)):
-// returns I * I_div, |result| <= 127 * 2^(k_out-1).
+// ShiftGELU on one int8 value (Sec. 3.4, Eq. 17-18, Algorithm 2), the maximum of the algorithm taken per element:
+// x sigmoid(1.702 x) with the sigmoid as a ratio of two exponentials whose arguments are both <= 0.  With
+// t = I + (I >> 1) + (I >> 3) + (I >> 4) (1.702 I in integers) these are min(t, 0) and min(-t, 0); IntDiv (Eq. 16) turns
+// their ratio into k_out - 1 fraction bits.  Returns I * I_div, |result| <= 127 * 2^(k_out-1).
 __device__ __forceinline__ int32_t shiftgelu_raw(int32_t I, ShiftParams p) {
-    int32_t Ip = I + (I >> 1) + (I >> 3) + (I >> 4);
-    int32_t mx = max(Ip, 0);
-    uint32_t e1 = shiftexp(Ip - mx, p.i0, p.n_shift);
-    uint32_t e2 = shiftexp(-mx, p.i0, p.n_shift);
-    uint32_t dv = intdiv_apply(recip_pow2(e1 + e2, p.m_bits), e1, p.m_bits, p.k_out);
-    return I * (int32_t)dv;
-}
-
-// floor(v / x) for 1 <= x and v < 2^22: the quotient from a single-precision reciprocal is off by at most one,
-// which one multiply and two compares repair (the general unsigned division does the same with more steps).
-__device__ __forceinline__ uint32_t div_small(uint32_t v, uint32_t x) {
-    uint32_t q = (uint32_t)((float)v * __builtin_amdgcn_rcpf((float)x));
-    const int32_t r = (int32_t)(v - q * x);
-    q += (r >= (int32_t)x);
-    q -= (r < 0);
-    return q;
-}
-
-// ShiftExp for arguments of small magnitude (|I| < 2^20, as every int8-derived argument is): the same value as
-// shiftexp() with the division by I_0 done through div_small.
-__device__ __forceinline__ uint32_t shiftexp_small(int32_t I, int32_t i0, int32_t n_shift) {
-    const int32_t Ip = I + (I >> 1) - (I >> 4);
-    const int32_t q = (int32_t)div_small((uint32_t)(-Ip), (uint32_t)i0);
-    const int32_t r = -Ip - q * i0;
-    const int32_t Ib = ((-r) >> 1) + i0;
-    return q > 31 ? 0u : (((uint32_t)Ib << n_shift) >> q);
+    const int32_t t = I + (I >> 1) + (I >> 3) + (I >> 4);
+    const uint32_t e_num = shiftexp(min(t, 0), p.i0, p.n_shift);
+    const uint32_t e_one = shiftexp(min(-t, 0), p.i0, p.n_shift);
+    return I * (int32_t)intdiv_apply(recip_pow2(e_num + e_one, p.m_bits), e_num, p.m_bits, p.k_out);
 }
 
 // Low 32 bits of the product of the low 24 bits of a and b, as the one full-rate instruction.  Written out because the

@@ -529,14 +529,14 @@ __global__ __launch_bounds__(256) void shiftgelu_rowmax_kernel(const int8_t* __r
         const bool rebuild = mx != table_mx;
         table_mx = mx;
         const int32_t m = max(ip_of(mx), 0);
-        const uint32_t e2 = shiftexp_small(-m, p.i0, p.n_shift);
+        const uint32_t e2 = shiftexp(-m, p.i0, p.n_shift);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             if (!rebuild) break;
             const int32_t I = (int32_t)(int8_t)(lane + 64 * k);  // the value whose low byte is the table index
             int32_t out = 0;
             if (I <= mx) {
-                const uint32_t e1 = shiftexp_small(ip_of(I) - m, p.i0, p.n_shift);
+                const uint32_t e1 = shiftexp(ip_of(I) - m, p.i0, p.n_shift);
                 const uint32_t sum = e1 + e2;                    // at most 2^31
                 // floor(2^M / sum), M <= 46, through one double-precision division: the quotient is correctly rounded
                 // and, when it is not an integer, lies at least 1 / sum below the next one, which is more than half

@@ -186,6 +186,104 @@ def test_workspace_and_block_validation(lib):
     assert att(empty) == 0 and lib.ivit_workspace_bytes(C.byref(empty)) > 0
 
 
+def test_forward_image_checks_everything_before_the_first_launch(lib):
+    """A bad block, final LayerNorm, workspace or alignment is reported with its own status.  No GPU is present in the
+    host suite, so a call that reached a launch would come back as IVIT_ERR_HIP instead: the status proves that
+    nothing was enqueued before the argument was found."""
+    good = binding.Dims(2, 65, 64, 2, 256)
+    need = lib.ivit_image_workspace_bytes(C.byref(good))
+    assert need > lib.ivit_workspace_bytes(C.byref(good))
+
+    def image(**kw):
+        ip = binding.ImageParams()
+        for name, t in binding.ImageParams._fields_:
+            if t is C.c_void_p:
+                setattr(ip, name, FAKE)
+        ip.patch_dim, ip.n_classes, ip.tok_rq, ip.pos_rq = 48, 10, DY, DY
+        for k, v in kw.items():
+            setattr(ip, k, v)
+        return ip
+
+    fl = binding.FinalLN(FAKE, FAKE, 16, 19)
+
+    def call(ip=None, blocks=None, n=2, fln=fl, ws=0x100000, nbytes=need, dims=good, patches=FAKE):
+        arr = blocks if blocks is not None else (binding.BlockParams * 2)(_fake_block(), _fake_block())
+        return lib.ivit_forward_image(None, patches, FAKE, C.byref(ip or image()), arr, n, C.byref(fln), C.byref(dims), ws, nbytes)
+
+    bad_block = _fake_block(); bad_block.res2_rq = binding.Dyadic(0, 1)
+    assert call(blocks=(binding.BlockParams * 2)(_fake_block(), bad_block)) == E["PARAM"]        # the LAST block is bad
+    null_block = _fake_block(); null_block.w_fc2 = None
+    assert call(blocks=(binding.BlockParams * 2)(null_block, _fake_block())) == E["NULL"]
+    odd_block = _fake_block(); odd_block.qkv_rq_b = FAKE + 2
+    assert call(blocks=(binding.BlockParams * 2)(_fake_block(), odd_block)) == E["ALIGN"]
+    assert call(fln=binding.FinalLN(FAKE, None, 16, 19)) == E["NULL"]
+    assert call(fln=binding.FinalLN(FAKE, FAKE, 21, 19)) == E["PARAM"]
+    assert call(ws=None) == E["WORKSPACE"] and call(nbytes=need - 1) == E["WORKSPACE"]
+    assert call(ws=0x100000 + 64) == E["ALIGN"] and call(patches=FAKE + 8) == E["ALIGN"]
+    assert call(ip=image(cls=None)) == E["NULL"] and call(ip=image(w_head=None)) == E["NULL"]
+    assert call(ip=image(pos=FAKE + 4)) == E["ALIGN"] and call(ip=image(head_rq_c=FAKE + 2)) == E["ALIGN"]
+    assert call(ip=image(patch_dim=40)) == E["SHAPE"] and call(ip=image(n_classes=0)) == E["SHAPE"]
+    assert call(ip=image(tok_rq=binding.Dyadic(0, 3))) == E["PARAM"]
+    assert call(n=-1) == E["SHAPE"] and call(dims=binding.Dims(2, 65, 60, 2, 256)) == E["SHAPE"]
+
+
+def test_linear_options_and_probe_arguments(lib):
+    ex = lambda opt, **kw: lib.ivit_linear_requant_ex(None, FAKE, FAKE, None, FAKE, FAKE, kw.get("res"), DY, None, DY, FAKE,
+                                                      kw.get("M", 8), kw.get("N", 64), kw.get("K", 384),
+                                                      None if opt is None else C.byref(binding.LinearOptions(opt)))
+    assert ex(3) == E["PARAM"] and ex(-1) == E["PARAM"]
+    # the register-stationary kernel takes K = 384 or 768 with N % 32 == 0 and nothing else
+    assert ex(2, K=512) == E["SHAPE"] and ex(2, N=48) == E["SHAPE"] and ex(2, K=1536) == E["SHAPE"]
+    assert ex(2, M=0) == 0 and ex(0, M=0) == 0 and ex(None, M=0) == 0 and ex(1, M=0, K=512) == 0
+    ops = C.c_int64(0)
+    pr = lambda rnd=0, it=100, s=0x100000, n=1 << 20, o=ops: lib.ivit_probe_mfma_rate(None, rnd, it, s, n, C.byref(o) if o is not None else None)
+    assert pr(it=0) == E["PARAM"] and pr(it=(1 << 24) + 1) == E["PARAM"]
+    assert pr(s=None) == E["NULL"] and pr(o=None) == E["NULL"]
+    assert pr(s=0x100000 + 16) == E["ALIGN"]
+
+
+def _ln_extreme(Cn, f_bits):
+    """Largest |x - mean| * f the definition of Eq. 19-20 gives over rows built to maximise it (brute force)."""
+    from oracle import oracle as orc
+    best = 0
+    rows = []
+    for k in range(1, 6):                       # k spikes of height h over a constant floor
+        for h in range(1, 256):
+            for base in (0, -128, 100):
+                r = np.full(Cn, base, np.int64)
+                r[:k] = np.clip(base + h, -128, 127) if base <= 0 else base - h
+                rows.append(r)
+    x = np.stack(rows)
+    s = x.sum(1)
+    mean = (s + Cn // 2) // Cn
+    dev = x - mean[:, None]
+    var = (dev * dev).sum(1) // Cn
+    std = np.maximum(1, orc.isqrt10_vec(var))
+    f = (1 << f_bits) // std
+    return int((np.abs(dev).max(1) * f).max())
+
+
+@pytest.mark.parametrize("Cn", [4, 64, 96, 384, 768, 2048])
+def test_ilayernorm_limits_cover_every_row(lib, Cn):
+    """The bound behind ivit_ilayernorm_limits, |x - mean| f <= 2 sqrt(C) 2^F, checked by brute force over the rows
+    that come closest to it, and the limits themselves: with them the largest value the kernel forms fits 32 bits."""
+    for f_bits, c_shift in ((16, 19), (20, 23), (8, 12), (1, 1), (20, 31)):
+        g, b = binding.ivit_ilayernorm_limits(Cn, f_bits, c_shift)
+        worst = _ln_extreme(Cn, f_bits)
+        bound = int(np.ceil(np.sqrt(4 * Cn))) << f_bits
+        assert worst <= bound, (worst, bound)
+        if f_bits >= 8:
+            assert worst > bound // 2, (worst, bound)                       # and not a slack one
+        assert b == min(1 << 30, 2 ** 31 - 1 - (1 << (c_shift - 1))) and 0 <= g <= 32767
+        assert bound * g + b + (1 << (c_shift - 1)) <= 2 ** 31 - 1
+        if g < 32767:
+            assert bound * (g + 1) + b + (1 << (c_shift - 1)) > 2 ** 31 - 1
+    gm, bm = C.c_int32(), C.c_int32()
+    assert lib.ivit_ilayernorm_limits(66, 16, 19, C.byref(gm), C.byref(bm)) == E["SHAPE"]
+    assert lib.ivit_ilayernorm_limits(64, 21, 19, C.byref(gm), C.byref(bm)) == E["PARAM"]
+    assert lib.ivit_ilayernorm_limits(64, 16, 19, None, C.byref(bm)) == E["NULL"]
+
+
 def test_binding_refuses_to_run_without_the_library(monkeypatch):
     monkeypatch.setattr(binding, "_lib", None)
     monkeypatch.setattr(binding, "LIB_PATH", os.path.join(ROOT, "does_not_exist.so"))

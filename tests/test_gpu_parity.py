@@ -52,11 +52,30 @@ def assert_same(got, want, what):
 def test_ilayernorm(ivit, rows, C, dist):
     rng = np.random.default_rng(rows + C)
     x = synth.make_rows(rows + C, rows, C, dist, 30.0)
+    if rows > 0:
+        x[0, :3] = -128; x[-1, -1] = -128           # the ABI takes any int8, -128 included
     g = np.rint((1.0 + 0.1 * rng.standard_normal(C)) * 256).astype(np.int32)
     b = np.rint(0.1 * rng.standard_normal(C) * 2 ** 24).astype(np.int32)
     y = empty((rows, C))
     ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, 16, 19)
     assert_same(host(y), orc.ilayernorm(x, g, b, 16, 19), "ilayernorm")
+
+
+@pytest.mark.parametrize("rows,C", [(170003, 384), (400007, 96)])
+def test_ilayernorm_many_rows_every_row(ivit, rows, C):
+    """Row counts that reach the kernel instantiations the bandwidth figures are quoted on (8 rows per thread at
+    C = 384, 4 at C = 96).  The input is a 4096-row tile repeated, so the oracle runs on the tile and every row of the
+    output is compared (rows are independent)."""
+    rng = np.random.default_rng(C)
+    tile = synth.make_rows(rows + C, 4096, C, "normal", 30.0)
+    tile[5, :9] = -128; tile[6] = 127; tile[7] = -128; tile[8, ::2] = -128
+    x = np.tile(tile, ((rows + 4095) // 4096, 1))[:rows]
+    g = np.rint((1.0 + 0.1 * rng.standard_normal(C)) * 256).astype(np.int32)
+    b = np.rint(0.1 * rng.standard_normal(C) * 2 ** 24).astype(np.int32)
+    y = empty((rows, C))
+    ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, 16, 19)
+    want = np.tile(orc.ilayernorm(tile, g, b, 16, 19), ((rows + 4095) // 4096, 1))[:rows]
+    assert_same(host(y), want, "ilayernorm on %d rows of %d" % (rows, C))
 
 
 def test_ilayernorm_other_shift_counts_and_spike_rows(ivit):
@@ -70,6 +89,31 @@ def test_ilayernorm_other_shift_counts_and_spike_rows(ivit):
         y = empty((16, C))
         ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, f_bits, c_shift)
         assert_same(host(y), orc.ilayernorm(x, g, b, f_bits, c_shift), "ilayernorm f=%d c=%d" % (f_bits, c_shift))
+
+
+@pytest.mark.parametrize("C,f_bits,c_shift", [(64, 16, 19), (96, 12, 14), (384, 16, 19), (768, 8, 12), (768, 16, 22), (2048, 10, 30)])
+def test_ilayernorm_at_the_largest_admissible_parameters(ivit, C, f_bits, c_shift):
+    """gamma_q and beta_q of magnitude ivit_ilayernorm_limits allows, on the rows that drive |x - mean| f to its
+    bound (constant rows with a few spikes, the variance-3 rows among them) and on ordinary rows: the 32-bit
+    arithmetic of the kernel must still equal the 64-bit arithmetic of the oracle."""
+    gmax, bmax = ivit.ivit_ilayernorm_limits(C, f_bits, c_shift)
+    assert gmax > 0
+    rng = np.random.default_rng(C + f_bits)
+    rows = []
+    for k in (1, 2, 3, 4):
+        for h in range(1, 256, 2):
+            for base in (0, -128, 127):
+                r = np.full(C, base, np.int64)
+                r[rng.choice(C, k, replace=False)] = base + h if base <= 0 else base - h
+                rows.append(np.clip(r, -128, 127))
+    x = np.concatenate([np.stack(rows).astype(np.int8), synth.make_rows(C, 300, C, "normal", 30.0)])
+    for sign in (1, -1):
+        g = np.where(rng.random(C) < 0.5, gmax, -gmax).astype(np.int32)
+        b = np.full(C, sign * bmax, np.int32)
+        g[::7] = rng.integers(-gmax, gmax + 1, len(g[::7]))
+        y = empty(x.shape)
+        ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, f_bits, c_shift)
+        assert_same(host(y), orc.ilayernorm(x, g, b, f_bits, c_shift), "ilayernorm at the limits C=%d" % C)
 
 
 # ------------------------------------------------------------------ Shiftmax
@@ -184,6 +228,8 @@ def dense_path(request):
 def test_linear_requant(ivit, dense_path, M, N, K, epi):
     x = synth.make_rows(M + N + K, M, K, "normal", 32.0)
     w, bias, rq_b, rq_c = synth.make_linear(M * 7 + N, N, K)
+    if M > 0:
+        x[0, :5] = -128; x[-1, -3:] = -128; w[0, :4] = -128; w[-1, -1] = -128        # the ABI takes any int8
     kw_o, kw_g = {}, {}
     if epi == "residual":
         res = synth.make_rows(N + 1, M, N, "uniform")
@@ -359,6 +405,7 @@ def test_attention(ivit, name, B, over):
     d = synth.dims_of(cfg, B)
     blk = synth.make_block(cfg, 0)
     qkv = synth.make_rows(B + cfg["T"], B * cfg["T"], 3 * cfg["C"], "normal", 32.0)
+    qkv[0, :6] = -128; qkv[0, cfg["C"]:cfg["C"] + 6] = -128; qkv[-1, -6:] = -128; qkv[::7, 2 * cfg["C"] + 1] = -128   # -128 in Q, K and V
     o = empty((B * cfg["T"], cfg["C"]))
     sc = empty((B, cfg["H"], cfg["T"], cfg["T"])); pr = empty((B, cfg["H"], cfg["T"], cfg["T"]))
     rb = None if blk["rel_bias"] is None else dev(blk["rel_bias"])
