@@ -134,9 +134,15 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
  *           IVIT_KERNEL_MANY_ROWS       never the kernel written for few rows;
  *           IVIT_KERNEL_REG_STATIONARY  the kernel that keeps the weights in registers; it takes K = 384 or 768
  *                                       with N % 32 == 0 only, other shapes give IVIT_ERR_SHAPE.
+ *   rounding  how every dyadic requantisation of the layer (Sec. 3.2, Eq. 8-10: the output's, the residual's, the
+ *           one after ShiftGELU) turns b v / 2^c into an integer:
+ *           IVIT_ROUND_NEAREST          (b v + 2^(c-1)) >> c, the rounding Eq. 8 asks for carried into Eq. 10 (what
+ *                                       every entry point without options does);
+ *           IVIT_ROUND_FLOOR            (b v) >> c, Eq. 10 exactly as printed, a bare arithmetic shift.
  * Errors: as ivit_linear_requant; PARAM for an unknown option value. */
 enum { IVIT_KERNEL_AUTO = 0, IVIT_KERNEL_MANY_ROWS = 1, IVIT_KERNEL_REG_STATIONARY = 2 };
-typedef struct { int32_t kernel; } ivit_linear_options;
+enum { IVIT_ROUND_NEAREST = 0, IVIT_ROUND_FLOOR = 1 };
+typedef struct { int32_t kernel; int32_t rounding; } ivit_linear_options;
 int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias,
                            const int32_t* rq_b, const int32_t* rq_c,
                            const int8_t* residual, ivit_dyadic res_rq,
@@ -263,6 +269,17 @@ int ivit_attention_masked(void* stream, const int8_t* qkv, const int8_t* rel_bia
 int ivit_window_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
                           const int32_t* tok_index, int32_t n_win, int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq,
                           ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs);
+
+/* ivit_window_attention with options (opt == NULL: exactly ivit_window_attention).
+ *   rounding  IVIT_ROUND_NEAREST or IVIT_ROUND_FLOOR, as in ivit_linear_options, for the two dyadic requantisations
+ *             of the layer (Sec. 3.2, Eq. 8-10 applied to Eq. 3-4): the scores Q K^T before Shiftmax and the output
+ *             P V.  Shiftmax itself (Algorithm 1) has no rounding step and is the same in both modes.
+ * Errors: as ivit_window_attention; PARAM for an unknown option value. */
+typedef struct { int32_t rounding; } ivit_attention_options;
+int ivit_window_attention_ex(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
+                             const int32_t* tok_index, int32_t n_win, int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq,
+                             ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs,
+                             const ivit_attention_options* opt);
 
 /* Per-launch timing for benchmarks.  Between ivit_trace_begin and ivit_trace_end every kernel launch the
  * library makes (from any entry point, on any stream) is bracketed by two HIP events recorded on the stream

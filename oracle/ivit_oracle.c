@@ -55,6 +55,16 @@ int64_t orc_requant(int64_t v, int32_t b, int32_t c) {
     return orc_clamp_k(orc_rnd_shift((int64_t)b * v, c), 8);
 }
 
+/* The other reading of Eq. 10, kept as a selectable mode: the equation is printed as a bare shift,
+ * I_out = (I_in * b) >> c, which is floor(b v / 2^c) with no rounding term.  floor_shift != 0 takes that; 0 is the
+ * rounded form above.  Used by the *_mode entry points of the Dense layer and of attention. */
+static int64_t shift_mode(int64_t v, int32_t c, int32_t floor_shift) {
+    return floor_shift ? (v >> c) : orc_rnd_shift(v, c);
+}
+static int64_t requant_mode(int64_t v, int32_t b, int32_t c, int32_t floor_shift) {
+    return orc_clamp_k(shift_mode((int64_t)b * v, c, floor_shift), 8);
+}
+
 /* ShiftExp (Algorithm 1; Eq. 13-15) for I <= 0, with I_0 = round(1/S) given by
  * the caller and N the left pre-shift of the algorithm's footnote.  Returns
  * I_exp with S/2^N * I_exp ~ exp(S*I).  The printed "I_b << (N-q)" is read as
@@ -213,11 +223,11 @@ void orc_ilayernorm(const int8_t* x, const int32_t* gamma_q, const int32_t* beta
  *    y = clamp_8(rnd_shift(b_j acc_j, c_j) + rnd_shift(b_r res, c_r)).
  *  - gelu != NULL: the int8 result goes through ShiftGELU and the dyadic
  *    requantisation of its output (Eq. 5: GELU sits between the two MLP layers). */
-void orc_linear_requant(const int8_t* x, const int8_t* w, const int32_t* bias,
-                        const int32_t* rq_b, const int32_t* rq_c,
-                        const int8_t* residual, orc_dyadic res_rq,
-                        const orc_shift_params* gelu, orc_dyadic gelu_rq,
-                        int8_t* y, int64_t M, int32_t N, int32_t K) {
+void orc_linear_requant_mode(const int8_t* x, const int8_t* w, const int32_t* bias,
+                             const int32_t* rq_b, const int32_t* rq_c,
+                             const int8_t* residual, orc_dyadic res_rq,
+                             const orc_shift_params* gelu, orc_dyadic gelu_rq,
+                             int8_t* y, int64_t M, int32_t N, int32_t K, int32_t floor_shift) {
     for (int64_t m = 0; m < M; ++m) {
         const int8_t* xr = x + m * (int64_t)K;
         for (int32_t j = 0; j < N; ++j) {
@@ -226,16 +236,24 @@ void orc_linear_requant(const int8_t* x, const int8_t* w, const int32_t* bias,
             for (int32_t k = 0; k < K; ++k) acc += (int64_t)xr[k] * wr[k];
             int64_t v;
             if (residual) {
-                v = orc_rnd_shift((int64_t)rq_b[j] * acc, rq_c[j])
-                  + orc_rnd_shift((int64_t)res_rq.b * residual[m * (int64_t)N + j], res_rq.c);
+                v = shift_mode((int64_t)rq_b[j] * acc, rq_c[j], floor_shift)
+                  + shift_mode((int64_t)res_rq.b * residual[m * (int64_t)N + j], res_rq.c, floor_shift);
                 v = orc_clamp_k(v, 8);
             } else {
-                v = orc_requant(acc, rq_b[j], rq_c[j]);
+                v = requant_mode(acc, rq_b[j], rq_c[j], floor_shift);
             }
-            if (gelu) v = orc_requant(orc_shiftgelu_raw1(v, *gelu), gelu_rq.b, gelu_rq.c);
+            if (gelu) v = requant_mode(orc_shiftgelu_raw1(v, *gelu), gelu_rq.b, gelu_rq.c, floor_shift);
             y[m * (int64_t)N + j] = (int8_t)v;
         }
     }
+}
+
+void orc_linear_requant(const int8_t* x, const int8_t* w, const int32_t* bias,
+                        const int32_t* rq_b, const int32_t* rq_c,
+                        const int8_t* residual, orc_dyadic res_rq,
+                        const orc_shift_params* gelu, orc_dyadic gelu_rq,
+                        int8_t* y, int64_t M, int32_t N, int32_t K) {
+    orc_linear_requant_mode(x, w, bias, rq_b, rq_c, residual, res_rq, gelu, gelu_rq, y, M, N, K, 0);
 }
 
 /* ------------------------------------------------------ attention and blocks */
@@ -263,9 +281,9 @@ typedef struct { int8_t *u, *qkv, *scores, *probs, *o, *xhat, *v, *h; } orc_taps
  * of the dyadic pair, by the homogeneity argument of Sec. 3.1), an optional
  * int8 relative-position bias [H,T,T] is added, P = Shiftmax(rows of A),
  * O = requant(P V; pv_rq), heads concatenated into o [B*T, C]. */
-void orc_attention_masked(const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask, int8_t* o,
-                          orc_dims d, orc_dyadic qk_rq, orc_shift_params sm, orc_dyadic pv_rq,
-                          int8_t* tap_scores, int8_t* tap_probs) {
+void orc_attention_mode(const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask, int8_t* o,
+                        orc_dims d, orc_dyadic qk_rq, orc_shift_params sm, orc_dyadic pv_rq,
+                        int8_t* tap_scores, int8_t* tap_probs, int32_t floor_shift) {
     int32_t T = d.T, C = d.C, H = d.H, hd = d.C / d.H;
     int8_t* a = (int8_t*)malloc((size_t)T * T);
     int8_t* p = (int8_t*)malloc((size_t)T * T);
@@ -278,7 +296,7 @@ void orc_attention_masked(const int8_t* qkv, const int8_t* rel_bias, const int8_
                     int64_t acc = 0;
                     for (int32_t k = 0; k < hd; ++k)
                         acc += (int64_t)base[(int64_t)i * 3 * C + k] * base[(int64_t)j * 3 * C + C + k];
-                    a[i * T + j] = (int8_t)orc_requant(acc, qk_rq.b, qk_rq.c);
+                    a[i * T + j] = (int8_t)requant_mode(acc, qk_rq.b, qk_rq.c, floor_shift);
                 }
             /* window b uses mask[b % n_mask] ([T, T], shared by the heads): the windows of an image are consecutive */
             for (int32_t i = 0; i < T; ++i)
@@ -289,13 +307,19 @@ void orc_attention_masked(const int8_t* qkv, const int8_t* rel_bias, const int8_
                     int64_t acc = 0;
                     for (int32_t j = 0; j < T; ++j)
                         acc += (int64_t)p[i * T + j] * base[(int64_t)j * 3 * C + 2 * C + k];
-                    o[((int64_t)b * T + i) * C + h * hd + k] = (int8_t)orc_requant(acc, pv_rq.b, pv_rq.c);
+                    o[((int64_t)b * T + i) * C + h * hd + k] = (int8_t)requant_mode(acc, pv_rq.b, pv_rq.c, floor_shift);
                 }
             int64_t off = ((int64_t)b * H + h) * T * T;
             if (tap_scores) memcpy(tap_scores + off, a, (size_t)T * T);
             if (tap_probs) memcpy(tap_probs + off, p, (size_t)T * T);
         }
     free(a); free(p); free(erow);
+}
+
+void orc_attention_masked(const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask, int8_t* o,
+                          orc_dims d, orc_dyadic qk_rq, orc_shift_params sm, orc_dyadic pv_rq,
+                          int8_t* tap_scores, int8_t* tap_probs) {
+    orc_attention_mode(qkv, rel_bias, mask, n_mask, o, d, qk_rq, sm, pv_rq, tap_scores, tap_probs, 0);
 }
 
 void orc_attention(const int8_t* qkv, const int8_t* rel_bias, int8_t* o,

@@ -94,8 +94,12 @@ def _L():
         lib.orc_linear_requant.restype = None
         lib.orc_linear_requant.argtypes = [_P, _P, _P, _P, _P, _P, Dyadic, C.POINTER(ShiftParams), Dyadic,
                                            _P, i64, i32, i32]
+        lib.orc_linear_requant_mode.restype = None
+        lib.orc_linear_requant_mode.argtypes = lib.orc_linear_requant.argtypes + [i32]
         lib.orc_attention_masked.restype = None
         lib.orc_attention_masked.argtypes = [_P, _P, _P, C.c_int32, _P, _Dims, Dyadic, ShiftParams, Dyadic, _P, _P]
+        lib.orc_attention_mode.restype = None
+        lib.orc_attention_mode.argtypes = lib.orc_attention_masked.argtypes + [i32]
         lib.orc_encoder_block.restype = None
         lib.orc_encoder_block.argtypes = [_P, _P, C.POINTER(_BlockParams), _Dims, C.POINTER(_Taps)]
         lib.orc_forward.restype = None
@@ -195,7 +199,8 @@ def ilayernorm(x, gamma_q, beta_q, f_bits, c_shift):
     return y
 
 
-def linear_requant(x, w, bias, rq_b, rq_c, residual=None, res_rq=None, gelu=None, gelu_rq=None):
+def linear_requant(x, w, bias, rq_b, rq_c, residual=None, res_rq=None, gelu=None, gelu_rq=None, floor_shift=False):
+    """floor_shift: every dyadic requantisation of the layer as the bare shift Eq. 10 prints instead of the rounded one."""
     x = _arr(x, np.int8); w = _arr(w, np.int8)
     M, K = x.shape
     N, K2 = w.shape
@@ -208,8 +213,11 @@ def linear_requant(x, w, bias, rq_b, rq_c, residual=None, res_rq=None, gelu=None
         assert residual.shape == (M, N)
     y = np.empty((M, N), np.int8)
     g = None if gelu is None else C.pointer(_sp(gelu))
-    _L().orc_linear_requant(_ptr(x), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c), _ptr(residual), _dy(res_rq),
-                            g, _dy(gelu_rq), _ptr(y), M, N, K)
+    args = (_ptr(x), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c), _ptr(residual), _dy(res_rq), g, _dy(gelu_rq), _ptr(y), M, N, K)
+    if floor_shift:
+        _L().orc_linear_requant_mode(*args, 1)
+    else:
+        _L().orc_linear_requant(*args)
     return y
 
 
@@ -217,8 +225,9 @@ def _dims(d):
     return _Dims(int(d["B"]), int(d["T"]), int(d["C"]), int(d["H"]), int(d["F"]))
 
 
-def attention(qkv, dims, qk_rq, softmax, pv_rq, rel_bias=None, want_taps=False, mask=None):
-    """mask: None or int8 [n_mask, T, T]; window b uses mask[b % n_mask]; nonzero entries add -100 (real units)."""
+def attention(qkv, dims, qk_rq, softmax, pv_rq, rel_bias=None, want_taps=False, mask=None, floor_shift=False):
+    """mask: None or int8 [n_mask, T, T]; window b uses mask[b % n_mask]; nonzero entries add -100 (real units).
+    floor_shift: both dyadic requantisations as the bare shift Eq. 10 prints."""
     qkv = _arr(qkv, np.int8)
     B, T, Cc, H = dims["B"], dims["T"], dims["C"], dims["H"]
     assert qkv.shape == (B * T, 3 * Cc)
@@ -227,8 +236,12 @@ def attention(qkv, dims, qk_rq, softmax, pv_rq, rel_bias=None, want_taps=False, 
     sc = np.empty((B, H, T, T), np.int8) if want_taps else None
     pr = np.empty((B, H, T, T), np.int8) if want_taps else None
     mask = None if mask is None else _arr(mask, np.int8)
-    _L().orc_attention_masked(_ptr(qkv), _ptr(rel_bias), _ptr(mask), 1 if mask is None else int(mask.shape[0]), _ptr(o),
-                              _dims(dims), _dy(qk_rq), _sp(softmax), _dy(pv_rq), _ptr(sc), _ptr(pr))
+    args = (_ptr(qkv), _ptr(rel_bias), _ptr(mask), 1 if mask is None else int(mask.shape[0]), _ptr(o),
+            _dims(dims), _dy(qk_rq), _sp(softmax), _dy(pv_rq), _ptr(sc), _ptr(pr))
+    if floor_shift:
+        _L().orc_attention_mode(*args, 1)
+    else:
+        _L().orc_attention_masked(*args)
     return (o, sc, pr) if want_taps else o
 
 

@@ -19,7 +19,7 @@ EXPORTS = ("ivit_strerror", "ivit_build_id", "ivit_linear_requant", "ivit_shiftm
            "ivit_ilayernorm", "ivit_workspace_bytes", "ivit_attention", "ivit_encoder_block", "ivit_forward",
            "ivit_trace_begin", "ivit_trace_end", "ivit_quantize_symmetric", "ivit_dyadic_from_float",
            "ivit_shift_params_from_scale", "ivit_embed_tokens", "ivit_classifier_head", "ivit_image_workspace_bytes",
-           "ivit_forward_image", "ivit_attention_masked", "ivit_window_attention", "ivit_patch_merge_gather",
+           "ivit_forward_image", "ivit_attention_masked", "ivit_window_attention", "ivit_window_attention_ex", "ivit_patch_merge_gather",
            "ivit_mean_pool", "ivit_swin_window_index", "ivit_swin_shift_mask", "ivit_swin_workspace_bytes",
            "ivit_forward_swin", "ivit_shiftgelu_rowmax", "ivit_encoder_block_static", "ivit_linear_requant_ex",
            "ivit_last_hip_error", "ivit_probe_mfma_rate", "ivit_ilayernorm_limits")
@@ -37,10 +37,15 @@ class Dyadic(C.Structure):
 
 
 class LinearOptions(C.Structure):
-    _fields_ = [("kernel", C.c_int32)]
+    _fields_ = [("kernel", C.c_int32), ("rounding", C.c_int32)]
+
+
+class AttentionOptions(C.Structure):
+    _fields_ = [("rounding", C.c_int32)]
 
 
 KERNELS = {"auto": 0, "many_rows": 1, "reg_stationary": 2}
+ROUNDING = {"nearest": 0, "floor": 1}
 
 
 class Dims(C.Structure):
@@ -143,6 +148,8 @@ def load():
     lib.ivit_attention_masked.argtypes = [_P, _P, _P, _P, i32, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
     lib.ivit_window_attention.restype = C.c_int
     lib.ivit_window_attention.argtypes = [_P, _P, _P, _P, i32, _P, i32, _P, C.POINTER(Dims), Dyadic, ShiftParams, Dyadic, _P, _P]
+    lib.ivit_window_attention_ex.restype = C.c_int
+    lib.ivit_window_attention_ex.argtypes = lib.ivit_window_attention.argtypes + [C.POINTER(AttentionOptions)]
     lib.ivit_patch_merge_gather.restype = C.c_int; lib.ivit_patch_merge_gather.argtypes = [_P, _P, _P, i32, i32, i32]
     lib.ivit_mean_pool.restype = C.c_int; lib.ivit_mean_pool.argtypes = [_P, _P, _P, i32, i32, i32, Dyadic]
     lib.ivit_swin_window_index.restype = C.c_int; lib.ivit_swin_window_index.argtypes = [i32, i32, i32, _P]
@@ -271,17 +278,19 @@ def dims(d):
 
 # ------------------------------------------------------------------ entry points (same names as the C ABI)
 def ivit_linear_requant(x, w, bias, rq_b, rq_c, y, residual=None, res_rq=None, gelu=None, gelu_rq=None, stream=None,
-                        kernel=None):
-    """kernel: None -> ivit_linear_requant; "auto" / "many_rows" / "reg_stationary" -> ivit_linear_requant_ex."""
+                        kernel=None, rounding=None):
+    """kernel, rounding: both None -> ivit_linear_requant; otherwise ivit_linear_requant_ex with kernel "auto" /
+    "many_rows" / "reg_stationary" and rounding "nearest" / "floor"."""
     M, K = x.shape
     N = w.shape[0]
     g = None if gelu is None else C.byref(shift_params(gelu))
     args = (_stream(stream), _ptr(x), _ptr(w), _ptr(bias), _ptr(rq_b), _ptr(rq_c), _ptr(residual), dyadic(res_rq), g,
             dyadic(gelu_rq), _ptr(y), M, N, K)
-    if kernel is None:
+    if kernel is None and rounding is None:
         _check(load().ivit_linear_requant(*args), "ivit_linear_requant")
     else:
-        _check(load().ivit_linear_requant_ex(*args, C.byref(LinearOptions(KERNELS[kernel]))), "ivit_linear_requant_ex")
+        opt = LinearOptions(KERNELS[kernel or "auto"], ROUNDING[rounding or "nearest"])
+        _check(load().ivit_linear_requant_ex(*args, C.byref(opt)), "ivit_linear_requant_ex")
     return y
 
 
@@ -451,13 +460,16 @@ def ivit_forward_image(patches, logits, image, blocks, d, workspace, final_ln, s
 
 
 def ivit_window_attention(qkv, o, d, qk_rq, softmax, pv_rq, rel_bias, tok_index, mask=None, tap_scores=None, tap_probs=None,
-                          stream=None):
-    """tok_index: int32 CUDA tensor [n_win, T]; mask: None or int8 [n_mask, T, T]."""
-    st = load().ivit_window_attention(_stream(stream), _ptr(qkv), _ptr(rel_bias), _ptr(mask),
-                                      1 if mask is None else int(mask.shape[0]), _ptr(tok_index),
-                                      1 if tok_index is None else int(tok_index.shape[0]), _ptr(o), C.byref(dims(d)),
-                                      dyadic(qk_rq), shift_params(softmax), dyadic(pv_rq), _ptr(tap_scores), _ptr(tap_probs))
-    _check(st, "ivit_window_attention")
+                          stream=None, rounding=None):
+    """tok_index: None or int32 CUDA tensor [n_win, T]; mask: None or int8 [n_mask, T, T]; rounding: None (the entry point
+    without options) or "nearest" / "floor" (ivit_window_attention_ex)."""
+    args = (_stream(stream), _ptr(qkv), _ptr(rel_bias), _ptr(mask), 1 if mask is None else int(mask.shape[0]), _ptr(tok_index),
+            1 if tok_index is None else int(tok_index.shape[0]), _ptr(o), C.byref(dims(d)), dyadic(qk_rq), shift_params(softmax),
+            dyadic(pv_rq), _ptr(tap_scores), _ptr(tap_probs))
+    if rounding is None:
+        _check(load().ivit_window_attention(*args), "ivit_window_attention")
+    else:
+        _check(load().ivit_window_attention_ex(*args, C.byref(AttentionOptions(ROUNDING[rounding]))), "ivit_window_attention_ex")
     return o
 
 

@@ -209,6 +209,7 @@ int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const
                            const int32_t* rq_c, const int8_t* residual, ivit_dyadic res_rq, const ivit_shift_params* gelu,
                            ivit_dyadic gelu_rq, int8_t* y, int64_t M, int32_t N, int32_t K, const ivit_linear_options* opt) {
     if (opt && (opt->kernel < IVIT_KERNEL_AUTO || opt->kernel > IVIT_KERNEL_REG_STATIONARY)) return IVIT_ERR_PARAM;
+    if (opt && opt->rounding != IVIT_ROUND_NEAREST && opt->rounding != IVIT_ROUND_FLOOR) return IVIT_ERR_PARAM;
     if (M < 0 || N < 1 || K < 16 || K > 65536 || (K & 15)) return IVIT_ERR_SHAPE;
     if (M > 0 && (!x || !y)) return IVIT_ERR_NULL;             // an empty tensor may have no storage
     if (!w || !rq_b || !rq_c) return IVIT_ERR_NULL;
@@ -226,6 +227,7 @@ int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const
     if (gelu) { a.gelu_p = sp(*gelu); a.gelu_rq = dy(gelu_rq); }
     a.y = y; a.M = M; a.N = N; a.K = K;
     a.kernel = opt ? opt->kernel : ivit::LINEAR_AUTO;
+    a.floor_shift = opt && opt->rounding == IVIT_ROUND_FLOOR;
     if (a.kernel == ivit::LINEAR_REG_STATIONARY && M > 0 && !ivit::linear_rs_takes(a)) return IVIT_ERR_SHAPE;
     return hip_status(ivit::launch_linear(static_cast<hipStream_t>(stream), a));
 }
@@ -302,7 +304,16 @@ int ivit_attention_masked(void* stream, const int8_t* qkv, const int8_t* rel_bia
 int ivit_window_attention(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
                           const int32_t* tok_index, int32_t n_win, int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq,
                           ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs) {
+    return ivit_window_attention_ex(stream, qkv, rel_bias, mask, n_mask, tok_index, n_win, o, d, qk_rq, softmax, pv_rq,
+                                    tap_scores, tap_probs, nullptr);
+}
+
+int ivit_window_attention_ex(void* stream, const int8_t* qkv, const int8_t* rel_bias, const int8_t* mask, int32_t n_mask,
+                             const int32_t* tok_index, int32_t n_win, int8_t* o, const ivit_dims* d, ivit_dyadic qk_rq,
+                             ivit_shift_params softmax, ivit_dyadic pv_rq, int8_t* tap_scores, int8_t* tap_probs,
+                             const ivit_attention_options* opt) {
     if (!d) return IVIT_ERR_NULL;
+    if (opt && opt->rounding != IVIT_ROUND_NEAREST && opt->rounding != IVIT_ROUND_FLOOR) return IVIT_ERR_PARAM;
     if (mask && n_mask < 1) return IVIT_ERR_SHAPE;
     int st;
     if ((st = check_dims(d)) != IVIT_OK) return st;
@@ -317,6 +328,7 @@ int ivit_window_attention(void* stream, const int8_t* qkv, const int8_t* rel_bia
     a.mask = mask; a.n_mask = mask ? n_mask : 1;
     a.tok_index = tok_index; a.n_win = tok_index ? n_win : 1;
     a.qk_rq = dy(qk_rq); a.sm = sp(softmax); a.pv_rq = dy(pv_rq); a.tap_scores = tap_scores; a.tap_probs = tap_probs;
+    a.floor_shift = opt && opt->rounding == IVIT_ROUND_FLOOR;
     return hip_status(ivit::launch_attention(static_cast<hipStream_t>(stream), a));
 }
 

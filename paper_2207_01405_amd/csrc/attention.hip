@@ -25,10 +25,7 @@ namespace ivit {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-#ifndef IVIT_ATT_WAVES
-#define IVIT_ATT_WAVES 4
-#endif
-constexpr int ATT_WAVES = IVIT_ATT_WAVES, ATT_THREADS = 64 * ATT_WAVES;   // wavefronts per workgroup
+constexpr int ATT_WAVES = 4, ATT_THREADS = 64 * ATT_WAVES;   // wavefronts per workgroup
 
 // position of key k inside a V^T row: 64-key chunk c = k / 64; inside it lane group g = (k % 16) / 4 owns
 // 16 consecutive bytes ordered by tile (k / 16) % 4, then k % 4
@@ -43,7 +40,7 @@ struct Narrow { int32_t lo, hi, mb, ad; };
 
 // FAST: 0 general 64-bit requantisation, 1 pairs that fit 32 bits, 2 the 24-bit form above (and the 24-bit IntDiv).
 template <int FAST>
-__device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d, Narrow n) {
+__device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d, Narrow n, int32_t rnd) {
     if (FAST == 2) {
         // The median of three as the one instruction, by hand because the compiler cannot know lo <= hi.  The compiler
         // does not see what an asm statement reads and puts no wait states between it and the producer of v: v must
@@ -53,7 +50,7 @@ __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d, Narrow n) {
         asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m) : "v"(v), "v"(n.lo), "v"(n.hi));
         return (__mul24(m, n.mb) + n.ad) >> 24;
     }
-    return FAST ? clamp8(rnd_shift_fit32(v, d.b, d.c)) : requant64(v, d.b, d.c);
+    return FAST ? clamp8(rnd_shift_fit32(v, d.b, d.c, rnd)) : requant64(v, d.b, d.c, rnd);
 }
 
 // FAST: both dyadic pairs are rescales by at most 1 with c <= 31 (32-bit requantisation) and the row sum always
@@ -66,7 +63,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                                                         const int8_t* __restrict__ mask, int n_mask,
                                                         const int32_t* __restrict__ tok_index, int n_win,
                                                         int8_t* __restrict__ o, int n_items, int split, int T_arg, int C, int H,
-                                                        Dyadic qk, ShiftParams sm, Dyadic pv, Narrow nqk, Narrow npv,
+                                                        Dyadic qk, ShiftParams sm, Dyadic pv, Narrow nqk, Narrow npv, int rnd,
                                                         int8_t* __restrict__ tap_s, int8_t* __restrict__ tap_p) {
     const int T = TFIX ? TFIX : T_arg;
     constexpr int KROW = D + 16;                  // K row pitch (bytes)
@@ -239,7 +236,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int key = 16 * t + 4 * lg + r;
-                        int32_t a = requant8<FAST>(sc[t][r], qk, nqk);
+                        int32_t a = requant8<FAST>(sc[t][r], qk, nqk, rnd);
                         if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
                         if (BIAS) a += (int32_t)(int8_t)(bw >> (8 * r));
                         if (MASK) { if ((mw >> (8 * r)) & 0xffu) a += mask_add; }
@@ -251,7 +248,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int key = 16 * t + 4 * lg + r;
-                        int32_t a = requant8<FAST>(sc[t][r], qk, nqk);
+                        int32_t a = requant8<FAST>(sc[t][r], qk, nqk, rnd);
                         if (key < T) {
                             if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
                             if (BIAS) { if (!MASK || brow) a += brow[key]; }
@@ -363,7 +360,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             for (int n = 0; n < ND; ++n) {
                 uint32_t w = 0;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) w |= ((uint32_t)requant8<FAST>(oacc[n][r], pv, npv) & 0xffu) << (8 * r);
+                for (int r = 0; r < 4; ++r) w |= ((uint32_t)requant8<FAST>(oacc[n][r], pv, npv, rnd) & 0xffu) << (8 * r);
                 ow[n] = w;
             }
             if (q < T) {
@@ -376,11 +373,12 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 }
 
 // The 24-bit constants of a pair, or false when the pair needs the wider forms.
-static bool narrow_of(Dyadic d, Narrow& n) {
+// (rnd = 1: the rounding addend h is 2^(c-1); rnd = 0: the bare shift of Eq. 10, h = 0)
+static bool narrow_of(Dyadic d, int rnd, Narrow& n) {
     if (d.c < 1 || d.c > 24 || d.b < 1 || d.b >= (1 << (d.c - 1))) return false;
-    const int64_t half = (int64_t)1 << (d.c - 1), two_c = (int64_t)1 << d.c;
-    const int64_t hi = (127 * two_c - half + d.b - 1) / d.b;             // first v with round(v b / 2^c) >= 127
-    const int64_t lo = -((127 * two_c - half + 1 + d.b - 1) / d.b);      // last v with round(v b / 2^c) <= -127
+    const int64_t half = (int64_t)rnd << (d.c - 1), two_c = (int64_t)1 << d.c;
+    const int64_t hi = (127 * two_c - half + d.b - 1) / d.b;             // first v with (v b + h) >> c >= 127
+    const int64_t lo = -((126 * two_c + 1 + half + d.b - 1) / d.b);      // last v with (v b + h) >> c <= -127
     if (lo < -(1 << 23) || hi >= (1 << 23)) return false;
     n.lo = (int32_t)lo; n.hi = (int32_t)hi; n.mb = d.b << (24 - d.c); n.ad = (int32_t)(half << (24 - d.c));
     return true;
@@ -391,11 +389,12 @@ static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, int sp
     const int n_items = a.B * a.H;
     Narrow nqk{}, npv{};
     // the 24-bit forms: both requantisations, and IntDiv with its quotient in the top byte of a 24-bit product
-    const bool narrow = narrow_of(a.qk_rq, nqk) && narrow_of(a.pv_rq, npv) && a.sm.m_bits - (a.sm.k_out - 1) == 24;
+    const int rnd = a.floor_shift ? 0 : 1;
+    const bool narrow = narrow_of(a.qk_rq, rnd, nqk) && narrow_of(a.pv_rq, rnd, npv) && a.sm.m_bits - (a.sm.k_out - 1) == 24;
 #define IVIT_ATT(TAPS_, BIAS_, MASK_, FAST_, TFIX_)                                                                         \
     hipLaunchKernelGGL((attention_kernel<D, NKT, TAPS_, BIAS_, MASK_, FAST_, TFIX_>), dim3(grid), dim3(ATT_THREADS), 0, s,     \
                        a.qkv, a.rel_bias, a.mask, a.n_mask, a.tok_index, a.n_win, a.o, n_items, split, a.T, a.C, a.H, a.qk_rq, \
-                       a.sm, a.pv_rq, nqk, npv, a.tap_scores, a.tap_probs)
+                       a.sm, a.pv_rq, nqk, npv, rnd, a.tap_scores, a.tap_probs)
     // the production paths are <no taps, fast>, with the 24-bit requantisation when both pairs allow it; everything else
     // shares one fully general instantiation per bias / mask combination (a mask is always compiled with the bias code,
     // which tests the bias pointer)

@@ -21,13 +21,8 @@ namespace ivit {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-#ifndef IVIT_GEMM_BK
-#define IVIT_GEMM_BK 128
-#endif
-#ifndef IVIT_GEMM_WGS_PER_CU
-#define IVIT_GEMM_WGS_PER_CU 2
-#endif
-constexpr int BM = 128, BN = 128, BK = IVIT_GEMM_BK;
+constexpr int BM = 128, BN = 128, BK = 128;
+constexpr int TILED_WGS_PER_CU = 2;           // workgroups of the tiled kernel resident per compute unit
 constexpr int CPR = BK / 16;                  // 16-byte chunks per tile row
 constexpr int RPP = 256 / CPR;                // tile rows covered by one pass of the 256 threads
 constexpr int NLD = BM / RPP;                 // passes (= 16-byte loads per thread and operand) per K step
@@ -41,6 +36,7 @@ struct GemmParams {
     const int8_t* residual; Dyadic res_rq; ShiftParams gelu_p; Dyadic gelu_rq;
     int8_t* y; int64_t M; int N; int K; int tiles_n; int64_t tiles; int64_t per_xcd;
     int64_t ldx;                         // bytes between rows of x
+    int rnd;                             // 1: round to nearest, 0: floor (every requantisation of the epilogue)
 };
 
 // LDS row (0..63) of channel offset n (0..63) inside a wavefront's 64-channel slab.  MFMA tile ct, row
@@ -87,13 +83,13 @@ __device__ __forceinline__ void epilogue(const GemmParams& P, const v16i (&acc)[
                 if (EPI == EPI_RESIDUAL) {
                     const int32_t res = (int32_t)(int8_t)(resw[w4] >> (8 * r));
                     if (FAST && res_fast) {
-                        v = clamp8(rnd_shift_fit32(a32, qb[r], qc[r]) + rnd_shift_fit32(res, P.res_rq.b, P.res_rq.c));
+                        v = clamp8(rnd_shift_fit32(a32, qb[r], qc[r], P.rnd) + rnd_shift_fit32(res, P.res_rq.b, P.res_rq.c, P.rnd));
                     } else {
-                        const int64_t rr = rnd_shift64(res, P.res_rq.b, P.res_rq.c);
-                        v = clamp8_64((FAST ? (int64_t)rnd_shift_fit32(a32, qb[r], qc[r]) : rnd_shift64(a32, qb[r], qc[r])) + rr);
+                        const int64_t rr = rnd_shift64(res, P.res_rq.b, P.res_rq.c, P.rnd);
+                        v = clamp8_64((FAST ? (int64_t)rnd_shift_fit32(a32, qb[r], qc[r], P.rnd) : rnd_shift64(a32, qb[r], qc[r], P.rnd)) + rr);
                     }
                 } else {
-                    v = FAST ? clamp8(rnd_shift_fit32(a32, qb[r], qc[r])) : requant64(a32, qb[r], qc[r]);
+                    v = FAST ? clamp8(rnd_shift_fit32(a32, qb[r], qc[r], P.rnd)) : requant64(a32, qb[r], qc[r], P.rnd);
                     if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
                 }
                 packed |= ((uint32_t)v & 0xffu) << (8 * r);
@@ -117,7 +113,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& P, const v16i (&acc)[
 struct Stage { v4i x[NLD], w[NLD]; };               // one K step of a thread's share of both operand tiles
 
 template <int EPI>
-__global__ __launch_bounds__(256, IVIT_GEMM_WGS_PER_CU) void gemm_i8_kernel(GemmParams P) {
+__global__ __launch_bounds__(256, TILED_WGS_PER_CU) void gemm_i8_kernel(GemmParams P) {
     __shared__ __align__(16) int8_t Xs[2][BM * LROW];
     __shared__ __align__(16) int8_t Ws[2][BN * LROW];
     __shared__ __align__(16) int32_t qb_s[BN], qc_s[BN], bias_s[BN];
@@ -143,7 +139,7 @@ __global__ __launch_bounds__(256, IVIT_GEMM_WGS_PER_CU) void gemm_i8_kernel(Gemm
 #pragma unroll
     for (int p = 0; p < NLD; ++p) {
         const int r = ld_row + RPP * p;
-        const int64_t xm = min<int64_t>(m0 + r, M - 1);
+        const int64_t xm = min64(m0 + r, M - 1);
         const int wnn = min(n0 + r, N - 1);
         xg[p] = P.x + xm * P.ldx + ld_k;
         wg[p] = P.w + (int64_t)wnn * K + ld_k;
@@ -184,7 +180,7 @@ __global__ __launch_bounds__(256, IVIT_GEMM_WGS_PER_CU) void gemm_i8_kernel(Gemm
     }
     if (EPI == EPI_GELU) {
         const int32_t I = (int32_t)(int8_t)tid;
-        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
+        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c, P.rnd);
     }
     store_stage(st0, 0);
     if (steps > 2) load_stage(st0, 2);
@@ -330,11 +326,11 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
     v4i xa[UNIT][4], xb[UNIT][4];
     const int l8 = lane >> 3, p8 = lane & 7;
     auto issue = [&](v4i (&buf)[UNIT][4]) __attribute__((always_inline)) {
-        const int64_t g0 = min<int64_t>(lgrp, W.groups - 1) * 32 + l8;
+        const int64_t g0 = min64(lgrp, W.groups - 1) * 32 + l8;
         const int start = lu * (UNIT * WS_CHUNK) + 16 * p8;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const int8_t* row = P.x + min<int64_t>(g0 + 8 * t, M - 1) * P.ldx;
+            const int8_t* row = P.x + min64(g0 + 8 * t, M - 1) * P.ldx;
 #pragma unroll
             for (int c = 0; c < UNIT; ++c) {
                 const int off = start + c * WS_CHUNK;
@@ -366,10 +362,10 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
                 if (n0 + n < N && 16 * ck < K) v = *reinterpret_cast<const v4i*>(P.w + (int64_t)(n0 + n) * K + 16 * ck);
                 *reinterpret_cast<v4i*>(Wl + row_of_channel<NCB>(n) * pitch + 16 * ck) = v;
             }
-        if (tid < NS) { qb_s[tid] = pb; qc_s[tid] = pc; bias_s[tid] = pbias; hb_s[tid] = (int64_t)pbias * pb + (int64_t)(1u << ((pc - 1) & 31)); }
+        if (tid < NS) { qb_s[tid] = pb; qc_s[tid] = pc; bias_s[tid] = pbias; hb_s[tid] = (int64_t)pbias * pb + (int64_t)((uint32_t)P.rnd << ((pc - 1) & 31)); }
         if (EPI == EPI_GELU && tid < 256) {
             const int32_t I = (int32_t)(int8_t)tid;
-            gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
+            gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c, P.rnd);
         }
         // 24-bit requantisation.  With v = dot + bias, the int8 result clamp8((v b + 2^(c-1)) >> c) is the same for all
         // v >= Lp (127) and all v <= Ln (-127), Lp / Ln being the first v that reach +-127; for b < 2^c the result AT Lp
@@ -389,7 +385,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             const int64_t br = P.res_rq.b, cr = P.res_rq.c;
             bool res_ok = br >= 1 && br < (1 << 23) && cr >= 1 && cr <= 30;
             if (res_ok) {
-                const int64_t hr = (int64_t)1 << (cr - 1);
+                const int64_t hr = (int64_t)P.rnd << (cr - 1);
                 const int64_t r2 = max((127 * br + hr) >> cr, -((-128 * br + hr) >> cr));
                 res_ok = r2 <= 128;
                 wlim = 127 + r2;
@@ -402,9 +398,11 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             if (n0 + tid < N && chan_24) {
                 chan_24 = pc >= 1 && pc <= sh24 && pb >= 1 && pb < (1 << ((pc - 1) & 31));
                 if (chan_24) {
-                    const int64_t half = (int64_t)1 << (pc - 1), two_c = (int64_t)1 << pc;
+                    // with h the rounding addend (2^(c-1), or 0 for the bare shift): (v b + h) >> c >= W from
+                    // v = ceil((W 2^c - h) / b) on, <= -W up to v = -ceil(((W - 1) 2^c + 1 + h) / b)
+                    const int64_t half = (int64_t)P.rnd << (pc - 1), two_c = (int64_t)1 << pc;
                     const int64_t Lp = (wlim * two_c - half + pb - 1) / pb;
-                    const int64_t Ln = -((wlim * two_c - half + 1 + pb - 1) / pb);
+                    const int64_t Ln = -(((wlim - 1) * two_c + 1 + half + pb - 1) / pb);
                     const int64_t l = Ln - pbias, h = Lp - pbias;
                     chan_24 = l >= -(1 << 23) && h < (1 << 23);
                     lo = (int32_t)l; hi = (int32_t)h; mb = pb << (sh24 - pc);
@@ -515,10 +513,10 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             asm volatile("s_nop 7");
             asm volatile("s_nop 3");
             __builtin_amdgcn_sched_barrier(0);
-            const int32_t rb = P.res_rq.b, rc = P.res_rq.c, rh = 1 << ((P.res_rq.c - 1) & 31);
+            const int32_t rb = P.res_rq.b, rc = P.res_rq.c, rh = P.rnd << ((P.res_rq.c - 1) & 31);
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
-                const int64_t rt = min<int64_t>(tok, M - 1);
+                const int64_t rt = min64(tok, M - 1);
                 const v4i resv = *reinterpret_cast<const v4i*>(P.residual + rt * N + min(n0 + nl + 16 * cb, N - 16));
                 v4i outv;
 #pragma unroll
@@ -548,7 +546,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
             for (int cb = 0; cb < NCB; ++cb) {
                 v4i resv = {0, 0, 0, 0};
                 if (EPI == EPI_RESIDUAL) {              // N % 16 == 0: a 16-channel piece is in or out as a whole
-                    const int64_t rt = min<int64_t>(tok, M - 1);
+                    const int64_t rt = min64(tok, M - 1);
                     resv = *reinterpret_cast<const v4i*>(P.residual + rt * N + min(n0 + nl + 16 * cb, N - 16));
                 }
                 v4i outv;
@@ -568,7 +566,7 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
                         int32_t v = (int32_t)__builtin_amdgcn_alignbit((uint32_t)(pr >> 32), (uint32_t)pr, qc[r]);
                         if (EPI == EPI_RESIDUAL) {
                             const int32_t res = (int32_t)(int8_t)((uint32_t)resv[w4] >> (8 * r));
-                            v += rnd_shift_fit32(res, P.res_rq.b, P.res_rq.c);
+                            v += rnd_shift_fit32(res, P.res_rq.b, P.res_rq.c, P.rnd);
                         }
                         v = clamp8(v);
                         if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
@@ -601,9 +599,9 @@ __global__ __launch_bounds__(WS_THREADS) void gemm_ws_kernel(WsParams W) {
                     const int n = n0 + nloc;
                     if (tk < M && n < N) {
                         const int32_t a32 = st32[t * 32 + c] + bias_s[nloc];
-                        int64_t r64 = rnd_shift64(a32, qb_s[nloc], qc_s[nloc]);
+                        int64_t r64 = rnd_shift64(a32, qb_s[nloc], qc_s[nloc], P.rnd);
                         int32_t v;
-                        if (EPI == EPI_RESIDUAL) v = clamp8_64(r64 + rnd_shift64(P.residual[tk * N + n], P.res_rq.b, P.res_rq.c));
+                        if (EPI == EPI_RESIDUAL) v = clamp8_64(r64 + rnd_shift64(P.residual[tk * N + n], P.res_rq.b, P.res_rq.c, P.rnd));
                         else v = clamp8_64(r64);
                         if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
                         P.y[tk * N + n] = (int8_t)v;
@@ -671,10 +669,10 @@ __global__ __launch_bounds__(64 * SM_WAVES) void gemm_small_kernel(GemmParams P)
     const int n0 = (int)(tile % tiles_n) * 32;
     if (EPI == EPI_GELU) {
         const int32_t I = (int32_t)(int8_t)tid;
-        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
+        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c, P.rnd);
     }
     // rows past the end repeat the last one (their results are not stored); K % 32 == 16: the upper half of the last step is zero
-    const int8_t* xr = P.x + min<int64_t>(m0 + li, M - 1) * P.ldx + 16 * lg;
+    const int8_t* xr = P.x + min64(m0 + li, M - 1) * P.ldx + 16 * lg;
     const int8_t* wr = P.w + (int64_t)min(n0 + li, N - 1) * K + 16 * lg;
     const int nsteps = (K + 31) / 32;
     // the first wavefront's requantisation constants are requested before the operands, not after the multiply
@@ -719,9 +717,9 @@ __global__ __launch_bounds__(64 * SM_WAVES) void gemm_small_kernel(GemmParams P)
             int32_t a = acc[i] + part[0][i][lane] + part[1][i][lane] + part[2][i][lane];
             if (tok < M && n < N) {
                 a += qbias[i];
-                const int64_t r64 = rnd_shift64(a, qb[i], qc[i]);
+                const int64_t r64 = rnd_shift64(a, qb[i], qc[i], P.rnd);
                 int32_t v;
-                if (EPI == EPI_RESIDUAL) v = clamp8_64(r64 + rnd_shift64(P.residual[tok * N + n], P.res_rq.b, P.res_rq.c));
+                if (EPI == EPI_RESIDUAL) v = clamp8_64(r64 + rnd_shift64(P.residual[tok * N + n], P.res_rq.b, P.res_rq.c, P.rnd));
                 else v = clamp8_64(r64);
                 if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
                 P.y[tok * N + n] = (int8_t)v;
@@ -779,7 +777,7 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     GemmParams P;
     P.x = a.x; P.w = a.w; P.bias = a.bias; P.rq_b = a.rq_b; P.rq_c = a.rq_c;
     P.residual = a.residual; P.res_rq = a.res_rq; P.gelu_p = a.gelu_p; P.gelu_rq = a.gelu_rq;
-    P.y = a.y; P.M = a.M; P.N = a.N; P.K = a.K; P.ldx = a.ldx ? a.ldx : a.K;
+    P.y = a.y; P.M = a.M; P.N = a.N; P.K = a.K; P.ldx = a.ldx ? a.ldx : a.K; P.rnd = a.floor_shift ? 0 : 1;
     P.tiles_n = (a.N + BN - 1) / BN;
     const int64_t tiles_m = (a.M + BM - 1) / BM;
     P.tiles = tiles_m * P.tiles_n;

@@ -40,7 +40,8 @@ struct RsParams {
     const int8_t* residual; Dyadic res_rq; ShiftParams gelu_p; Dyadic gelu_rq;
     int8_t* y; int64_t M; int N; int64_t ldx;
     int slabs, q;                            // channel slabs (4 NCB tiles each), workgroups per slab
-    int64_t stages;                          // stages of GR token tiles of 32
+    int stages;                              // stages of GR token tiles of 32
+    int rnd;                                 // 1: round to nearest, 0: floor (every requantisation of the epilogue)
 };
 
 __device__ __forceinline__ uint32_t lds_offset(const int8_t* p) {
@@ -85,14 +86,18 @@ struct RsLayout {
     static constexpr int RP = 32 * NCB + 16, RS16 = RP / 16;       // residual staging: pitch of a token row, 16-byte slots in it
     static constexpr int RNI = (32 * RS16 + 63) / 64;              // residual load instructions per lane and tile
     static constexpr int RT = RNI * 1024;
-    static constexpr int XS = 0, OUT = 3 * XT, RES = OUT + NW * OT;
+    // stage buffers 1 and 2, the output and residual staging and the ShiftGELU table share their memory with the weight
+    // chunks of the prologue; stage buffer 0 lies beyond both, so that the first stage can be requested at the very start
+    static constexpr int XS1 = 0, OUT = 2 * XT, RES = OUT + NW * OT;
     static constexpr int LUT = RES + (EPI == EPI_RESIDUAL ? NW * 2 * RT : 0);
     static constexpr int MAIN = LUT + 256;
     static constexpr int NCHUNK = NCB * (K / WCK);                 // weight chunks of the prologue
     static constexpr int WNI = (WWI + NW - 1) / NW;                // load instructions per wavefront and chunk
     static constexpr int WCHUNK = WNI * NW * 1024;                 // LDS bytes of a chunk (whole rounds of all wavefronts)
     static constexpr int STAGING = (NCHUNK > 1 ? 2 : 1) * WCHUNK;  // the chunks pass through the same memory, before the main loop
-    static constexpr int TOTAL = MAIN > STAGING ? MAIN : STAGING;
+    static constexpr int XS0 = MAIN > STAGING ? MAIN : STAGING;
+    static constexpr int TOTAL = XS0 + XT;
+    __host__ __device__ static constexpr int stage_offset(int b) { return b == 0 ? XS0 : XS1 + (b - 1) * XT; }
     static_assert(K % WCK == 0, "K must be a whole number of weight chunks");
     static_assert(TOTAL + 1024 <= 160 * 1024, "LDS");
 };
@@ -122,7 +127,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     static_assert(KS - SYNC >= NI && KS - SYNC >= RNI && KS - SYNC >= NCB + 1, "the work after the barrier is spread over its k-steps");
 
     extern __shared__ __align__(1024) int8_t lds[];
-    int8_t* Xs = lds + LY::XS;                                 // [3][XT]
+    int8_t* Xs = lds;                                          // stage buffer b at LY::stage_offset(b), XT bytes each
     int8_t* Out = lds + LY::OUT;                               // [waves][OT]
     int8_t* Res = lds + LY::RES;                               // [waves][2][RT]   (residual layers only)
     int8_t* gelu_lut = lds + LY::LUT;                          // [256]
@@ -143,7 +148,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     const int slab = L % P.slabs, wi = L / P.slabs;
     const int tile0 = (slab * 4 + wq) * NCB;                   // first channel tile of this wavefront
     const int n0w = tile0 * 32;                                // its first channel
-    const int64_t ntile = wi < P.stages ? (P.stages - wi + P.q - 1) / P.q : 0;  // stages of this workgroup; stage k is wi + k q
+    const int ntile = wi < P.stages ? (P.stages - wi + P.q - 1) / P.q : 0;      // stages of this workgroup; stage k is wi + k q
     if (ntile == 0) return;                                    // (the same for all wavefronts of a workgroup)
 
     // ---- requantisation parameters of this lane's channels: requested first, used after the weights are in place
@@ -152,6 +157,54 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     for (int cb = 0; cb < NCB; ++cb) {
         const int ch = min(tile0 + cb, Nt - 1) * 32 + lj;      // channel tiles past the last one repeat it; never stored
         pb[cb] = P.rq_b[ch]; pc[cb] = P.rq_c[ch]; pbias[cb] = P.bias ? P.bias[ch] : 0;
+    }
+
+    // ---- activation loads: load instruction n (64 lanes x 16 bytes, n = i NW + wavefront) of a stage covers slots
+    // 64 n .. 64 n + 63; slot s is piece s % P16 of LDS row s / P16, and LDS row r holds token token_of_row(r % 32) of
+    // tile r / 32 of the stage, so that the lanes of an MFMA "A" read sit in consecutive LDS rows (the pad piece repeats
+    // the last one; slots past the last row repeat it and land in the slack of the stage).  The address of a piece is
+    // a scalar base (the stage) plus a 32-bit offset per lane, computed once; only a ragged last stage, whose missing
+    // rows repeat the last row of the matrix, computes offsets of its own.  What a stage or tile needs beyond that
+    // (its base pointer, how many of its rows exist) is scalar state that moves on by a fixed step per tile.
+    constexpr int SR = 32 * GR;                                // rows of a stage
+    const uint32_t xs_off = lds_offset(Xs) + wv * 1024;
+    const int ldx = (int)P.ldx;                                // (K: far below 2^24, the offsets inside a stage are 24-bit products)
+    int ld_row[NI], ld_col[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+        const int s = 64 * (i * NW + wv) + lane;
+        const int r = min(s / P16, SR - 1);
+        ld_row[i] = 32 * (r >> 5) + token_of_row(r & 31);
+        ld_col[i] = 16 * min(s % P16, 2 * KS - 1);
+    }
+    const int row_step = P.q * SR;                             // rows between two stages of this workgroup
+    struct Cursor {                                            // a stage (or this group's tile of it) some steps ahead
+        const int8_t* p;                                       // its first row (never dereferenced when rows <= 0)
+        int rows;                                              // rows of the matrix from there on (<= 0: past the end)
+    };
+    auto cursor = [&](const int8_t* base, int64_t row_bytes, int ahead, int row_in_stage) __attribute__((always_inline)) -> Cursor {
+        const int64_t row0 = ((int64_t)wi + (int64_t)ahead * P.q) * SR + row_in_stage;
+        return Cursor{base + row0 * row_bytes, (int)max64(M - row0, -(1 << 30))};
+    };
+    const int64_t x_step = (int64_t)row_step * P.ldx, n_step = (int64_t)row_step * N;
+    auto advance = [&](Cursor& c, int64_t step_bytes) __attribute__((always_inline)) { c.p += step_bytes; c.rows -= row_step; };
+    const int8_t* x_last = P.x + (M - 1) * P.ldx;              // a stage past the matrix reads its last row instead
+    // What a load instruction needs of its stage: where it starts and which is its last row that exists (the rows
+    // after it repeat it) -- two scalars; every lane limits its row and forms its offset from them (two instructions).
+    struct Span { const int8_t* base; int last; };
+    auto span_of = [&](const Cursor& c, const int8_t* fallback, int rows_max) __attribute__((always_inline)) -> Span {
+        return Span{uniform_ptr(c.rows > 0 ? c.p : fallback), __builtin_amdgcn_readfirstlane(min(max(c.rows, 1), rows_max) - 1)};
+    };
+    auto issue_act_one = [&](const Span& sp, uint32_t dst, int i) __attribute__((always_inline)) {
+        if ((i + 1) * NW > NWI && i * NW + wv >= NWI) return;  // the stage ends inside the last round of instructions
+        dma16(sp.base, (uint32_t)(__mul24(min(ld_row[i], sp.last), ldx) + ld_col[i]), dst + i * (NW * 1024));
+    };
+
+    // the first stage is requested before anything else: it lands while the weights are brought in
+    {
+        const Span s0 = span_of(cursor(P.x, P.ldx, 0, 0), x_last, SR);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) issue_act_one(s0, xs_off + LY::stage_offset(0), i);
     }
 
     // ---- weights.  Lane (lj, lg) needs, for channel tile cb and k-step ks, bytes 32 ks + 16 lg .. + 15 of the row of
@@ -177,8 +230,13 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
 #pragma unroll
         for (int c = 0; c < NCHUNK; ++c) {
             // loads complete in order: all but the WNI of the following chunk
+            if (c == 0) RS_STAMP(25);
             if (c + 1 < NCHUNK) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WNI) : "memory"); else wait_vm0();
+            if (c == 0) RS_STAMP(26);
+            if (c == 1) RS_STAMP(28);
             __syncthreads();
+            if (c == 0) RS_STAMP(27);
+            if (c == 1) RS_STAMP(29);
             const int cb = c / KH, kh = c % KH;
             const int8_t* src = lds + (c & 1) * WCHUNK + (wq * 32 + lj) * WPITCH + 16 * lg;
 #pragma unroll
@@ -193,67 +251,23 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         }
     }
 
-    // ---- activation loads: load instruction n (64 lanes x 16 bytes, n = i NW + wavefront) of a stage covers slots
-    // 64 n .. 64 n + 63; slot s is piece s % P16 of LDS row s / P16, and LDS row r holds token token_of_row(r % 32) of
-    // tile r / 32 of the stage, so that the lanes of an MFMA "A" read sit in consecutive LDS rows (the pad piece repeats
-    // the last one; slots past the last row repeat it and land in the slack of the stage).  The address of a piece is
-    // a scalar base (the stage) plus a 32-bit offset per lane, computed once; only a ragged last stage, whose missing
-    // rows repeat the last row of the matrix, computes offsets of its own.  What a stage or tile needs beyond that
-    // (its base pointer, how many of its rows exist) is scalar state that moves on by a fixed step per tile.
-    constexpr int SR = 32 * GR;                                // rows of a stage
-    const uint32_t xs_off = lds_offset(Xs) + wv * 1024;
-    int ld_row[NI], ld_col[NI];
-    uint32_t ld_off[NI];
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int s = 64 * (i * NW + wv) + lane;
-        const int r = min(s / P16, SR - 1);
-        ld_row[i] = 32 * (r >> 5) + token_of_row(r & 31);
-        ld_col[i] = 16 * min(s % P16, 2 * KS - 1);
-        ld_off[i] = (uint32_t)(ld_row[i] * (int)P.ldx + ld_col[i]);
-    }
-    const int64_t row_step = (int64_t)P.q * SR;                // rows between two stages of this workgroup
-    struct Cursor {                                            // a stage (or this group's tile of it) some steps ahead
-        const int8_t* p;                                       // its first row
-        int64_t rows;                                          // rows of the matrix from there on (<= 0: past the end)
-        int left;                                              // steps until it has reached the workgroup's last stage
-    };
-    auto cursor = [&](const int8_t* base, int64_t row_bytes, int64_t ahead, int row_in_stage) __attribute__((always_inline)) -> Cursor {
-        const int64_t k = min<int64_t>(ahead, ntile - 1);
-        const int64_t row0 = (wi + k * P.q) * SR + row_in_stage;
-        return Cursor{base + row0 * row_bytes, M - row0, (int)min<int64_t>(ntile - 1 - k, 1 << 30)};
-    };
-    auto advance = [&](Cursor& c, int64_t step_bytes) __attribute__((always_inline)) {      // past the end: the last stage again
-        if (c.left > 0) { --c.left; c.p += step_bytes; c.rows -= row_step; }
-    };
-    const int64_t x_step = row_step * P.ldx, n_step = row_step * N;
-    // one load instruction of a stage: base and rows are the stage's (scalars), rows >= 1
-    auto issue_act_one = [&](const int8_t* base, int rows, uint32_t dst, int i) __attribute__((always_inline)) {
-        if ((i + 1) * NW > NWI && i * NW + wv >= NWI) return;  // the stage ends inside the last round of instructions
-        if (rows >= SR) dma16(base, ld_off[i], dst + i * (NW * 1024));
-        else dma16(base, (uint32_t)(min(ld_row[i], rows - 1) * (int)P.ldx + ld_col[i]), dst + i * (NW * 1024));
-    };
-
     // ---- residual tile of a wavefront: [32 tokens][RP] bytes, slot s = 64 i + lane = piece s % RS16 of token s / RS16
     int8_t* out_w = Out + wv * OT;
     int8_t* res_w = Res + wv * 2 * RT;
     static_assert(NT >= 256, "the ShiftGELU table is filled by threads 0 .. 255");
     const uint32_t res_off = lds_offset(res_w);
     int rs_col[RNI], rs_row[RNI];
-    uint32_t rs_off[RNI];
     if (EPI == EPI_RESIDUAL) {
 #pragma unroll
         for (int i = 0; i < RNI; ++i) {
             const int s = 64 * i + lane;
             rs_row[i] = min(s / RS16, 31);
             rs_col[i] = min(n0w + 16 * min(s % RS16, 2 * NCB - 1), N - 16);
-            rs_off[i] = (uint32_t)(rs_row[i] * N + rs_col[i]);
         }
     }
     const int8_t* res_last = P.residual ? P.residual + (M - 1) * N : nullptr;     // a tile past the matrix reads its last row
-    auto issue_res_one = [&](const int8_t* base, int rows, uint32_t dst, int i) __attribute__((always_inline)) {      // rows >= 1
-        if (rows >= 32) dma16(base, rs_off[i], dst + i * 1024);
-        else dma16(base, (uint32_t)(min(rs_row[i], rows - 1) * N + rs_col[i]), dst + i * 1024);
+    auto issue_res_one = [&](const Span& sp, uint32_t dst, int i) __attribute__((always_inline)) {
+        dma16(sp.base, (uint32_t)(__mul24(min(rs_row[i], sp.last), N) + rs_col[i]), dst + i * 1024);
     };
     // transposing read of the residual tile: in every block of 16 lanes the even lanes name eight 8-byte rows and lanes
     // 0-7 receive their columns, the odd lanes name eight more and lanes 8-15 receive theirs.  Lane L = 16 B + j is to
@@ -271,24 +285,21 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
 
     RS_STAMP(24);
     {
-        const Cursor c0 = cursor(P.x, P.ldx, 0, 0), c1 = cursor(P.x, P.ldx, 1, 0);
+        const Span s1 = span_of(cursor(P.x, P.ldx, 1, 0), x_last, SR);
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            issue_act_one(uniform_ptr(c0.p), (int)min<int64_t>(c0.rows, SR), xs_off, i);
-            issue_act_one(uniform_ptr(c1.p), (int)min<int64_t>(c1.rows, SR), xs_off + XT, i);
-        }
+        for (int i = 0; i < NI; ++i) issue_act_one(s1, xs_off + LY::stage_offset(1), i);
         if (EPI == EPI_RESIDUAL) {
-            const Cursor r0 = cursor(P.residual, N, 0, 32 * grp);
+            const Span r0 = span_of(cursor(P.residual, N, 0, 32 * grp), res_last, 32);
 #pragma unroll
-            for (int i = 0; i < RNI; ++i)
-                issue_res_one(uniform_ptr(r0.rows > 0 ? r0.p : res_last), (int)max<int64_t>(1, min<int64_t>(r0.rows, 32)), res_off, i);
+            for (int i = 0; i < RNI; ++i) issue_res_one(r0, res_off, i);
         }
     }
 
     // ---- requantisation constants (while the first activations are on their way).  With v = dot + bias the int8 result
-    // clamp8((v b + 2^(c-1)) >> c) is the same for all v >= Lp (127) and all v <= Ln (-127), Lp / Ln being the first v
-    // that reach +-127; so the dot product is limited to [Ln - bias, Lp - bias] first (one median of three), after
-    // which T = v b + 2^(c-1) lies in (-128 2^c, 128 2^c), T 2^(24-c) fits 32 bits and its top byte is the result: one
+    // clamp8((v b + h) >> c), h the rounding addend (2^(c-1), or 0 for the bare shift of Eq. 10), is the same for all
+    // v >= Lp (127) and all v <= Ln (-127), Lp / Ln being the first v that reach +-127; so the dot product is limited to
+    // [Ln - bias, Lp - bias] first (one median of three), after
+    // which T = v b + h lies in (-128 2^c, 128 2^c), T 2^(24-c) fits 32 bits and its top byte is the result: one
     // 24-bit multiply-add by b 2^(24-c), the addend (modulo 2^32) carrying bias and rounding.  Needs c <= 24,
     // b < 2^(c-1) and bounds within 24 bits.  Residual layers: the first term only has to be exact within
     // +-(127 + R2), R2 the largest magnitude of the residual term (<= 128 required), because beyond that the clamped
@@ -302,7 +313,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         const int64_t br = P.res_rq.b, cr = P.res_rq.c;
         bool res_ok = br >= 1 && br < (1 << 23) && cr >= 1 && cr <= 30;
         if (res_ok) {
-            const int64_t hr = (int64_t)1 << (cr - 1);
+            const int64_t hr = (int64_t)P.rnd << (cr - 1);
             const int64_t r2 = max((127 * br + hr) >> cr, -((-128 * br + hr) >> cr));
             res_ok = r2 <= 128;
             wlim = 127 + r2;
@@ -315,9 +326,10 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         int32_t lo = 0, hi = 0, mb = 0, ad = 0;
         bool ok = chan_24 && pc[cb] >= 1 && pc[cb] <= sh24 && pb[cb] >= 1 && pb[cb] < (1 << ((pc[cb] - 1) & 31));
         if (ok) {
-            const int64_t half = (int64_t)1 << (pc[cb] - 1), two_c = (int64_t)1 << pc[cb];
-            const int64_t Lp = (wlim * two_c - half + pb[cb] - 1) / pb[cb];
-            const int64_t Ln = -((wlim * two_c - half + 1 + pb[cb] - 1) / pb[cb]);
+            const int64_t half = (int64_t)P.rnd << (pc[cb] - 1), two_c = (int64_t)1 << pc[cb];
+            // (both numerators are below 256 * 2^24 = 2^32: unsigned 32-bit divisions, a fraction of the cost of 64-bit ones)
+            const int64_t Lp = (int64_t)((uint32_t)(wlim * two_c - half + pb[cb] - 1) / (uint32_t)pb[cb]);
+            const int64_t Ln = -(int64_t)((uint32_t)((wlim - 1) * two_c + 1 + half + pb[cb] - 1) / (uint32_t)pb[cb]);
             const int64_t l = Ln - pbias[cb], h = Lp - pbias[cb];
             ok = l >= -(1 << 23) && h < (1 << 23);
             lo = (int32_t)l; hi = (int32_t)h; mb = pb[cb] << (sh24 - pc[cb]);
@@ -328,12 +340,13 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     }
     if (EPI == EPI_GELU && tid < 256) {
         const int32_t I = (int32_t)(int8_t)tid;
-        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c);
+        gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c, P.rnd);
     }
     RS_STAMP(1);
-    wait_vm0();
+    // (no wait for the loads just requested: stage 0 landed before the first weight chunk was read, loads completing in
+    // order; stage 1 and the residual tile are first read after the barrier inside tile 0, which waits for them)
     const bool fast24 = __syncthreads_and(chan_24) != 0;
-    RS_STAMP(2);        // also: tiles 0 and 1 (and residual tile 0) are in LDS
+    RS_STAMP(2);
     if (!fast24) {                                              // the general form keeps the raw parameters instead
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) { c_lo[cb] = pb[cb]; c_hi[cb] = pc[cb]; c_mb[cb] = pbias[cb]; c_ad[cb] = 0; }
@@ -344,28 +357,33 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     // channels, half-block 8 s + 2 B + o = 2 NCB tb + cg being tokens 8 tb .. + 7, channels 16 cg .. + 15: lane
     // L = 16 B + 8 o + j receives token 8 tb + j (two transposing reads: channels 16 cg + 0..7, + 8..15) and stores 16
     // bytes of a row of y.
-    int st_src[NCB], st_tok[NCB];
+    int st_src[NCB];
     uint32_t st_dst[NCB];
 #pragma unroll
     for (int s = 0; s < NCB; ++s) {
         const int B = lane >> 4, o_src = lane & 1, b = (lane & 15) >> 1, o_dst = (lane >> 3) & 1, j = lane & 7;
         const int hs = 8 * s + 2 * B + o_src, hd = 8 * s + 2 * B + o_dst;
         st_src[s] = (16 * (hs % (2 * NCB)) + b) * OP + 8 * (hs / (2 * NCB));
-        // token of the tile this lane stores; 64 (never below the number of rows left) for channel tiles past the last one
-        st_tok[s] = n0w + 16 * (hd % (2 * NCB)) < N ? 8 * (hd / (2 * NCB)) + j : 64;
-        st_dst[s] = (uint32_t)((8 * (hd / (2 * NCB)) + j) * N + 16 * (hd % (2 * NCB)));
+        // where this lane's piece goes, relative to the tile's first row at the wavefront's first channel; pieces of
+        // channel tiles past the last one get an offset no buffer reaches
+        st_dst[s] = n0w + 16 * (hd % (2 * NCB)) < N ? (uint32_t)((8 * (hd / (2 * NCB)) + j) * N + 16 * (hd % (2 * NCB))) : 0x80000000u;
     }
     auto store_read = [&](int s, v2i& a, v2i& b) __attribute__((always_inline)) {
         a = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(out_w + st_src[s]));
         b = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(out_w + st_src[s] + 8 * OP));
     };
-    typedef v4i __attribute__((address_space(1))) gv4i;
-    // base: first row of the tile in y, at this wavefront's first channel (scalar); rows: rows of the tile that exist
-    auto store_write = [&](int8_t* base, int rows, int s, const v2i& a, const v2i& b) __attribute__((always_inline)) {
-        if (st_tok[s] < rows) *(gv4i*)(base + st_dst[s]) = v4i{a[0], a[1], b[0], b[1]};
+    // The rows of a tile that exist, from the wavefront's first channel on, as a buffer: a store past its end (a row
+    // that does not exist, a channel tile past the last one) is dropped by the hardware, so no lane is masked by hand.
+    auto tile_buffer = [&](const Cursor& c) __attribute__((always_inline)) {
+        int8_t* base = const_cast<int8_t*>(uniform_ptr(c.p + n0w));
+        const int rows = __builtin_amdgcn_readfirstlane(min(max(c.rows, 0), 32));
+        return __builtin_amdgcn_make_buffer_rsrc(base, 0, rows * N, 0x00020000);
+    };
+    auto store_write = [&](__amdgpu_buffer_rsrc_t buf, int s, const v2i& a, const v2i& b) __attribute__((always_inline)) {
+        __builtin_amdgcn_raw_buffer_store_b128(v4i{a[0], a[1], b[0], b[1]}, buf, (int)st_dst[s], 0, 0);
     };
 
-    const int32_t rb = P.res_rq.b, rc = P.res_rq.c, rh = 1 << ((P.res_rq.c - 1) & 31);
+    const int32_t rb = P.res_rq.b, rc = P.res_rq.c, rh = P.rnd << ((P.res_rq.c - 1) & 31);
 
     // one epilogue unit: the four outputs e = 4 d .. 4 d + 3 of channel tile cb -> one packed word
     auto unit_fast = [&](const v16i& a, int cb, int d, const v2i (&rw)[NCB][2]) __attribute__((always_inline)) -> int {
@@ -393,10 +411,10 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         const int32_t b = c_lo[cb], c = c_hi[cb], bias = c_mb[cb];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            int64_t r64 = rnd_shift64(a[4 * d + r] + bias, b, c);
+            int64_t r64 = rnd_shift64(a[4 * d + r] + bias, b, c, P.rnd);
             if (EPI == EPI_RESIDUAL) {
                 const int32_t res = (int32_t)(int8_t)((uint32_t)rw[cb][d >> 1][d & 1] >> (8 * r));
-                r64 += rnd_shift64(res, P.res_rq.b, P.res_rq.c);
+                r64 += rnd_shift64(res, P.res_rq.b, P.res_rq.c, P.rnd);
             }
             int32_t v = clamp8_64(r64);
             if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
@@ -410,14 +428,14 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         *reinterpret_cast<v4i*>(out_w + (32 * cb + lj) * OP + 16 * lg) = w4;
     };
 
-    // The stage of token tile k is buffer k % 3.  One barrier per tile, before the first fragments of tile k + 1 are
+    // The stage of token tile k is stage buffer k % 3.  One barrier per tile, before the first fragments of tile k + 1 are
     // read: wait for this wavefront's loads (all requested most of a tile earlier), barrier (now every wavefront's
     // loads of stage k + 1 have landed and nobody reads stage k - 1 any more); in the k-steps after it, one piece per
     // step: the stores of tile k - 1, the requests of stage k + 2 (into the buffer of k - 1) and of residual tile k + 1.
     const int a_base = (32 * grp + lj) * PITCH + 16 * lg;       // this lane's A fragment of k-step ks: + 32 ks
     v4i af[RG];
     {
-        const int8_t* xa = Xs + a_base;
+        const int8_t* xa = Xs + LY::stage_offset(0) + a_base;
 #pragma unroll
         for (int i = 0; i < RG - 1; ++i) af[i] = *reinterpret_cast<const v4i*>(xa + 32 * i);
     }
@@ -427,7 +445,8 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     Cursor c_req, c_res, c_out, c_prev;                         // stage being requested, residual tile being requested, tile k, tile k - 1
     int par = 0;                                                // residual tile k is in half `par` of the residual staging
 
-    // Token tile k in buffer b0 (b1 holds stage k + 1, b2 is free for stage k + 2): multiply into `cur`.  With one
+    // Token tile k in the stage buffer at offset b0 (the one at b1 holds stage k + 1, the one at b2 is free for stage
+    // k + 2): multiply into `cur`.  With one
     // wavefront per SIMD (GR == 1) there are two sets of accumulators and, when `ep`, `prev` (tile k - 1) is requantised
     // between the MFMAs, in the k-steps before the barrier, and stored after it.
     // With two wavefronts per SIMD (GR == 2) there is a single set: tile k is requantised right after its multiply, and
@@ -441,19 +460,16 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         v2i sa = {}, sb = {};
         if (EPI == EPI_RESIDUAL && ep && TWO_SETS) read_res(par ^ 1, rw);
         constexpr int FIRST = PH == 0 ? SYNC : 0;              // k-step of the first piece of the work that follows a barrier
-        const int8_t* xa = Xs + b0 * XT + a_base;
-        const int8_t* xb = Xs + b1 * XT + a_base;
+        const int8_t* xa = Xs + b0 + a_base;
+        const int8_t* xb = Xs + b1 + a_base;
         // this tile's scalars, pinned in scalar registers (recomputing them at every use would cost more instructions
         // than the loads and stores themselves)
-        const auto sc = [](int64_t v) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane((int)v); };
-        const int8_t* q_base = uniform_ptr(c_req.p);
-        int q_rows = sc(min<int64_t>(c_req.rows, SR));
-        uint32_t q_dst = (uint32_t)sc(xs_off + (PH == 0 ? b2 : b1) * XT);
-        const int8_t* r_base = EPI == EPI_RESIDUAL ? uniform_ptr(c_res.rows > 0 ? c_res.p : res_last) : nullptr;
-        int r_rows = sc(max<int64_t>(1, min<int64_t>(c_res.rows, 32)));
-        uint32_t r_dst = (uint32_t)sc(res_off + (par ^ 1) * RT);
-        int8_t* y_base = const_cast<int8_t*>(uniform_ptr(c_prev.p + n0w));
-        int y_rows = sc(max<int64_t>(0, min<int64_t>(c_prev.rows, 32)));
+        const auto sc = [](int v) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(v); };
+        const Span q_span = span_of(c_req, x_last, SR);
+        const uint32_t q_dst = (uint32_t)sc(xs_off + (PH == 0 ? b2 : b1));
+        const Span r_span = EPI == EPI_RESIDUAL ? span_of(c_res, res_last, 32) : Span{nullptr, 0};
+        const uint32_t r_dst = (uint32_t)sc(res_off + (par ^ 1) * RT);
+        const __amdgpu_buffer_rsrc_t y_buf = tile_buffer(c_prev);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             if (PH == 0 && ks == SYNC) {
@@ -486,10 +502,10 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
             }
             if (ks >= FIRST) {
                 const int j = ks - FIRST;
-                if (ep && j >= 1 && j <= NCB) store_write(y_base, y_rows, j - 1, sa, sb);
+                if (ep && j >= 1 && j <= NCB) store_write(y_buf, j - 1, sa, sb);
                 if (ep && j < NCB) store_read(j, sa, sb);
-                if (j < NI) issue_act_one(q_base, q_rows, q_dst, j);
-                if (EPI == EPI_RESIDUAL && j < RNI) issue_res_one(r_base, r_rows, r_dst, j);     // past the last tile: a repeat, never used
+                if (j < NI) issue_act_one(q_span, q_dst, j);
+                if (EPI == EPI_RESIDUAL && j < RNI) issue_res_one(r_span, r_dst, j);     // past the last tile: a repeat, never used
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -512,7 +528,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         }
         // on to tile k + 1
         c_prev = c_out;
-        c_out.p += n_step; c_out.rows -= row_step;
+        advance(c_out, n_step);
         advance(c_req, x_step);
         advance(c_res, n_step);
         par ^= 1;
@@ -533,11 +549,12 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
                 if (d == 3) put_out(cb, ow[cb]);
             }
         }
+        const __amdgpu_buffer_rsrc_t y_buf = tile_buffer(c_prev);
 #pragma unroll
         for (int s = 0; s < NCB; ++s) {
             v2i a, b;
             store_read(s, a, b);
-            store_write(const_cast<int8_t*>(uniform_ptr(c_prev.p)) + n0w, (int)max<int64_t>(0, min<int64_t>(c_prev.rows, 32)), s, a, b);
+            store_write(y_buf, s, a, b);
         }
     };
     auto start = [&](int ahead) __attribute__((always_inline)) {
@@ -549,10 +566,10 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     };
     auto run_one_set = [&]<bool fast, int PH>() __attribute__((always_inline)) {
         start(PH == 0 ? 2 : 1);
-        tile_step.template operator()<false, fast, PH>(0, 1, 2, accA, accA);
+        tile_step.template operator()<false, fast, PH>(LY::stage_offset(0), LY::stage_offset(1), LY::stage_offset(2), accA, accA);
         RS_STAMP(3);
-        int b0 = 1, b1 = 2, b2 = 0;
-        for (int64_t k = 1; k < ntile; ++k) {
+        int b0 = LY::stage_offset(1), b1 = LY::stage_offset(2), b2 = LY::stage_offset(0);
+        for (int k = 1; k < ntile; ++k) {
             tile_step.template operator()<true, fast, PH>(b0, b1, b2, accA, accA);
             RS_STAMP(3 + k);
             const int t = b0; b0 = b1; b1 = b2; b2 = t;
@@ -566,10 +583,10 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
             return;
         }
         start(2);
-        tile_step.template operator()<false, fast, 0>(0, 1, 2, accA, accB);
+        tile_step.template operator()<false, fast, 0>(LY::stage_offset(0), LY::stage_offset(1), LY::stage_offset(2), accA, accB);
         RS_STAMP(3);
-        int b0 = 1, b1 = 2, b2 = 0;
-        for (int64_t k = 1; k < ntile; k += 2) {
+        int b0 = LY::stage_offset(1), b1 = LY::stage_offset(2), b2 = LY::stage_offset(0);
+        for (int k = 1; k < ntile; k += 2) {
             tile_step.template operator()<true, fast, 0>(b0, b1, b2, accB, accA);
             RS_STAMP(3 + k);
             { const int t = b0; b0 = b1; b1 = b2; b2 = t; }
@@ -597,8 +614,8 @@ template <int KS, int NCB, int GR>
 hipError_t launch_rs_epi(hipStream_t s, RsParams& P, const LinearArgs& a) {
     const int nt = a.N / 32;
     P.slabs = (nt + 4 * NCB - 1) / (4 * NCB);
-    P.stages = (a.M + 32 * GR - 1) / (32 * GR);
-    P.q = (int)std::max<int64_t>(1, std::min<int64_t>(P.stages, num_cus() / P.slabs));
+    P.stages = (int)((a.M + 32 * GR - 1) / (32 * GR));
+    P.q = std::max(1, std::min(P.stages, num_cus() / P.slabs));
     const int grid = P.q * P.slabs;
     if (a.residual) return launch_rs<EPI_RESIDUAL, KS, NCB, GR>(s, P, grid);
     if (a.gelu) return launch_rs<EPI_GELU, KS, NCB, GR>(s, P, grid);
@@ -608,10 +625,12 @@ hipError_t launch_rs_epi(hipStream_t s, RsParams& P, const LinearArgs& a) {
 }  // namespace
 
 // Shapes this kernel takes: K = 384 or 768 (the weights of a wavefront must fit its registers, and the k-steps are
-// unrolled), N a multiple of 32, dense rows; offsets inside the weight matrix and inside a token tile are 32-bit.
+// unrolled), N a multiple of 32, dense rows, at most 2^30 of them; offsets inside the weight matrix and inside a token
+// tile are 32-bit.
 bool linear_rs_takes(const LinearArgs& a) {
     if (a.K != 384 && a.K != 768) return false;
     if ((int64_t)a.N * a.K > 0x7fffffffLL) return false;
+    if (a.M > (1 << 30)) return false;                         // row counts are kept in 32 bits
     return (a.N & 31) == 0 && (a.ldx == 0 || a.ldx == a.K) && a.M >= 1;
 }
 
@@ -625,7 +644,7 @@ hipError_t launch_linear_rs(hipStream_t s, const LinearArgs& a) {
     RsParams P;
     P.x = a.x; P.w = a.w; P.bias = a.bias; P.rq_b = a.rq_b; P.rq_c = a.rq_c;
     P.residual = a.residual; P.res_rq = a.res_rq; P.gelu_p = a.gelu_p; P.gelu_rq = a.gelu_rq;
-    P.y = a.y; P.M = a.M; P.N = a.N; P.ldx = a.K;
+    P.y = a.y; P.M = a.M; P.N = a.N; P.ldx = a.K; P.rnd = a.floor_shift ? 0 : 1;
     // K = 384: 64 channels per wavefront leave room for two wavefronts per SIMD; K = 768: one
     if (a.K == 384) return launch_rs_epi<12, 2, 2>(s, P, a);
     return launch_rs_epi<24, 2, 1>(s, P, a);

@@ -17,10 +17,16 @@ constexpr int kWave = 64;
 
 __device__ __forceinline__ int32_t clamp8(int32_t v) { return min(max(v, -127), 127); }
 
-// round(b * v / 2^c) half up, full 64-bit product (Eq. 8 realised as Eq. 10); any 1 <= c <= 62.
-__device__ __forceinline__ int64_t rnd_shift64(int32_t v, int32_t b, int32_t c) {
+// 64-bit minimum / maximum as a compare and a select (the min / max templates of the HIP headers, instantiated for
+// int64_t, go through double precision).
+__device__ __forceinline__ int64_t min64(int64_t a, int64_t b) { return a < b ? a : b; }
+__device__ __forceinline__ int64_t max64(int64_t a, int64_t b) { return a > b ? a : b; }
+
+// (b v + rnd 2^(c-1)) >> c with the full 64-bit product; any 1 <= c <= 62.  rnd = 1: round(b v / 2^c) half up (Eq. 8
+// realised as Eq. 10, the reading used throughout); rnd = 0: the bare shift of Eq. 10 as printed, floor(b v / 2^c).
+__device__ __forceinline__ int64_t rnd_shift64(int32_t v, int32_t b, int32_t c, int32_t rnd = 1) {
     int64_t p = (int64_t)v * (int64_t)b;
-    return (p + ((int64_t)1 << (c - 1))) >> c;
+    return (p + ((int64_t)rnd << (c - 1))) >> c;
 }
 
 __device__ __forceinline__ int32_t clamp8_64(int64_t v) {
@@ -29,8 +35,8 @@ __device__ __forceinline__ int32_t clamp8_64(int64_t v) {
     return (int32_t)v;
 }
 
-__device__ __forceinline__ int32_t requant64(int32_t v, int32_t b, int32_t c) {
-    return clamp8_64(rnd_shift64(v, b, c));
+__device__ __forceinline__ int32_t requant64(int32_t v, int32_t b, int32_t c, int32_t rnd = 1) {
+    return clamp8_64(rnd_shift64(v, b, c, rnd));
 }
 
 // round(b v / 2^c) when 1 <= c <= 31 and 1 <= b <= 2^c (a rescale by at most 1, so the result fits 32 bits):
@@ -38,8 +44,8 @@ __device__ __forceinline__ int32_t requant64(int32_t v, int32_t b, int32_t c) {
 __device__ __forceinline__ bool dyadic_fits32(int32_t b, int32_t c) {
     return c >= 1 && c <= 31 && b >= 1 && (uint32_t)b <= (1u << c);
 }
-__device__ __forceinline__ int32_t rnd_shift_fit32(int32_t v, int32_t b, int32_t c) {
-    const int64_t p = (int64_t)v * b + (int64_t)(1u << (c - 1));
+__device__ __forceinline__ int32_t rnd_shift_fit32(int32_t v, int32_t b, int32_t c, int32_t rnd = 1) {
+    const int64_t p = (int64_t)v * b + (int64_t)((uint32_t)rnd << (c - 1));
     return (int32_t)__builtin_amdgcn_alignbit((uint32_t)(p >> 32), (uint32_t)p, c);
 }
 

@@ -27,6 +27,7 @@ struct LinearArgs {
     int8_t* y; int64_t M; int N; int K;
     int64_t ldx;                         // bytes between rows of x; 0 means K (dense rows)
     int kernel;                          // 0: chosen from the shape; otherwise one of LinearKernel, forced (tests, measurements)
+    int floor_shift;                     // 0: requantisations round to nearest (Eq. 8 through Eq. 10); 1: bare shift of Eq. 10 (floor)
 };
 enum LinearKernel { LINEAR_AUTO = 0, LINEAR_MANY_ROWS = 1, LINEAR_REG_STATIONARY = 2 };
 hipError_t launch_linear(hipStream_t s, const LinearArgs& a);
@@ -46,6 +47,7 @@ struct AttentionArgs {
     int B, T, C, H;
     Dyadic qk_rq; ShiftParams sm; Dyadic pv_rq;
     int8_t* tap_scores; int8_t* tap_probs;
+    int floor_shift;                     // as LinearArgs::floor_shift, for both requantisations (scores, output)
 };
 hipError_t launch_attention(hipStream_t s, const AttentionArgs& a);
 

@@ -232,6 +232,14 @@ def test_linear_options_and_probe_arguments(lib):
                                                       kw.get("M", 8), kw.get("N", 64), kw.get("K", 384),
                                                       None if opt is None else C.byref(binding.LinearOptions(opt)))
     assert ex(3) == E["PARAM"] and ex(-1) == E["PARAM"]
+    bad_round = binding.LinearOptions(0, 2)
+    assert lib.ivit_linear_requant_ex(None, FAKE, FAKE, None, FAKE, FAKE, None, DY, None, DY, FAKE, 8, 64, 384, C.byref(bad_round)) == E["PARAM"]
+    good = binding.Dims(2, 65, 64, 2, 256)
+    wa = lambda opt: lib.ivit_window_attention_ex(None, FAKE, None, None, 1, None, 1, FAKE, C.byref(good), DY, SP, DY, None, None, opt)
+    assert wa(C.byref(binding.AttentionOptions(2))) == E["PARAM"] and wa(C.byref(binding.AttentionOptions(-1))) == E["PARAM"]
+    empty = binding.Dims(0, 65, 64, 2, 256)
+    assert lib.ivit_window_attention_ex(None, None, None, None, 1, None, 1, None, C.byref(empty), DY, SP, DY, None, None,
+                                        C.byref(binding.AttentionOptions(1))) == 0
     # the register-stationary kernel takes K = 384 or 768 with N % 32 == 0 and nothing else
     assert ex(2, K=512) == E["SHAPE"] and ex(2, N=48) == E["SHAPE"] and ex(2, K=1536) == E["SHAPE"]
     assert ex(2, M=0) == 0 and ex(0, M=0) == 0 and ex(None, M=0) == 0 and ex(1, M=0, K=512) == 0

@@ -241,8 +241,16 @@ def test_linear_requant(ivit, dense_path, M, N, K, epi):
     assert_same(host(y), orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o), "linear %s" % epi)
 
 
-def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit, dense_path):
+@pytest.fixture(params=[None, "floor"])
+def rounding(request):
+    """None: the entry point's own rounding (to nearest); "floor": the bare shift of Eq. 10, an option of the _ex entry
+    points, compared with the oracle's floor mode."""
+    return request.param
+
+
+def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit, dense_path, rounding):
     """Multipliers and shifts outside the 15-bit fast range take the 64-bit path, channel by channel."""
+    fs = rounding == "floor"
     rng = np.random.default_rng(42)
     M, N, K = 200, 96, 128
     x = synth.make_rows(1, M, K, "uniform")
@@ -257,8 +265,8 @@ def test_linear_requant_general_dyadic_pairs_and_no_bias(ivit, dense_path):
     for kw_o, kw_g in (({}, {}), (dict(residual=res, res_rq=(2 ** 31 - 1, 31)), dict(residual=dev(res), res_rq=(2 ** 31 - 1, 31))),
                        (dict(residual=res, res_rq=(3, 1)), dict(residual=dev(res), res_rq=(3, 1))), (gl, gl)):
         y = empty((M, N))
-        ivit.ivit_linear_requant(dev(x), dev(w), None, dev(rq_b), dev(rq_c), y, kernel=dense_path, **kw_g)
-        want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
+        ivit.ivit_linear_requant(dev(x), dev(w), None, dev(rq_b), dev(rq_c), y, kernel=dense_path, rounding=rounding, **kw_g)
+        want = orc.linear_requant(x, w, None, rq_b, rq_c, floor_shift=fs, **kw_o)
         assert_same(host(y), want, "linear general")
         assert np.abs(want.astype(np.int32)).mean() > 2
 
@@ -282,7 +290,7 @@ def test_linear_requant_largest_accumulators(ivit, dense_path):
 
 
 @pytest.mark.parametrize("K", [128, 1536, 384, 768])
-def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K):
+def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K, rounding):
     """Per-channel parameters at and around the limits of the 24-bit requantisation (shift 1..24, multiplier just
     below and at 2^(c-1), biases that push the clamp bounds to and past 24 bits), on operands that drive the
     accumulators to both saturated ends (K * 127^2 exceeds 2^23 for the larger K) and through the whole range.
@@ -290,6 +298,7 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
     run on the kernel that keeps the weights in registers as well (its workgroups span 384 or 256 channels)."""
     if K in (384, 768) and dense_path == "many_rows":
         dense_path = "reg_stationary"
+    fs = rounding == "floor"
     rng = np.random.default_rng(K)
     M, N = 333, 64 * 10
     x = synth.make_rows(K, M, K, "uniform")
@@ -322,8 +331,8 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
     gl = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21))
     for kw in ({}, gl):
         y = empty((M, N))
-        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, kernel=dense_path, **kw)
-        want = orc.linear_requant(x, w, bias, b, c, **kw)
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, kernel=dense_path, rounding=rounding, **kw)
+        want = orc.linear_requant(x, w, bias, b, c, floor_shift=fs, **kw)
         assert_same(host(y), want, "linear at the limits of the narrow path" + (" + gelu" if kw else ""))
     plain = orc.linear_requant(x, w, bias, b, c)
     assert (plain == 127).mean() > 0.02 and (plain == -127).mean() > 0.02 and (np.abs(plain) < 127).mean() > 0.3
@@ -334,9 +343,38 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
     for rq in ((2 ** 15, 15), (2 ** 15 - 1, 15), (2 ** 15 + 1, 15), (33000, 15), (2 ** 23 - 1, 23), (2 ** 23, 23),
                (2 ** 23 - 1, 30), (5, 31), (1, 1), (3, 2), (23456, 15)):
         y = empty((M, N))
-        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, residual=dev(res), res_rq=rq, kernel=dense_path)
-        want = orc.linear_requant(x, w, bias, b, c, residual=res, res_rq=rq)
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(b), dev(c), y, residual=dev(res), res_rq=rq, kernel=dense_path,
+                                 rounding=rounding)
+        want = orc.linear_requant(x, w, bias, b, c, residual=res, res_rq=rq, floor_shift=fs)
         assert_same(host(y), want, "linear + residual at the limits of the narrow path, residual pair %s" % (rq,))
+
+
+# Eq. 10 as a bare shift: every epilogue of every Dense kernel (few rows, tiled, weights in LDS, weights in registers)
+FLOOR_SHAPES = [(65, 192, 64, None), (5, 7, 80, None), (1000, 384, 384, "many_rows"), (300, 384, 1536, "many_rows"),
+                (257, 130, 3072, "many_rows"), (333, 208, 96, "many_rows"), (30011, 128, 384, None),
+                (1000, 1152, 384, "reg_stationary"), (4100, 384, 384, "reg_stationary"), (515, 256, 768, "reg_stationary")]
+
+
+@pytest.mark.parametrize("M,N,K,kernel", FLOOR_SHAPES)
+@pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
+def test_linear_requant_floor_mode(ivit, M, N, K, kernel, epi):
+    x = synth.make_rows(M + N + K, M, K, "normal", 32.0)
+    w, bias, rq_b, rq_c = synth.make_linear(M * 7 + N, N, K)
+    x[0, :5] = -128; w[-1, -1] = -128
+    kw_o, kw_g = {}, {}
+    if epi == "residual":
+        res = synth.make_rows(N + 1, M, N, "uniform")
+        kw_o = dict(residual=res, res_rq=(23456, 15)); kw_g = dict(residual=dev(res), res_rq=(23456, 15))
+    elif epi == "gelu":
+        kw_o = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)); kw_g = dict(kw_o)
+    y = empty((M, N))
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, kernel=kernel, rounding="floor", **kw_g)
+    want = orc.linear_requant(x, w, bias, rq_b, rq_c, floor_shift=True, **kw_o)
+    assert_same(host(y), want, "linear %s, floor" % epi)
+    assert (want != orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o)).mean() > 0.05      # the modes really differ
+    y2 = empty((M, N))                                                                      # and "nearest" through the option
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y2, kernel=kernel, rounding="nearest", **kw_g)
+    assert_same(host(y2), orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o), "linear %s, nearest through the option" % epi)
 
 
 # the kernel that keeps the weights in registers (K = 384 / 768): row counts around the 32-token tiles and around the
@@ -427,20 +465,48 @@ def test_attention(ivit, name, B, over):
     ((3, 24), (24001, 21)),                     # bounds of the 24-bit form beyond 24 bits (tiny multiplier)
     ((37, 10), (5, 4)),                         # small shifts
 ])
-def test_attention_dyadic_pair_regimes(ivit, qk, pv):
+def test_attention_dyadic_pair_regimes(ivit, qk, pv, rounding):
+    fs = rounding == "floor"
     cfg = synth.CONFIGS["c0_tiny"]
     d = synth.dims_of(cfg, 2)
     qkv = synth.make_rows(3, 2 * cfg["T"], 3 * cfg["C"], "normal", 50.0)
     qkv[:4] = 127; qkv[4:8] = -127              # saturating dot products on both sides
     sm = synth.shift_params(12)
-    want, _, pr_ref = orc.attention(qkv, d, qk, sm, pv, want_taps=True)
+    want, _, pr_ref = orc.attention(qkv, d, qk, sm, pv, want_taps=True, floor_shift=fs)
     o = empty((2 * cfg["T"], cfg["C"]))
-    ivit.ivit_attention(dev(qkv), o, d, qk, sm, pv)
+    att = (lambda *a, **kw: ivit.ivit_window_attention(*a, None, None, rounding="floor", **kw)) if fs else ivit.ivit_attention
+    att(dev(qkv), o, d, qk, sm, pv)
     assert_same(host(o), want, "attention, pair regime")
     pr = empty(pr_ref.shape)
-    ivit.ivit_attention(dev(qkv), o, d, qk, sm, pv, tap_probs=pr)
+    att(dev(qkv), o, d, qk, sm, pv, tap_probs=pr)
     assert_same(host(pr), pr_ref, "attention probabilities, pair regime")
     assert_same(host(o), want, "attention with taps, pair regime")
+
+
+@pytest.mark.parametrize("name,B", [("c0_tiny", 2), ("c2_deit_s", 2), ("c4_swin_t", 5), ("c3_vit_b", 1)])
+def test_attention_floor_mode(ivit, name, B):
+    """Eq. 10 as a bare shift in both requantisations of the attention layer (scores, output), with and without taps."""
+    cfg = synth.CONFIGS[name]
+    d = synth.dims_of(cfg, B)
+    blk = synth.make_block(cfg, 0)
+    qkv = synth.make_rows(B + cfg["T"], B * cfg["T"], 3 * cfg["C"], "normal", 32.0)
+    qkv[0, :6] = -128; qkv[-1, -6:] = -128
+    rb = None if blk["rel_bias"] is None else dev(blk["rel_bias"])
+    o_ref, sc_ref, pr_ref = orc.attention(qkv, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], blk["rel_bias"], want_taps=True,
+                                          floor_shift=True)
+    o = empty((B * cfg["T"], cfg["C"]))
+    ivit.ivit_window_attention(dev(qkv), o, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], rb, None, rounding="floor")
+    assert_same(host(o), o_ref, "attention out, floor")
+    sc = empty(sc_ref.shape); pr = empty(pr_ref.shape); o2 = empty(o.shape)
+    ivit.ivit_window_attention(dev(qkv), o2, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], rb, None, tap_scores=sc, tap_probs=pr,
+                               rounding="floor")
+    assert_same(host(sc), sc_ref, "scores, floor")
+    assert_same(host(pr), pr_ref, "probs, floor")
+    assert_same(host(o2), o_ref, "attention out with taps, floor")
+    assert (o_ref != orc.attention(qkv, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], blk["rel_bias"])).mean() > 0.02
+    o3 = empty(o.shape)
+    ivit.ivit_window_attention(dev(qkv), o3, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], rb, None, rounding="nearest")
+    assert_same(host(o3), orc.attention(qkv, d, blk["qk_rq"], blk["softmax"], blk["pv_rq"], blk["rel_bias"]), "nearest through the option")
 
 
 # ------------------------------------------------------------------ encoder block with every intermediate tensor

@@ -767,3 +767,49 @@ def test_floor_requantisation_differs_from_the_rounded_one_by_at_most_one_step()
         assert d.min() == 0 and d.max() == 1 and 0.4 < d.mean() < 0.6
         frac = [Fraction(int(x) * b, 2 ** c) for x in v[:200]]
         assert floored[:200].tolist() == [math.floor(f) for f in frac]
+
+
+def test_floor_mode_of_the_dense_layer_and_of_attention_against_exact_fractions():
+    """The selectable other reading of Eq. 10 (a bare shift): every requantisation of the layer is floor(b v / 2^c),
+    checked element by element with exact rationals; with all products exact multiples of 2^c both modes coincide."""
+    rng = np.random.default_rng(91)
+    M, N, K = 5, 7, 16
+    x = rng.integers(-128, 128, (M, K)).astype(np.int8)
+    w = rng.integers(-128, 128, (N, K)).astype(np.int8)
+    bias = rng.integers(-3000, 3000, N).astype(np.int32)
+    b = rng.integers(200, 16000, N).astype(np.int32)
+    c = rng.integers(15, 22, N).astype(np.int32)
+    res = rng.integers(-128, 128, (M, N)).astype(np.int8)
+    acc = x.astype(np.int64) @ w.astype(np.int64).T + bias
+    fl = lambda v, bb, cc: math.floor(Fraction(int(v) * int(bb), 2 ** int(cc)))
+    clamp = lambda v: max(-127, min(127, v))
+    got = orc.linear_requant(x, w, bias, b, c, floor_shift=True)
+    assert got.tolist() == [[clamp(fl(acc[m, j], b[j], c[j])) for j in range(N)] for m in range(M)]
+    rq = (23456, 15)
+    got = orc.linear_requant(x, w, bias, b, c, residual=res, res_rq=rq, floor_shift=True)
+    assert got.tolist() == [[clamp(fl(acc[m, j], b[j], c[j]) + fl(res[m, j], *rq)) for j in range(N)] for m in range(M)]
+    assert not np.array_equal(got, orc.linear_requant(x, w, bias, b, c, residual=res, res_rq=rq))
+    # ShiftGELU between the layers: only its output requantisation changes with the mode
+    p, grq = synth.shift_params(32), (24171, 21)
+    plain = orc.linear_requant(x, w, bias, b, c, floor_shift=True)
+    raw = orc.shiftgelu_raw(plain, p).astype(np.int64)
+    got = orc.linear_requant(x, w, bias, b, c, gelu=p, gelu_rq=grq, floor_shift=True)
+    assert got.tolist() == [[clamp(fl(raw[m, j], *grq)) for j in range(N)] for m in range(M)]
+    # b v a multiple of 2^c everywhere: nothing to round, the modes agree
+    same = orc.linear_requant(x, w, None, np.full(N, 1 << 10, np.int32), np.full(N, 10, np.int32), floor_shift=True)
+    assert np.array_equal(same, orc.linear_requant(x, w, None, np.full(N, 1 << 10, np.int32), np.full(N, 10, np.int32)))
+
+    # attention: scores and output requantised by floor, Shiftmax untouched
+    d = dict(B=1, T=5, C=8, H=2, F=16)
+    qkv = rng.integers(-128, 128, (5, 24)).astype(np.int8)
+    qk, pv, sm = (1234, 14), (300, 15), synth.shift_params(32)
+    o, sc, pr = orc.attention(qkv, d, qk, sm, pv, want_taps=True, floor_shift=True)
+    for h in range(2):
+        q = qkv[:, 4 * h:4 * h + 4].astype(np.int64); k = qkv[:, 8 + 4 * h:12 + 4 * h].astype(np.int64)
+        v = qkv[:, 16 + 4 * h:20 + 4 * h].astype(np.int64)
+        s_want = [[clamp(fl(t, *qk)) for t in row] for row in (q @ k.T)]
+        assert sc[0, h].tolist() == s_want
+        assert np.array_equal(pr[0, h], orc.shiftmax(np.array(s_want, np.int8), sm))
+        o_want = [[clamp(fl(t, *pv)) for t in row] for row in (pr[0, h].astype(np.int64) @ v)]
+        assert o[:, 4 * h:4 * h + 4].tolist() == o_want
+    assert not np.array_equal(sc, orc.attention(qkv, d, qk, sm, pv, want_taps=True)[1])
