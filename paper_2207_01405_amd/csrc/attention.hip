@@ -2,16 +2,18 @@
 // pipeline of Sec. 3.2 and Shiftmax of Sec. 3.3 / Algorithm 1):
 //   A = requant(Q K^T) [+ relative-position bias];  P = Shiftmax(rows of A);  O = requant(P V).
 //
-// One workgroup (4 wavefronts) handles one (image-or-window, head) at a time: K and a transposed copy
-// of V live in LDS, and each wavefront takes 16 query tokens at a time.  Scores are produced by
+// One workgroup (4 wavefronts) handles one (image-or-window, head) at a time: K and V live in LDS, both
+// row by row as they come from memory, and each wavefront takes 16 query tokens at a time.  Scores are produced by
 // v_mfma_i32_16x16x64_i8 (d = 64) or 16x16x32 (d = 32) in the orientation keys x queries, so that a lane
 // holds, for ONE query, four keys of every 16-key tile: the whole score row of a query sits in the
 // registers of four lanes.  Max and sum need an in-lane pass plus two cross-lane steps; ShiftExp is a
 // table lookup on Delta = max - value (at most 510); the packed int8 probabilities are already laid out as
 // the MFMA "B" operand (contraction index = key) of O^T = V^T P^T, so scores and probabilities never
-// leave registers.  The key order inside each 64-key chunk of the V^T rows is permuted when V is
-// written to LDS to match that register layout, and the rows (head features) are permuted so that a
-// lane ends up with d/4 consecutive features of its query: one 16-byte (d = 64) store.
+// leave registers.  The "A" operand of that product, V^T, is read from the rows of V with the transposing
+// LDS read of gfx950 (ds_read_b64_tr_b8): the lanes of a 16-lane block name eight key rows each for the even and
+// the odd lanes, so the key order the register layout asks for and the choice of features are a matter of which
+// addresses the lanes name, and V needs no rearranging when it is written.  One exchange between neighbouring
+// lane blocks then gives every lane d/4 consecutive features of its query: one 16-byte (d = 64) store.
 //
 // The kernel is bound by the vector ALU (about a dozen integer operations per score element against
 // 2 d multiply-accumulates on the matrix core), so the per-element path is kept minimal: debug taps, the
@@ -27,11 +29,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int ATT_WAVES = 4, ATT_THREADS = 64 * ATT_WAVES;   // wavefronts per workgroup
 
-// position of key k inside a V^T row: 64-key chunk c = k / 64; inside it lane group g = (k % 16) / 4 owns
-// 16 consecutive bytes ordered by tile (k / 16) % 4, then k % 4
-__device__ __forceinline__ int vt_pos(int k) {
-    return (k & ~63) + ((k >> 2) & 3) * 16 + ((k >> 4) & 3) * 4 + (k & 3);
-}
+typedef int v2i_att __attribute__((ext_vector_type(2)));
 
 // Constants of the 24-bit requantisation of one per-tensor dyadic pair (no bias): the accumulator is limited to
 // [lo, hi], the first values that give -127 / +127, after which (v b + 2^(c-1)) 2^(24-c) fits 32 bits with the int8
@@ -53,10 +51,26 @@ __device__ __forceinline__ int32_t requant8(int32_t v, Dyadic d, Narrow n, int32
     return FAST ? clamp8(rnd_shift_fit32(v, d.b, d.c, rnd)) : requant64(v, d.b, d.c, rnd);
 }
 
+// Four values at once: the four medians first, then the four multiply-adds, so that no instruction reads the result of
+// the asm statement right before it (the compiler, not knowing what the statement is, would put a wait state there).
+template <int FAST>
+__device__ __forceinline__ void requant8x4(int32_t (&v)[4], Dyadic d, Narrow n, int32_t rnd) {
+    if (FAST == 2) {
+        int32_t m[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) asm("v_med3_i32 %0, %1, %2, %3" : "=v"(m[r]) : "v"(v[r]), "v"(n.lo), "v"(n.hi));
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = (__mul24(m[r], n.mb) + n.ad) >> 24;
+    } else {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = requant8<FAST>(v[r], d, n, rnd);
+    }
+}
+
 // FAST: both dyadic pairs are rescales by at most 1 with c <= 31 (32-bit requantisation) and the row sum always
 // exceeds 2^(k_out-1), so that IntDiv is one multiply-high by the pre-shifted reciprocal.
-// TFIX: 0, or the token count known at compile time (49, the 7 x 7 windows): every test of a key or query against T then
-// folds, and the fifteen absent keys of the last key tile cost nothing.
+// TFIX: 0, or the token count known at compile time (49, the 7 x 7 windows; 197, the 14 x 14 patches with a class token):
+// every test of a key or query against T then folds, and the absent keys of the last key tile cost nothing.
 template <int D, int NKT, bool TAPS, bool BIAS, bool MASK, int FAST, int TFIX = 0>
 __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t* __restrict__ qkv,
                                                         const int8_t* __restrict__ rel_bias,
@@ -68,22 +82,22 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
     const int T = TFIX ? TFIX : T_arg;
     constexpr int KROW = D + 16;                  // K row pitch (bytes)
     constexpr int NKC = (NKT + 3) / 4;            // 64-key chunks of the P V contraction
-    constexpr int VROW = NKC * 64 + 16;           // V^T row pitch (bytes)
+    constexpr int VP = D == 64 ? 72 : 40;         // V row pitch (bytes): the transposing reads below meet no bank twice
     constexpr int ND = D / 16;                    // 16-feature tiles of the output
     constexpr int DCH = D / 16;                   // 16-byte chunks per K / V row
     __shared__ __align__(16) int8_t Ks[NKT * 16 * KROW];
-    __shared__ __align__(16) int8_t Vt[D * VROW];
+    __shared__ __align__(16) int8_t Vs[NKC * 64 * VP];
     // table of ShiftExp(-delta): int8 scores give delta <= 254; with a bias and the mask the exact range is wider,
     // and beyond the table the value is 0 whenever it can occur (see the mask comment below)
     constexpr int NLUT = MASK ? 1024 : (BIAS ? 512 : 256);
-    __shared__ uint16_t lut[NLUT];
+    __shared__ uint32_t lut[NLUT];                // (whole words: the value comes out of the read ready to use)
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int li = lane & 15, lg = lane >> 4;
-    for (int i = tid; i < NLUT; i += ATT_THREADS) lut[i] = (uint16_t)shiftexp(-i, sm.i0, sm.n_shift);
+    // (the ShiftExp table is filled inside the first item, once its loads of K, V and Q are on their way)
     // keys beyond the 16-key tiles but inside the last 64-key chunk multiply probabilities that are zero;
-    // clear them once so that no uninitialised LDS is ever read
-    for (int i = tid; i < D * VROW / 4; i += ATT_THREADS) reinterpret_cast<uint32_t*>(Vt)[i] = 0u;
+    // clear their rows once so that no uninitialised LDS is ever read
+    for (int i = NKT * 16 * VP / 4 + tid; i < NKC * 64 * VP / 4; i += ATT_THREADS) reinterpret_cast<uint32_t*>(Vs)[i] = 0u;
 
     const int sh = sm.m_bits - (sm.k_out - 1);
     const uint32_t top = (1u << (sm.k_out - 1)) - 1u;
@@ -111,7 +125,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             const int key = min((tid + ATT_THREADS * it) / DCH, T - 1);
             kv[it] = r0 + (int)min((uint32_t)tr[key], (uint32_t)(tpi - 1));
         }
-        qr = r0 + (int)min((uint32_t)tr[min((work % split + split * wv) * 16 + li, T - 1)], (uint32_t)(tpi - 1));
+        qr = r0 + (int)min((uint32_t)tr[min((work % split + split * ((wv + item) % ATT_WAVES)) * 16 + li, T - 1)], (uint32_t)(tpi - 1));
     };
     // a work item is one (window, head) or, with split > 1, every split-th query tile of it: when there are too few
     // (window, head) pairs to give every workgroup slot of the device one, each pair is shared by `split` workgroups
@@ -121,7 +135,10 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 
     for (int work = first; work < n_work; work += G) {
         const int item = work / split, part = work % split;
-        const int qt0 = part + split * wv;         // this wavefront's first query tile
+        // this wavefront's first query tile.  The tiles rarely divide evenly among the wavefronts (13 tiles of 197
+        // tokens: one wavefront gets four, the others three); which wavefront starts moves on with the item, so that
+        // the workgroups that share a compute unit do not all give the extra tile to the same SIMD.
+        const int qt0 = part + split * ((wv + item) % ATT_WAVES);
         const int b = item / H, h = item % H;
         const int8_t* base = qkv + h * D;
         const int32_t* trow = gather ? tok_index + (b % n_win) * T : nullptr;
@@ -153,6 +170,9 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             kreg[it] = *reinterpret_cast<const v4i*>(kv_row + C);
             vreg[it] = *reinterpret_cast<const v4i*>(kv_row + 2 * C);
         }
+        if (work == first) {                       // the table, while the first loads are in flight (visible after the barrier below)
+            for (int i = tid; i < NLUT; i += ATT_THREADS) lut[i] = shiftexp(-i, sm.i0, sm.n_shift);
+        }
         const int64_t orow0 = q_row(qt0);          // output row of the first query tile (before the indices move on)
         if (BIAS) {
             if (gather && work + G < n_work) {
@@ -170,13 +190,9 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
             const v4i kv = key < T ? kreg[it] : v4i{0, 0, 0, 0};
             const v4i vv = key < T ? vreg[it] : v4i{0, 0, 0, 0};
             *reinterpret_cast<v4i*>(&Ks[key * KROW + 16 * part]) = kv;
-            const int pos = vt_pos(key);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int dd = 16 * part + e;      // feature; stored in row 16 n + 4 g' + r with dd = g' (D/4) + 4 n + r
-                const int row = ((dd % (D / 4)) >> 2) * 16 + (dd / (D / 4)) * 4 + (dd & 3);
-                Vt[row * VROW + pos] = (int8_t)(vv[e >> 2] >> (8 * (e & 3)));
-            }
+            v2i_att* vdst = reinterpret_cast<v2i_att*>(&Vs[key * VP + 16 * part]);      // (rows are 8-byte aligned)
+            vdst[0] = v2i_att{vv[0], vv[1]};
+            vdst[1] = v2i_att{vv[2], vv[3]};
         }
         __syncthreads();
 
@@ -233,10 +249,11 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                     uint32_t bw = 0, mw = 0;
                     if (BIAS) { if (!MASK || brow) __builtin_memcpy(&bw, brow + 16 * t + 4 * lg, 4); }
                     if (MASK) __builtin_memcpy(&mw, mrow + 16 * t + 4 * lg, 4);
+                    requant8x4<FAST>(sc[t], qk, nqk, rnd);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int key = 16 * t + 4 * lg + r;
-                        int32_t a = requant8<FAST>(sc[t][r], qk, nqk, rnd);
+                        int32_t a = sc[t][r];
                         if (TAPS) { if (tap_s && q < T) tap_s[tap_row + key] = (int8_t)a; }
                         if (BIAS) a += (int32_t)(int8_t)(bw >> (8 * r));
                         if (MASK) { if ((mw >> (8 * r)) & 0xffu) a += mask_add; }
@@ -261,9 +278,9 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 __builtin_amdgcn_sched_barrier(0);     // keep the 64-bit temporaries of one tile at a time
             }
             mx = rows_allreduce(mx, [](int32_t a, int32_t b) { return max(a, b); });
-            // ---- ShiftExp by table, row sum.  The byte offset 2 (max - a) of the table entry is one 24-bit multiply-add.
+            // ---- ShiftExp by table, row sum.  The byte offset 4 (max - a) of the table entry is one 24-bit multiply-add.
             int32_t sum = 0;
-            const int32_t mx2 = 2 * mx;
+            const int32_t mx4 = 4 * mx;
             const char* lut_b = reinterpret_cast<const char*>(lut);
 #pragma unroll
             for (int t = 0; t < NKT; ++t) {
@@ -275,7 +292,7 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                             const int32_t delta = mx - sc[t][r];
                             e = delta < NLUT ? (int32_t)lut[min(delta, NLUT - 1)] : 0;
                         } else {
-                            e = (int32_t)*reinterpret_cast<const uint16_t*>(lut_b + (__mul24(sc[t][r], -2) + mx2));
+                            e = (int32_t)*reinterpret_cast<const uint32_t*>(lut_b + (__mul24(sc[t][r], -4) + mx4));
                         }
                         sc[t][r] = e;
                         sum += e;
@@ -334,7 +351,13 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
                 for (int t = 0; t < NKT; ++t) pk[t] -= (pk[t] >> (sm.k_out - 1)) & 0x01010101u;   // bytewise min(p, 2^(k_out-1) - 1)
             }
-            // ---- O^T = V^T P^T : "A" = V^T rows (features), "B" = packed probabilities (keys x queries)
+            // ---- O^T = V^T P^T : "A" = V^T rows (features), "B" = packed probabilities (keys x queries).
+            // Contraction position 16 lg + 4 j + r of chunk c is key 64 c + 16 j + 4 lg + r (the layout of pk).  A
+            // transposing read hands lane i of a 16-lane block byte i' of the 8-byte row named by lane 2 i' (i < 8)
+            // or 2 i' + 1 (i >= 8): the even lanes name keys j = 2 hh + (b >> 2), r = b & 3 (b = half the lane number)
+            // at features 8 n .. 8 n + 7, the odd lanes the same keys at features D/2 + 8 n .., so that row i of
+            // output tile n is feature 8 n + i (i < 8) or D/2 + 8 n + i - 8.
+            const int8_t* vbase = Vs + (4 * lg + 16 * ((li >> 1) >> 2) + ((li >> 1) & 3)) * VP + ((li & 1) ? D / 2 : 0);
             v4i oacc[ND];
 #pragma unroll
             for (int n = 0; n < ND; ++n) oacc[n] = v4i{0, 0, 0, 0};
@@ -343,12 +366,17 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
                 const v4i pf = {(int)pk[4 * c], (int)pk[4 * c + 1], (int)pk[4 * c + 2], (int)pk[4 * c + 3]};
 #pragma unroll
                 for (int n = 0; n < ND; ++n) {
-                    const v4i vf = *reinterpret_cast<const v4i*>(&Vt[(16 * n + li) * VROW + 64 * c + 16 * lg]);
+                    typedef v2i_att __attribute__((address_space(3))) * lds_v2i;
+                    const v2i_att v0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(vbase + (64 * c) * VP + 8 * n));
+                    const v2i_att v1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i)(vbase + (64 * c + 32) * VP + 8 * n));
+                    const v4i vf = {v0[0], v0[1], v1[0], v1[1]};
                     oacc[n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(vf, pf, oacc[n], 0, 0, 0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            // ---- requantise and store: lane holds features lg (D/4) + 4 n + r of query q
+            // ---- requantise and store: lane block lg holds rows 4 lg + r of every tile n, i.e. features
+            // (lg >= 2 ? D/2 : 0) + 8 n + 4 (lg & 1) + r of query q; exchanging tile n + ND/2 of the even blocks with tile
+            // n of the odd ones leaves block lg with the D/4 consecutive features lg (D/4) ..
             if (FAST == 2) {                       // as above: asm readers of fresh MFMA results
                 __builtin_amdgcn_sched_barrier(0);
                 asm volatile("s_nop 7");
@@ -359,13 +387,21 @@ __global__ __launch_bounds__(ATT_THREADS, 3) void attention_kernel(const int8_t*
 #pragma unroll
             for (int n = 0; n < ND; ++n) {
                 uint32_t w = 0;
+                int32_t ov[4] = {oacc[n][0], oacc[n][1], oacc[n][2], oacc[n][3]};
+                requant8x4<FAST>(ov, pv, npv, rnd);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) w |= ((uint32_t)requant8<FAST>(oacc[n][r], pv, npv, rnd) & 0xffu) << (8 * r);
+                for (int r = 0; r < 4; ++r) w |= ((uint32_t)ov[r] & 0xffu) << (8 * r);
                 ow[n] = w;
+            }
+#pragma unroll
+            for (int n = 0; n < ND / 2; ++n) {
+                // (odd blocks of the first operand <-> even blocks of the second)
+                const auto sw = __builtin_amdgcn_permlane16_swap(ow[n], ow[n + ND / 2], false, false);
+                ow[n] = sw[0]; ow[n + ND / 2] = sw[1];
             }
             if (q < T) {
                 int8_t* op = o + (qt == qt0 ? orow0 : row_of(q)) * C + h * D + lg * (D / 4);
-                if (D == 64) *reinterpret_cast<uint4*>(op) = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+                if (D == 64) *reinterpret_cast<uint4*>(op) = make_uint4(ow[0], ow[2], ow[1], ow[3]);
                 else *reinterpret_cast<uint2*>(op) = make_uint2(ow[0], ow[1 % ND]);
             }
         }
@@ -400,7 +436,10 @@ static void launch_flags(hipStream_t s, const AttentionArgs& a, int grid, int sp
     // which tests the bias pointer)
     const bool masked = a.mask != nullptr;
     constexpr int T49 = (D == 32 && NKT == 4) ? 49 : 0;                        // the windowed models' shape
-    if (T49 && a.T == 49 && !taps && fast && bias) {
+    constexpr int T197 = (D == 64 && NKT == 13) ? 197 : 0;                     // 14 x 14 patches and a class token
+    if (T197 && a.T == 197 && !taps && fast && !bias) {
+        if (narrow) IVIT_ATT(false, false, false, 2, T197); else IVIT_ATT(false, false, false, 1, T197);
+    } else if (T49 && a.T == 49 && !taps && fast && bias) {
         if (masked) { if (narrow) IVIT_ATT(false, true, true, 2, T49); else IVIT_ATT(false, true, true, 1, T49); }
         else { if (narrow) IVIT_ATT(false, true, false, 2, T49); else IVIT_ATT(false, true, false, 1, T49); }
     } else if (!taps && fast) {

@@ -66,6 +66,17 @@ __device__ __forceinline__ uint32_t div_small(uint32_t v, uint32_t x) {
     return q;
 }
 
+// The same repair works whenever the QUOTIENT is small (below 2^18, say), whatever the size of v < 2^31: the estimate
+// is then still within one of the quotient, and the remainder is formed exactly in 32 bits.
+__device__ __forceinline__ uint32_t div_small_quotient(uint32_t v, uint32_t x) { return div_small(v, x); }
+
+// floor(n / c) for c >= 1 and |n| < 2^22, through the unsigned form: floor(n / c) = -ceil(-n / c) for n < 0.
+__device__ __forceinline__ int32_t floordiv_small(int32_t n, int32_t c) {
+    const uint32_t a = n < 0 ? (uint32_t)(-n + c - 1) : (uint32_t)n;
+    const int32_t q = (int32_t)div_small(a, (uint32_t)c);
+    return n < 0 ? -q : q;
+}
+
 // ShiftExp (Sec. 3.3, Eq. 13-15, Algorithm 1) of an argument I <= 0: the value E with (S / 2^N) E ~ exp(S I).
 // t = -(I + (I >> 1) - (I >> 4)) >= 0 is the magnitude of I log2(e) in units of S; it splits as t = q I_0 + r with
 // 0 <= r < I_0: q whole powers of two to shift out, and the fraction -r / I_0, whose power of two is taken as
@@ -130,27 +141,45 @@ __device__ __forceinline__ int32_t mul_i24(int32_t a, int32_t b) {
 }
 
 // Tenth iterate of I <- (I + floor(v / I)) >> 1 from I = 2^floor(bitlen(v) / 2) (Eq. 20); 0 for v = 0.
-__device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
+constexpr uint32_t isqrt10_steps(uint32_t v) {
     if (v == 0) return 0;
-    uint32_t x = 1u << ((32 - __clz(v)) >> 1);
-    // An iterate that repeats is a fixed point of the map, so every later iterate equals it: stopping there gives the
-    // tenth iterate with fewer steps (an oscillating sequence simply runs all ten).
-    if (v < (1u << 22)) {
-#pragma unroll 1
-        for (int it = 0; it < 10; ++it) {
-            const uint32_t xn = (x + div_small(v, x)) >> 1;
-            if (xn == x) break;
-            x = xn;
-        }
-    } else {
+    uint32_t bits = 0;
+    for (uint32_t t = v; t; t >>= 1) ++bits;
+    uint32_t x = 1u << (bits >> 1);
+    for (int it = 0; it < 10; ++it) x = (x + v / x) >> 1;
+    return x;
+}
+// The iteration settles on floor(sqrt v) long before the tenth step (from that start, for v < 2^32), unless v + 1 is
+// a square, v = m^2 - 1: there it alternates between m - 1 and m for ever, and which of the two the tenth iterate is
+// depends on how many steps it took to get there.  For the variances of int8 rows (v <= 255^2) the answer per m is this
+// table, bit m of it set when the tenth iterate of m^2 - 1 is m; the compiler evaluates the iteration itself to fill it.
+struct Isqrt10Table {
+    uint32_t w[8];
+    constexpr Isqrt10Table() : w{} {
+        for (uint32_t m = 2; m < 256; ++m)
+            if (isqrt10_steps(m * m - 1) == m) w[m >> 5] |= 1u << (m & 31);
+    }
+};
+__device__ __forceinline__ uint32_t isqrt10(uint32_t v) {
+    if (v > 255u * 255u) {                                      // (beyond what an int8 row can give: the iteration as it stands)
+        uint32_t x = 1u << ((32 - __clz(v)) >> 1);
 #pragma unroll 1
         for (int it = 0; it < 10; ++it) {
             const uint32_t xn = (x + v / x) >> 1;               // x stays >= 1 for v >= 1
-            if (xn == x) break;
+            if (xn == x) break;                                 // a fixed point: every later iterate equals it
             x = xn;
         }
+        return x;
     }
-    return x;
+    // v <= 255^2: floor(sqrt v) from the single-precision square root (exact to within one for such v), repaired
+    constexpr Isqrt10Table T{};
+    uint32_t s = (uint32_t)__builtin_sqrtf((float)v);
+    s -= (s * s > v);
+    s += ((s + 1) * (s + 1) <= v);
+    const uint32_t m = s + 1;                                   // v == m^2 - 1 <=> v == s^2 + 2 s
+    const bool osc = (v == s * s + 2 * s) & (s >= 1);
+    const uint32_t bit = (T.w[m >> 5 & 7] >> (m & 31)) & 1u;
+    return osc ? s + bit : s;
 }
 
 // Reductions over the 64 lanes of a wavefront; every lane gets the result.  Inside each row of 16 lanes four DPP

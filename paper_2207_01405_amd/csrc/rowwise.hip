@@ -100,7 +100,9 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
                                                                int8_t* __restrict__ y, int64_t rows, int C,
                                                                int f_bits, int c_shift) {
     typedef int v4i __attribute__((ext_vector_type(4)));
-    __shared__ int2 part[J * 256];                 // [pass][thread]: (sum x, sum x^2) of one 16-byte chunk
+    // (sum x, sum x^2) of one 16-byte chunk, laid out [pass][chunk][row of the pass] so that the threads that add up
+    // the rows (consecutive rows, the same chunk at a time) read consecutive words: no bank conflicts there
+    __shared__ int2 part[J * 256];
     __shared__ int2 stat[J * 64];                  // [row in workgroup]: (mean, f)
     const int tid = threadIdx.x;
     const int CPR = C >> 4, RP = 256 / CPR, R = RP * J;
@@ -131,19 +133,21 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
             s = __builtin_amdgcn_sdot4(xv[j][d], 0x01010101, s, false);
             ss = __builtin_amdgcn_sdot4(xv[j][d], xv[j][d], ss, false);
         }
-        part[j * 256 + tid] = make_int2(s, ss);
+        if (active) part[j * 256 + cc * RP + rgrp] = make_int2(s, ss);
     }
     __syncthreads();
     for (int r = tid; r < R; r += 256) {           // one row per thread: r = j * RP + rgrp
         const int j = r / RP, rg = r - j * RP;
-        const int2* p = &part[j * 256 + rg * CPR];
+        const int2* p = &part[j * 256 + rg];
         int32_t s = 0, ss = 0;
-        for (int c = 0; c < CPR; ++c) { s += p[c].x; ss += p[c].y; }
-        const int32_t mean = floordiv(s + (C >> 1), C);
+        for (int c = 0; c < CPR; ++c) { s += p[c * RP].x; ss += p[c * RP].y; }
+        // (|sum x| <= 128 C < 2^19, the variance is at most 255^2 and f at most 2^20: the three divisions are of the
+        // kind one reciprocal and a repair step settle)
+        const int32_t mean = floordiv_small(s + (C >> 1), C);
         const int32_t sq = ss - 2 * mean * s + C * mean * mean;      // sum of squared deviations (exact)
-        const uint32_t var = (uint32_t)sq / (uint32_t)C;
+        const uint32_t var = div_small_quotient((uint32_t)sq, (uint32_t)C);
         const uint32_t sd = max(isqrt10(var), 1u);
-        stat[r] = make_int2(mean, (int32_t)((1u << f_bits) / sd));
+        stat[r] = make_int2(mean, (int32_t)div_small(1u << f_bits, sd));
     }
     __syncthreads();
     int32_t g[16], bt[16];

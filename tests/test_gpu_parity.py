@@ -91,6 +91,41 @@ def test_ilayernorm_other_shift_counts_and_spike_rows(ivit):
         assert_same(host(y), orc.ilayernorm(x, g, b, f_bits, c_shift), "ilayernorm f=%d c=%d" % (f_bits, c_shift))
 
 
+def test_ilayernorm_rows_whose_variance_is_one_below_a_square(ivit):
+    """Variances m^2 - 1 are where the ten-step square root of Eq. 20 never settles (it alternates between m - 1 and m);
+    m^2 and m^2 - 2 sit on either side.  Rows built to have exactly these variances: k entries at +a, k at -a, one probe
+    entry of 1 in a channel of the row's own, the rest 0 (mean 0, variance floor((2 k a^2 + 1) / C)).  The probe
+    channel's gamma and beta are set so that its output is 64 for the right standard deviation and moves by several
+    steps for a neighbouring one, so a wrong choice between m - 1 and m cannot hide in the int8 rounding."""
+    C, F, c = 384, 16, 10
+    reach = {}
+    for k in range(1, 41):
+        for a in range(1, 128):
+            reach.setdefault((2 * k * a * a + 1) // C, (k, a))
+    rows, stds = [], []
+    for m in range(2, 128):
+        for v in (m * m - 1, m * m, m * m - 2):
+            if v in reach and len(rows) < 300:
+                k, a = reach[v]
+                r = np.zeros(C, np.int8); r[:k] = a; r[k:2 * k] = -a; r[80 + len(rows)] = 1
+                rows.append(r); stds.append(orc.isqrt10(v))
+    assert len(rows) > 100
+    x = np.stack(rows)
+    g = np.ones(C, np.int32); b = np.zeros(C, np.int32)
+    G = 2048
+    for i, sd in enumerate(stds):
+        f = (1 << F) // sd
+        g[80 + i] = G; b[80 + i] = 64 * (1 << c) - G * f
+        for other in (sd - 1, sd + 1):                       # what a neighbouring standard deviation would print there
+            if other >= 1:
+                assert abs(((G * ((1 << F) // other) + b[80 + i] + (1 << (c - 1))) >> c) - 64) >= 2
+    y = empty(x.shape)
+    ivit.ivit_ilayernorm(dev(x), dev(g), dev(b), y, F, c)
+    want = orc.ilayernorm(x, g, b, F, c)
+    assert [int(want[i, 80 + i]) for i in range(len(rows))] == [64] * len(rows)
+    assert_same(host(y), want, "ilayernorm on rows with variance m^2 - 1")
+
+
 @pytest.mark.parametrize("C,f_bits,c_shift", [(64, 16, 19), (96, 12, 14), (384, 16, 19), (768, 8, 12), (768, 16, 22), (2048, 10, 30)])
 def test_ilayernorm_at_the_largest_admissible_parameters(ivit, C, f_bits, c_shift):
     """gamma_q and beta_q of magnitude ivit_ilayernorm_limits allows, on the rows that drive |x - mean| f to its
