@@ -269,7 +269,7 @@ def main():
             o = Forward(binding, synth, torch, name)
             oc = o.cfg
             n = max(5, min(args.steps, int(0.6 / max(1e-4, o.timed(2, 2)))))
-            e = o.timed(n, 0)
+            e = o.timed(n, 2)
             ok, _, orf = o.traced(3)
             oa, og_ms, og_ops, og_n = gemm_family(ok)
             unit = "windows/s" if name == "c4_swin_t" else "images/s"

@@ -6,14 +6,18 @@
 // operand, so the matrix cores read no weights from LDS; the groups hold the same channels and work on different
 // token tiles.  The workgroup walks over stages of GR tiles of 32 tokens: the activations of a stage are fetched
 // straight from global memory into LDS (LDS-direct loads, no register pass) two stages ahead, and every wavefront
-// reads its group's tile from there as the "A" operand, one 1 KB fragment per NCB MFMAs.  (With K = 384 two
-// wavefronts per SIMD fit the register file, and a single wavefront cannot issue instructions fast enough to keep
-// its matrix core busy: the second one fills the gaps.  With K = 768 the weights leave room for one.)  The accumulator of a lane is then ONE
-// channel and 16 tokens, so the four requantisation constants of a channel live in four registers for the whole
-// kernel: the epilogue reads no tables.  There are two sets of accumulators; while token tile t is multiplied, the
-// results of tile t - 1 are requantised between the MFMAs of the same wavefront (an issued MFMA executes in the
-// background; with one wavefront per SIMD nothing else could fill the gaps).  Everything else a tile needs (one
-// barrier, the loads of a later tile, the stores of an earlier one) is spread over the k-steps in the same way.
+// reads its group's tile from there as the "A" operand, one 1 KB fragment per NCB MFMAs.  The accumulator of a lane
+// is then ONE channel and 16 tokens, so the four requantisation constants of a channel live in four registers for the
+// whole kernel: the epilogue reads no tables.
+//   K = 768: the weights leave room for one wavefront per SIMD (GR = 1).  It has two sets of accumulators; while
+// token tile t is multiplied, the results of tile t - 1 are requantised between the MFMAs (an issued MFMA executes in
+// the background, and nothing else could fill the gaps).
+//   K = 384: two wavefronts per SIMD (GR = 2) with one set of accumulators each; a tile is requantised right after
+// its multiply while the other wavefront of the SIMD multiplies.
+// Everything else a tile needs (one barrier, the loads of a later tile, the stores of an earlier one) is spread over
+// the k-steps, one piece per step.  What bounds the kernel is the rate at which a SIMD issues instructions of any kind
+// (about one per 4.4 cycles, measured), so the tile loop is written to need few of them: tile bookkeeping in 32-bit
+// scalars, one address computation per load, stores through a buffer descriptor whose bounds check replaces lane masks.
 // The int8 results (16 tokens of a channel per lane) are turned into token rows through wavefront-private LDS with
 // the transposing LDS read of gfx950 (ds_read_b64_tr_b8) and leave as 16-byte pieces of contiguous row segments; the
 // residual operand comes in by the mirror image of that path.
@@ -102,24 +106,13 @@ struct RsLayout {
     static_assert(TOTAL + 1024 <= 160 * 1024, "LDS");
 };
 
-#ifdef IVIT_RS_TIMING
-__device__ long long rs_stamps[2048][32];
-#define RS_STAMP(i) do { if (lane == 0) rs_stamps[blockIdx.x * NW + wv][(i) < 31 ? (i) : 31] = clock64(); } while (0)
-#else
-#define RS_STAMP(i) do { } while (0)
-#endif
-
 template <int EPI, int KS, int NCB, int GR>
 __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     using LY = RsLayout<KS, NCB, EPI, GR>;
     constexpr int NW = LY::NW, NT = LY::NT;
-    constexpr int K = LY::K, PITCH = LY::PITCH, P16 = LY::P16, NWI = LY::NWI, NI = LY::NI, XT = LY::XT, OT = LY::OT;
+    constexpr int K = LY::K, PITCH = LY::PITCH, P16 = LY::P16, NWI = LY::NWI, NI = LY::NI, OT = LY::OT;
     constexpr int RP = LY::RP, RS16 = LY::RS16, RNI = LY::RNI, RT = LY::RT, WNI = LY::WNI, WCHUNK = LY::WCHUNK;
-#ifdef IVIT_RS_RG
-    constexpr int RG = GR == 2 ? IVIT_RS_RG : 3;
-#else
     constexpr int RG = (KS % 3 == 0) ? 3 : 4;                  // ring of A fragments: RG - 1 k-steps of prefetch distance
-#endif
     constexpr int NU = 4 * NCB;                                // epilogue units (4 outputs each) per token tile and lane
     constexpr int SYNC = KS / 2;                               // k-step of the barrier
     static_assert(KS % RG == 0, "ring must align with the tile");
@@ -139,7 +132,6 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     const int N = P.N;
     const int64_t M = P.M;
     const int Nt = N >> 5;
-    RS_STAMP(0);
 
     // workgroups of one XCD (block id modulo 8) get consecutive logical ids, so the slabs that share a token tile,
     // and therefore read the same activations, sit on the same L2
@@ -230,13 +222,8 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
 #pragma unroll
         for (int c = 0; c < NCHUNK; ++c) {
             // loads complete in order: all but the WNI of the following chunk
-            if (c == 0) RS_STAMP(25);
             if (c + 1 < NCHUNK) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WNI) : "memory"); else wait_vm0();
-            if (c == 0) RS_STAMP(26);
-            if (c == 1) RS_STAMP(28);
             __syncthreads();
-            if (c == 0) RS_STAMP(27);
-            if (c == 1) RS_STAMP(29);
             const int cb = c / KH, kh = c % KH;
             const int8_t* src = lds + (c & 1) * WCHUNK + (wq * 32 + lj) * WPITCH + 16 * lg;
 #pragma unroll
@@ -283,7 +270,6 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
                 rw[cb][h] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(t + 8 * h * RP + 32 * cb));
     };
 
-    RS_STAMP(24);
     {
         const Span s1 = span_of(cursor(P.x, P.ldx, 1, 0), x_last, SR);
 #pragma unroll
@@ -342,11 +328,9 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         const int32_t I = (int32_t)(int8_t)tid;
         gelu_lut[tid] = (int8_t)requant64(shiftgelu_raw(I, P.gelu_p), P.gelu_rq.b, P.gelu_rq.c, P.rnd);
     }
-    RS_STAMP(1);
     // (no wait for the loads just requested: stage 0 landed before the first weight chunk was read, loads completing in
     // order; stage 1 and the residual tile are first read after the barrier inside tile 0, which waits for them)
     const bool fast24 = __syncthreads_and(chan_24) != 0;
-    RS_STAMP(2);
     if (!fast24) {                                              // the general form keeps the raw parameters instead
 #pragma unroll
         for (int cb = 0; cb < NCB; ++cb) { c_lo[cb] = pb[cb]; c_hi[cb] = pc[cb]; c_mb[cb] = pbias[cb]; c_ad[cb] = 0; }
@@ -446,39 +430,37 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     int par = 0;                                                // residual tile k is in half `par` of the residual staging
 
     // Token tile k in the stage buffer at offset b0 (the one at b1 holds stage k + 1, the one at b2 is free for stage
-    // k + 2): multiply into `cur`.  With one
-    // wavefront per SIMD (GR == 1) there are two sets of accumulators and, when `ep`, `prev` (tile k - 1) is requantised
-    // between the MFMAs, in the k-steps before the barrier, and stored after it.
-    // With two wavefronts per SIMD (GR == 2) there is a single set: tile k is requantised right after its multiply, and
-    // `ep` only says whether tile k - 1 is there to be stored.  The two wavefronts of a SIMD are kept half a period
-    // apart: group 0 (PH == 0) meets the barrier of stage k in the middle of its multiply of tile k, group 1 (PH == 1)
-    // in the middle of its requantisation of tile k, having multiplied all of it already; its multiply of tile k
-    // therefore runs after barrier k - 1 and carries that barrier's follow-up work (requests of stage k + 1).
+    // k + 2): multiply into `cur`.  With one wavefront per SIMD (GR == 1) there are two sets of accumulators and, when
+    // `ep`, `prev` (tile k - 1) is requantised between the MFMAs, in the k-steps before the barrier, and stored after it.
+    // With two wavefronts per SIMD (GR == 2) there is a single set: tile k is requantised right after its multiply
+    // (the other wavefront of the SIMD multiplies meanwhile), and `ep` only says whether tile k - 1 is there to be
+    // stored.  (Measured alternatives that gained nothing and are not kept: two sets with two wavefronts per SIMD,
+    // which just fits 128 registers; holding the two wavefronts of a SIMD half a tile apart through the barrier.)
     constexpr bool TWO_SETS = GR == 1;
-    auto tile_step = [&]<bool ep, bool fast, int PH>(int b0, int b1, int b2, v16i (&cur)[NCB], const v16i (&prev)[NCB]) __attribute__((always_inline)) {
+    auto tile_step = [&]<bool ep, bool fast>(int b0, int b1, int b2, v16i (&cur)[NCB], const v16i (&prev)[NCB]) __attribute__((always_inline)) {
         v4i ow[NCB];
         v2i sa = {}, sb = {};
         if (EPI == EPI_RESIDUAL && ep && TWO_SETS) read_res(par ^ 1, rw);
-        constexpr int FIRST = PH == 0 ? SYNC : 0;              // k-step of the first piece of the work that follows a barrier
+        constexpr int FIRST = SYNC;                            // k-step of the first piece of the work that follows the barrier
         const int8_t* xa = Xs + b0 + a_base;
         const int8_t* xb = Xs + b1 + a_base;
         // this tile's scalars, pinned in scalar registers (recomputing them at every use would cost more instructions
         // than the loads and stores themselves)
         const auto sc = [](int v) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(v); };
         const Span q_span = span_of(c_req, x_last, SR);
-        const uint32_t q_dst = (uint32_t)sc(xs_off + (PH == 0 ? b2 : b1));
+        const uint32_t q_dst = (uint32_t)sc(xs_off + b2);
         const Span r_span = EPI == EPI_RESIDUAL ? span_of(c_res, res_last, 32) : Span{nullptr, 0};
         const uint32_t r_dst = (uint32_t)sc(res_off + (par ^ 1) * RT);
         const __amdgpu_buffer_rsrc_t y_buf = tile_buffer(c_prev);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            if (PH == 0 && ks == SYNC) {
+            if (ks == SYNC) {
                 wait_vm0();
                 __syncthreads();
             }
             // fragment ks + RG - 1: of the next tile once this one runs out (valid since the barrier of this tile)
             if (ks + RG - 1 < KS) af[(ks + RG - 1) % RG] = *reinterpret_cast<const v4i*>(xa + 32 * (ks + RG - 1));
-            else if (PH == 0) af[(ks + RG - 1) % RG] = *reinterpret_cast<const v4i*>(xb + 32 * (ks + RG - 1 - KS));
+            else af[(ks + RG - 1) % RG] = *reinterpret_cast<const v4i*>(xb + 32 * (ks + RG - 1 - KS));
 #pragma unroll
             for (int cb = 0; cb < NCB; ++cb) {
                 if (ks == 0) {
@@ -510,17 +492,11 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
             __builtin_amdgcn_sched_barrier(0);
         }
         if (!TWO_SETS) {
-            if (EPI == EPI_RESIDUAL) read_res(par, rw);         // residual tile k landed before barrier k - 1 (PH 1) or k (PH 0)
+            if (EPI == EPI_RESIDUAL) read_res(par, rw);         // residual tile k landed before barrier k
             asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");      // the last MFMAs have written the accumulators
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < NU; ++u) {
-                if (PH == 1 && u == NU / 2) {
-                    wait_vm0();
-                    __syncthreads();
-#pragma unroll
-                    for (int i = 0; i < RG - 1; ++i) af[i] = *reinterpret_cast<const v4i*>(xb + 32 * i);      // first fragments of the next tile
-                }
                 const int cb = u >> 2, d = u & 3;
                 ow[cb][d] = fast ? unit_fast(cur[cb], cb, d, rw) : unit_general(cur[cb], cb, d, rw);
                 if (d == 3) put_out(cb, ow[cb]);
@@ -564,40 +540,33 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
         c_prev = c_out;
         par = 0;
     };
-    auto run_one_set = [&]<bool fast, int PH>() __attribute__((always_inline)) {
-        start(PH == 0 ? 2 : 1);
-        tile_step.template operator()<false, fast, PH>(LY::stage_offset(0), LY::stage_offset(1), LY::stage_offset(2), accA, accA);
-        RS_STAMP(3);
+    auto run_one_set = [&]<bool fast>() __attribute__((always_inline)) {
+        start(2);
+        tile_step.template operator()<false, fast>(LY::stage_offset(0), LY::stage_offset(1), LY::stage_offset(2), accA, accA);
         int b0 = LY::stage_offset(1), b1 = LY::stage_offset(2), b2 = LY::stage_offset(0);
         for (int k = 1; k < ntile; ++k) {
-            tile_step.template operator()<true, fast, PH>(b0, b1, b2, accA, accA);
-            RS_STAMP(3 + k);
+            tile_step.template operator()<true, fast>(b0, b1, b2, accA, accA);
             const int t = b0; b0 = b1; b1 = b2; b2 = t;
         }
         drain.template operator()<fast>(accA);
-        RS_STAMP(30);
     };
     auto run = [&]<bool fast>() __attribute__((always_inline)) {
         if (!TWO_SETS) {
-            run_one_set.template operator()<fast, 0>();
+            run_one_set.template operator()<fast>();
             return;
         }
         start(2);
-        tile_step.template operator()<false, fast, 0>(LY::stage_offset(0), LY::stage_offset(1), LY::stage_offset(2), accA, accB);
-        RS_STAMP(3);
+        tile_step.template operator()<false, fast>(LY::stage_offset(0), LY::stage_offset(1), LY::stage_offset(2), accA, accB);
         int b0 = LY::stage_offset(1), b1 = LY::stage_offset(2), b2 = LY::stage_offset(0);
         for (int k = 1; k < ntile; k += 2) {
-            tile_step.template operator()<true, fast, 0>(b0, b1, b2, accB, accA);
-            RS_STAMP(3 + k);
+            tile_step.template operator()<true, fast>(b0, b1, b2, accB, accA);
             { const int t = b0; b0 = b1; b1 = b2; b2 = t; }
             if (k + 1 < ntile) {
-                tile_step.template operator()<true, fast, 0>(b0, b1, b2, accA, accB);
-                RS_STAMP(4 + k);
+                tile_step.template operator()<true, fast>(b0, b1, b2, accA, accB);
                 const int t = b0; b0 = b1; b1 = b2; b2 = t;
             }
         }
         if (ntile & 1) drain.template operator()<fast>(accA); else drain.template operator()<fast>(accB);
-        RS_STAMP(30);
     };
     if (fast24) run.template operator()<true>(); else run.template operator()<false>();
     wait_vm0();            // LDS-direct loads still in flight (repeats of the last stage) must land before the LDS is released
@@ -633,12 +602,6 @@ bool linear_rs_takes(const LinearArgs& a) {
     if (a.M > (1 << 30)) return false;                         // row counts are kept in 32 bits
     return (a.N & 31) == 0 && (a.ldx == 0 || a.ldx == a.K) && a.M >= 1;
 }
-
-#ifdef IVIT_RS_TIMING
-extern "C" int ivit_rs_read_stamps(long long* out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(rs_stamps), sizeof(long long) * 2048 * 32);
-}
-#endif
 
 hipError_t launch_linear_rs(hipStream_t s, const LinearArgs& a) {
     RsParams P;
