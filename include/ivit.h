@@ -132,8 +132,8 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
  *           the schedule), so this is a switch for tests and measurements:
  *           IVIT_KERNEL_AUTO            chosen from the shape;
  *           IVIT_KERNEL_MANY_ROWS       never the kernel written for few rows;
- *           IVIT_KERNEL_REG_STATIONARY  the kernel that keeps the weights in registers; it takes K = 384 or 768
- *                                       with N % 32 == 0 only, other shapes give IVIT_ERR_SHAPE.
+ *           IVIT_KERNEL_REG_STATIONARY  the kernels that keep the weights in registers; they take K = 384, 768 or
+ *                                       1536 with N % 32 == 0 only, other shapes give IVIT_ERR_SHAPE.
  *   rounding  how every dyadic requantisation of the layer (Sec. 3.2, Eq. 8-10: the output's, the residual's, the
  *           one after ShiftGELU) turns b v / 2^c into an integer:
  *           IVIT_ROUND_NEAREST          (b v + 2^(c-1)) >> c, the rounding Eq. 8 asks for carried into Eq. 10 (what

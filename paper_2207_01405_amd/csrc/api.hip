@@ -228,7 +228,7 @@ int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const
     a.y = y; a.M = M; a.N = N; a.K = K;
     a.kernel = opt ? opt->kernel : ivit::LINEAR_AUTO;
     a.floor_shift = opt && opt->rounding == IVIT_ROUND_FLOOR;
-    if (a.kernel == ivit::LINEAR_REG_STATIONARY && M > 0 && !ivit::linear_rs_takes(a)) return IVIT_ERR_SHAPE;
+    if (a.kernel == ivit::LINEAR_REG_STATIONARY && M > 0 && !ivit::linear_rs_takes(a) && !ivit::linear_ks_takes(a)) return IVIT_ERR_SHAPE;
     return hip_status(ivit::launch_linear(static_cast<hipStream_t>(stream), a));
 }
 

@@ -803,8 +803,11 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     // the kernels below on the DeiT-S and ViT-B shapes it wins on the layers without a residual (QKV 27.1 -> 23.0 us,
     // fc1 35.5 -> 29.6 us at K = 384; 122 -> 92 us and 199 -> 149 us at K = 768) and loses on the projection, whose
     // residual epilogue costs it more instructions per output (16.0 -> 21.2 us, 52 -> 60 us)
-    if (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && linear_rs_takes(a) && !a.residual && a.M >= 4096))
+    if (linear_rs_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && !a.residual && a.M >= 4096)))
         return launch_linear_rs(s, a);
+    // K = 1536: the same idea with K split over pairs of wavefronts (gemm_ks.hip)
+    if (linear_ks_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && a.M >= 4096)))
+        return launch_linear_ks(s, a);
     int ncb, unit, nunits, pitch; size_t lds_bytes;
     if (ws_plan(a, ncb, unit, nunits, pitch, lds_bytes)) {
         WsParams W;

@@ -34,6 +34,9 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a);
 // Register-stationary kernel (gemm_rs.hip): whether it takes this shape at all, and its launch.
 bool linear_rs_takes(const LinearArgs& a);
 hipError_t launch_linear_rs(hipStream_t s, const LinearArgs& a);
+// The same with K = 1536 split over pairs of wavefronts (gemm_ks.hip).
+bool linear_ks_takes(const LinearArgs& a);
+hipError_t launch_linear_ks(hipStream_t s, const LinearArgs& a);
 hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos, Dyadic tok_rq,
                                Dyadic pos_rq, int8_t* tokens, int B, int P, int C);
 

@@ -240,8 +240,9 @@ def test_linear_options_and_probe_arguments(lib):
     empty = binding.Dims(0, 65, 64, 2, 256)
     assert lib.ivit_window_attention_ex(None, None, None, None, 1, None, 1, None, C.byref(empty), DY, SP, DY, None, None,
                                         C.byref(binding.AttentionOptions(1))) == 0
-    # the register-stationary kernel takes K = 384 or 768 with N % 32 == 0 and nothing else
-    assert ex(2, K=512) == E["SHAPE"] and ex(2, N=48) == E["SHAPE"] and ex(2, K=1536) == E["SHAPE"]
+    # the register-stationary kernels take K = 384, 768 or 1536 with N % 32 == 0 and nothing else
+    assert ex(2, K=512) == E["SHAPE"] and ex(2, N=48) == E["SHAPE"] and ex(2, K=3072) == E["SHAPE"]
+    assert ex(2, K=1536, N=48) == E["SHAPE"] and ex(2, K=1536, M=0) == 0
     assert ex(2, M=0) == 0 and ex(0, M=0) == 0 and ex(None, M=0) == 0 and ex(1, M=0, K=512) == 0
     ops = C.c_int64(0)
     pr = lambda rnd=0, it=100, s=0x100000, n=1 << 20, o=ops: lib.ivit_probe_mfma_rate(None, rnd, it, s, n, C.byref(o) if o is not None else None)

@@ -329,9 +329,9 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
     """Per-channel parameters at and around the limits of the 24-bit requantisation (shift 1..24, multiplier just
     below and at 2^(c-1), biases that push the clamp bounds to and past 24 bits), on operands that drive the
     accumulators to both saturated ends (K * 127^2 exceeds 2^23 for the larger K) and through the whole range.
-    Slabs of 64 channels share one regime each, so both the narrow path and its fallbacks run.  K = 384 and 768 are
-    run on the kernel that keeps the weights in registers as well (its workgroups span 384 or 256 channels)."""
-    if K in (384, 768) and dense_path == "many_rows":
+    Slabs of 64 channels share one regime each, so both the narrow path and its fallbacks run.  K = 384, 768 and 1536
+    are run on the kernels that keep the weights in registers as well (their workgroups span 256 or 128 channels)."""
+    if K in (384, 768, 1536) and dense_path == "many_rows":
         dense_path = "reg_stationary"
     fs = rounding == "floor"
     rng = np.random.default_rng(K)
@@ -387,7 +387,8 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
 # Eq. 10 as a bare shift: every epilogue of every Dense kernel (few rows, tiled, weights in LDS, weights in registers)
 FLOOR_SHAPES = [(65, 192, 64, None), (5, 7, 80, None), (1000, 384, 384, "many_rows"), (300, 384, 1536, "many_rows"),
                 (257, 130, 3072, "many_rows"), (333, 208, 96, "many_rows"), (30011, 128, 384, None),
-                (1000, 1152, 384, "reg_stationary"), (4100, 384, 384, "reg_stationary"), (515, 256, 768, "reg_stationary")]
+                (1000, 1152, 384, "reg_stationary"), (4100, 384, 384, "reg_stationary"), (515, 256, 768, "reg_stationary"),
+                (700, 384, 1536, "reg_stationary")]
 
 
 @pytest.mark.parametrize("M,N,K,kernel", FLOOR_SHAPES)
@@ -417,7 +418,11 @@ def test_linear_requant_floor_mode(ivit, M, N, K, kernel, epi):
 # K = 384, 256 at K = 768), every epilogue; forced through the option so that small row counts reach it too
 RS_SHAPES = [(1, 32, 384), (31, 384, 384), (32, 96, 384), (33, 1152, 384), (197, 384, 384), (1000, 1536, 384), (2500, 416, 384),
              (8203, 384, 384), (9000, 1152, 384), (64, 768, 768), (333, 256, 768), (1577, 2304, 768), (300, 3072, 768),
-             (8300, 768, 768), (95, 160, 768)]
+             (8300, 768, 768), (95, 160, 768),
+             # K = 1536: the kernel that splits K over pairs of wavefronts (128 channels per workgroup): one tile, an even and an
+             # odd number of tiles per workgroup, partial slabs, more workgroups than tiles
+             (1, 32, 1536), (32, 128, 1536), (33, 384, 1536), (197, 96, 1536), (1000, 384, 1536), (2500, 416, 1536),
+             (8203, 384, 1536), (16400, 128, 1536), (300, 1536, 1536)]
 
 
 @pytest.mark.parametrize("M,N,K", RS_SHAPES)
@@ -459,7 +464,7 @@ def test_linear_requant_weights_in_registers_general_pairs_and_refusals(ivit):
         want = orc.linear_requant(x, w, None, rq_b, rq_c, **kw_o)
         assert_same(host(y), want, "linear general (weights in registers)")
         assert np.abs(want.astype(np.int32)).mean() > 2
-    for Mb, Nb, Kb in ((64, 64, 128), (64, 48, 384), (64, 1000, 768)):
+    for Mb, Nb, Kb in ((64, 64, 128), (64, 48, 384), (64, 1000, 768), (64, 48, 1536), (64, 64, 3072)):
         with pytest.raises(ivit.IvitError) as err:
             ivit.ivit_linear_requant(empty((Mb, Kb)), empty((Nb, Kb)), None, dev(rq_b[:1].repeat(Nb)), dev(rq_c[:1].repeat(Nb)),
                                      empty((Mb, Nb)), kernel="reg_stationary")

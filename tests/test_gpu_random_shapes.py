@@ -71,7 +71,7 @@ def test_linear_random(ivit, dense_path, seed):
     rng = np.random.default_rng(1000 + seed)
     K = 16 * int(rng.choice([1, 2, 3, 5, 6, 8, 12, 16, 24, 25, 48, 96, 100, 192]))
     if seed % 6 == 5 and dense_path == "many_rows":      # a sixth of the draws: the kernel with the weights in registers
-        K, dense_path = int(rng.choice([384, 768])), "reg_stationary"
+        K, dense_path = int(rng.choice([384, 768, 1536])), "reg_stationary"
     N = int(rng.choice([16, 48, 64, 80, 128, 144, 256, 400, 1000, 7, 33])) if seed % 3 else 16 * int(rng.integers(1, 60))
     if dense_path == "reg_stationary":
         N = 32 * int(rng.integers(1, 40))
