@@ -120,10 +120,13 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
     }
     // gamma and beta + 2^(c-1) go through LDS: read once per workgroup with coalesced loads instead of 128 bytes per
     // thread; each thread picks up its 16 channels after the first barrier
-    __shared__ __align__(16) int32_t gb[2 * GBN];
+    // (the 16 channels of a chunk are 20 words apart, so that the threads of a row, which read theirs at the same
+    // time, meet no bank twice)
+    constexpr int GBP = GBN / 16 * 20;
+    __shared__ __align__(16) int32_t gb[2 * GBP];
     for (int i = tid; i < C; i += 256) {
-        gb[i] = gamma_q[i];
-        gb[GBN + i] = (int32_t)((uint32_t)beta_q[i] + (uint32_t)half);
+        gb[(i >> 4) * 20 + (i & 15)] = gamma_q[i];
+        gb[GBP + (i >> 4) * 20 + (i & 15)] = (int32_t)((uint32_t)beta_q[i] + (uint32_t)half);
     }
 #pragma unroll
     for (int j = 0; j < J; ++j) {
@@ -153,8 +156,8 @@ __global__ __launch_bounds__(256) void ilayernorm_tiled_kernel(const int8_t* __r
     int32_t g[16], bt[16];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const v4i gv = *reinterpret_cast<const v4i*>(&gb[(active ? 16 * cc : 0) + 4 * q]);
-        const v4i bv = *reinterpret_cast<const v4i*>(&gb[GBN + (active ? 16 * cc : 0) + 4 * q]);
+        const v4i gv = *reinterpret_cast<const v4i*>(&gb[(active ? 20 * cc : 0) + 4 * q]);
+        const v4i bv = *reinterpret_cast<const v4i*>(&gb[GBP + (active ? 20 * cc : 0) + 4 * q]);
 #pragma unroll
         for (int e = 0; e < 4; ++e) { g[4 * q + e] = gv[e]; bt[4 * q + e] = bv[e]; }
     }
