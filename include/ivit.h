@@ -134,13 +134,15 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
  *           IVIT_KERNEL_MANY_ROWS       never the kernel written for few rows;
  *           IVIT_KERNEL_REG_STATIONARY  the kernels that keep the weights in registers; they take K = 384, 768 or
  *                                       1536 with N % 32 == 0 only, other shapes give IVIT_ERR_SHAPE.
+ *           IVIT_KERNEL_BIG_TILES       the kernel that streams both operands through LDS in 256 x 128 tiles; it
+ *                                       takes K % 128 == 0, K >= 384, N % 128 == 0 only (else IVIT_ERR_SHAPE).
  *   rounding  how every dyadic requantisation of the layer (Sec. 3.2, Eq. 8-10: the output's, the residual's, the
  *           one after ShiftGELU) turns b v / 2^c into an integer:
  *           IVIT_ROUND_NEAREST          (b v + 2^(c-1)) >> c, the rounding Eq. 8 asks for carried into Eq. 10 (what
  *                                       every entry point without options does);
  *           IVIT_ROUND_FLOOR            (b v) >> c, Eq. 10 exactly as printed, a bare arithmetic shift.
  * Errors: as ivit_linear_requant; PARAM for an unknown option value. */
-enum { IVIT_KERNEL_AUTO = 0, IVIT_KERNEL_MANY_ROWS = 1, IVIT_KERNEL_REG_STATIONARY = 2 };
+enum { IVIT_KERNEL_AUTO = 0, IVIT_KERNEL_MANY_ROWS = 1, IVIT_KERNEL_REG_STATIONARY = 2, IVIT_KERNEL_BIG_TILES = 3 };
 enum { IVIT_ROUND_NEAREST = 0, IVIT_ROUND_FLOOR = 1 };
 typedef struct { int32_t kernel; int32_t rounding; } ivit_linear_options;
 int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias,

@@ -44,7 +44,7 @@ class AttentionOptions(C.Structure):
     _fields_ = [("rounding", C.c_int32)]
 
 
-KERNELS = {"auto": 0, "many_rows": 1, "reg_stationary": 2}
+KERNELS = {"auto": 0, "many_rows": 1, "reg_stationary": 2, "big_tiles": 3}
 ROUNDING = {"nearest": 0, "floor": 1}
 
 

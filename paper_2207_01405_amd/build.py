@@ -15,11 +15,11 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libivit.so")
-SOURCES = ["api.hip", "trace.hip", "rowwise.hip", "gemm_i8.hip", "gemm_rs.hip", "gemm_ks.hip", "attention.hip", "host_helpers.hip", "probe.hip"]
+SOURCES = ["api.hip", "trace.hip", "rowwise.hip", "gemm_i8.hip", "gemm_rs.hip", "gemm_ks.hip", "gemm_tl.hip", "attention.hip", "host_helpers.hip", "probe.hip"]
 # gemm_rs.hip: MFMA results in ordinary vector registers (the epilogue reads them with vector instructions; the
 # weights sit in the accumulation registers instead)
 _REGST = ["-mllvm", "-amdgpu-mfma-vgpr-form", "-Wno-inline-asm"]
-EXTRA_FLAGS = {"gemm_rs.hip": _REGST, "gemm_ks.hip": _REGST}
+EXTRA_FLAGS = {"gemm_rs.hip": _REGST, "gemm_ks.hip": _REGST, "gemm_tl.hip": ["-Wno-inline-asm"]}
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed FP32 instructions are kept out of every code object of this library
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -208,7 +208,7 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
 int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const int32_t* bias, const int32_t* rq_b,
                            const int32_t* rq_c, const int8_t* residual, ivit_dyadic res_rq, const ivit_shift_params* gelu,
                            ivit_dyadic gelu_rq, int8_t* y, int64_t M, int32_t N, int32_t K, const ivit_linear_options* opt) {
-    if (opt && (opt->kernel < IVIT_KERNEL_AUTO || opt->kernel > IVIT_KERNEL_REG_STATIONARY)) return IVIT_ERR_PARAM;
+    if (opt && (opt->kernel < IVIT_KERNEL_AUTO || opt->kernel > IVIT_KERNEL_BIG_TILES)) return IVIT_ERR_PARAM;
     if (opt && opt->rounding != IVIT_ROUND_NEAREST && opt->rounding != IVIT_ROUND_FLOOR) return IVIT_ERR_PARAM;
     if (M < 0 || N < 1 || K < 16 || K > 65536 || (K & 15)) return IVIT_ERR_SHAPE;
     if (M > 0 && (!x || !y)) return IVIT_ERR_NULL;             // an empty tensor may have no storage
@@ -229,6 +229,7 @@ int ivit_linear_requant_ex(void* stream, const int8_t* x, const int8_t* w, const
     a.kernel = opt ? opt->kernel : ivit::LINEAR_AUTO;
     a.floor_shift = opt && opt->rounding == IVIT_ROUND_FLOOR;
     if (a.kernel == ivit::LINEAR_REG_STATIONARY && M > 0 && !ivit::linear_rs_takes(a) && !ivit::linear_ks_takes(a)) return IVIT_ERR_SHAPE;
+    if (a.kernel == ivit::LINEAR_BIG_TILES && M > 0 && !ivit::linear_tl_takes(a)) return IVIT_ERR_SHAPE;
     return hip_status(ivit::launch_linear(static_cast<hipStream_t>(stream), a));
 }
 

@@ -809,7 +809,15 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     if (linear_ks_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && a.M >= 4096)))
         return launch_linear_ks(s, a);
     int ncb, unit, nunits, pitch; size_t lds_bytes;
-    if (ws_plan(a, ncb, unit, nunits, pitch, lds_bytes)) {
+    const bool ws = ws_plan(a, ncb, unit, nunits, pitch, lds_bytes);
+    // rows too long for the weight-stationary kernels: 256 x 128 tiles with both operands streamed (gemm_tl.hip), when
+    // there are tiles enough to go round.  Its cost per tile outside the k-loop only pays off for long rows: on the
+    // 768-wide model it takes the second MLP layer (K = 3072) from 210 to 162 us and loses at K = 768 (QKV 174 against
+    // 124 us with the tiled kernel below)
+    if (linear_tl_takes(a) && (a.kernel == LINEAR_BIG_TILES ||
+                               (a.kernel == LINEAR_AUTO && !ws && a.K >= 2048 && (a.M + 255) / 256 * (a.N / 128) >= num_cus())))
+        return launch_linear_tl(s, a);
+    if (ws) {
         WsParams W;
         W.g = P; W.pitch = pitch; W.nunits = nunits;
         W.slabs = (a.N + 32 * ncb - 1) / (32 * ncb);

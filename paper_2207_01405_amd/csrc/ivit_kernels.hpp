@@ -29,7 +29,7 @@ struct LinearArgs {
     int kernel;                          // 0: chosen from the shape; otherwise one of LinearKernel, forced (tests, measurements)
     int floor_shift;                     // 0: requantisations round to nearest (Eq. 8 through Eq. 10); 1: bare shift of Eq. 10 (floor)
 };
-enum LinearKernel { LINEAR_AUTO = 0, LINEAR_MANY_ROWS = 1, LINEAR_REG_STATIONARY = 2 };
+enum LinearKernel { LINEAR_AUTO = 0, LINEAR_MANY_ROWS = 1, LINEAR_REG_STATIONARY = 2, LINEAR_BIG_TILES = 3 };
 hipError_t launch_linear(hipStream_t s, const LinearArgs& a);
 // Register-stationary kernel (gemm_rs.hip): whether it takes this shape at all, and its launch.
 bool linear_rs_takes(const LinearArgs& a);
@@ -37,6 +37,9 @@ hipError_t launch_linear_rs(hipStream_t s, const LinearArgs& a);
 // The same with K = 1536 split over pairs of wavefronts (gemm_ks.hip).
 bool linear_ks_takes(const LinearArgs& a);
 hipError_t launch_linear_ks(hipStream_t s, const LinearArgs& a);
+// Long rows, both operands streamed through LDS in 256 x 128 tiles (gemm_tl.hip).
+bool linear_tl_takes(const LinearArgs& a);
+hipError_t launch_linear_tl(hipStream_t s, const LinearArgs& a);
 hipError_t launch_embed_tokens(hipStream_t s, const int8_t* patch_tok, const int8_t* cls, const int8_t* pos, Dyadic tok_rq,
                                Dyadic pos_rq, int8_t* tokens, int B, int P, int C);
 

@@ -231,7 +231,10 @@ def test_linear_options_and_probe_arguments(lib):
     ex = lambda opt, **kw: lib.ivit_linear_requant_ex(None, FAKE, FAKE, None, FAKE, FAKE, kw.get("res"), DY, None, DY, FAKE,
                                                       kw.get("M", 8), kw.get("N", 64), kw.get("K", 384),
                                                       None if opt is None else C.byref(binding.LinearOptions(opt)))
-    assert ex(3) == E["PARAM"] and ex(-1) == E["PARAM"]
+    assert ex(4) == E["PARAM"] and ex(-1) == E["PARAM"]
+    # the big-tile kernel takes K % 128 == 0, K >= 384, N % 128 == 0
+    assert ex(3, K=384, N=64) == E["SHAPE"] and ex(3, K=256, N=128) == E["SHAPE"] and ex(3, K=448, N=128) == E["SHAPE"]
+    assert ex(3, K=384, N=128, M=0) == 0
     bad_round = binding.LinearOptions(0, 2)
     assert lib.ivit_linear_requant_ex(None, FAKE, FAKE, None, FAKE, FAKE, None, DY, None, DY, FAKE, 8, 64, 384, C.byref(bad_round)) == E["PARAM"]
     good = binding.Dims(2, 65, 64, 2, 256)

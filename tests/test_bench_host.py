@@ -10,12 +10,22 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_measured_traffic_reads_the_committed_counter_summary():
     sys.path.insert(0, ROOT)
     import bench
+    from paper_2207_01405_amd import synth
+    cfg = synth.CONFIGS["c2_deit_s"]
+    M, C, F = cfg["B"] * cfg["T"], cfg["C"], cfg["F"]
+    # algorithmic bytes of the four Dense launches of a block: activations in, weights, results (and the residual) out,
+    # 12 bytes of parameters per output channel
+    alg = ((M * C + 3 * C * C + 3 * M * C + 36 * C) + (M * C + C * C + 2 * M * C + 12 * C) + (M * C + F * C + M * F + 12 * F)
+           + (M * F + C * F + 2 * M * C + 12 * C)) // 4
     t = bench.measured_traffic("c2_deit_s")
-    alg = 44015616                      # algorithmic bytes per GEMM launch of the workload (stated in the same file)
     assert isinstance(t, int) and alg <= t < 2 * alg
     assert bench.measured_traffic("no_such_workload") is None
     text = open(os.path.join(ROOT, "profiles", "forward_c2_deit_s_hbm_traffic.txt")).read()
     assert "algorithmic_bytes_per_launch: %d" % alg in text and "rocprofv3 --pmc FETCH_SIZE" in text
+    # the summary names the build it was taken with; against another build the figure is withheld
+    build = [l.split(":", 1)[1].strip() for l in text.splitlines() if l.startswith("build_id:")]
+    assert len(build) == 1 and bench.measured_traffic("c2_deit_s", build[0]) == t
+    assert bench.measured_traffic("c2_deit_s", "0" * 16) is None
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -388,7 +388,7 @@ def test_linear_requant_narrow_multiplier_path_at_its_limits(ivit, dense_path, K
 FLOOR_SHAPES = [(65, 192, 64, None), (5, 7, 80, None), (1000, 384, 384, "many_rows"), (300, 384, 1536, "many_rows"),
                 (257, 130, 3072, "many_rows"), (333, 208, 96, "many_rows"), (30011, 128, 384, None),
                 (1000, 1152, 384, "reg_stationary"), (4100, 384, 384, "reg_stationary"), (515, 256, 768, "reg_stationary"),
-                (700, 384, 1536, "reg_stationary")]
+                (700, 384, 1536, "reg_stationary"), (700, 256, 512, "big_tiles")]
 
 
 @pytest.mark.parametrize("M,N,K,kernel", FLOOR_SHAPES)
@@ -423,6 +423,38 @@ RS_SHAPES = [(1, 32, 384), (31, 384, 384), (32, 96, 384), (33, 1152, 384), (197,
              # odd number of tiles per workgroup, partial slabs, more workgroups than tiles
              (1, 32, 1536), (32, 128, 1536), (33, 384, 1536), (197, 96, 1536), (1000, 384, 1536), (2500, 416, 1536),
              (8203, 384, 1536), (16400, 128, 1536), (300, 1536, 1536)]
+
+
+# the kernel with 256 x 128 tiles and both operands streamed: one tile, ragged last tiles, several tiles per workgroup
+# (more than 256 tiles), the shortest K it takes, long K
+TL_SHAPES = [(1, 128, 384), (255, 128, 640), (256, 256, 3072), (257, 128, 1024), (700, 384, 768), (5000, 768, 3072),
+             (40000, 256, 384), (33000, 384, 512)]
+
+
+@pytest.mark.parametrize("M,N,K", TL_SHAPES)
+@pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
+def test_linear_requant_big_tiles(ivit, M, N, K, epi):
+    x = synth.make_rows(M + N + K, M, K, "normal", 32.0)
+    x[0, :7] = -128; x[-1, -3:] = -128
+    w, bias, rq_b, rq_c = synth.make_linear(M * 7 + N, N, K)
+    w[0, :5] = -128
+    kw_o, kw_g = {}, {}
+    if epi == "residual":
+        res = synth.make_rows(N + 1, M, N, "uniform")
+        res[-1, ::3] = -128
+        kw_o = dict(residual=res, res_rq=(23456, 15)); kw_g = dict(residual=dev(res), res_rq=(23456, 15))
+    elif epi == "gelu":
+        kw_o = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)); kw_g = dict(kw_o)
+    y = empty((M, N))
+    ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y, kernel="big_tiles", **kw_g)
+    if M * N * K <= 6e9:
+        assert_same(host(y), orc.linear_requant(x, w, bias, rq_b, rq_c, **kw_o), "linear (big tiles) %s" % epi)
+    else:       # the oracle on a sample of rows (first and last tiles, and rows spread over the rest); every row against the other kernel
+        rows = np.unique(np.concatenate([np.arange(0, 300), np.arange(M - 300, M), np.arange(0, M, 97)]))
+        assert_same(host(y)[rows], orc.linear_requant(x[rows], w, bias, rq_b, rq_c, **({} if epi != "residual" else dict(residual=res[rows], res_rq=(23456, 15))) if epi != "gelu" else kw_o), "linear (big tiles) %s, sampled rows" % epi)
+        y2 = empty((M, N))
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), y2, kernel="many_rows", **kw_g)
+        assert bool((y == y2).all())
 
 
 @pytest.mark.parametrize("M,N,K", RS_SHAPES)
