@@ -13,10 +13,21 @@
 // lane fetches is free with LDS-direct loads, only where it lands is fixed).  One barrier per stage.  The epilogue is
 // that of gemm_rs.hip: tokens are the "A" operand, so a lane holds one channel and 16 tokens of an MFMA tile, the
 // requantisation constants of its channels sit in registers, and results (and the residual) pass through
-// wavefront-private LDS with the transposing LDS read so that global memory sees 16-byte pieces of rows.  That staging
-// lives in the buffer of the tile's last stage, whose refill waits until the epilogue is over.
+// wavefront-private LDS with the transposing LDS read so that global memory sees 16-byte pieces of rows.
+//
+// With one wavefront per SIMD nothing else runs while a wavefront works through its epilogue, about a third of a tile's
+// time at K = 3072.  So the finished accumulators move to a second register set (the accumulators of the tile being
+// multiplied live in AGPRs) and their epilogue rides along with the next tile's first eighteen stages, half a result
+// between two pairs of MFMAs; the residual values arrive one MFMA tile at a time through a 1 KB slot per wavefront,
+// requested two stages ahead.  Tiles with fewer than eighteen stages, the last tile of a workgroup and parameters
+// outside the 24-bit form take the epilogue alone, between two tiles.  Measured on 50432 x 768 x 3072 (one session):
+// tiled kernel of gemm_i8.hip 212 us, this kernel with 64-byte stages 186 us, with 128-byte stages 162 us, with the
+// epilogue riding along 150 us; without its loads 130 us, without loads and fragment reads 109 us: the one
+// instruction stream per SIMD is what bounds it.
 #include "regst_common.hpp"
 #include <algorithm>
+#include <type_traits>
+#include <utility>
 
 namespace ivit {
 
@@ -40,24 +51,25 @@ struct TlLayout {
     static constexpr int STG = (TM + TN) * BK;                     // bytes of a stage
     static constexpr int DPW = (TM + TN) * (BK / 16) / 64 / TL_NW;  // load instructions per wavefront and stage
     static constexpr int XI = TM * (BK / 16) / 64 / TL_NW;          // ... of which the first XI fetch activations
-    static constexpr int OT = 32 * 2 * OP;                         // output staging tile of a wavefront (two channel tiles)
-    static constexpr int RP = 64 + 16, RS16 = RP / 16;             // residual staging: pitch of a token row, 16-byte slots in it
-    static constexpr int RNI = (32 * RS16 + 63) / 64;
-    static constexpr int RT = RNI * 1024;
-    static constexpr int EW = OT + 2 * RT;                         // epilogue staging of a wavefront (inside a stage buffer)
-    static constexpr int LUT = NS * STG;
-    static constexpr int TOTAL = LUT + 256;
+    static constexpr int OPT = 32;                                 // output staging of a wavefront: [64 channels][32 tokens]
+    static constexpr int OT = 64 * OPT;
+    static constexpr int RT = 32 * 32;                             // residual staging of a wavefront: [32 tokens][32 channels]
+    static constexpr int LUT = NS * STG, OUT = LUT + 256, RES = OUT + TL_NW * OT;
+    static constexpr int TOTAL = RES + TL_NW * RT;
     static_assert(DPW * 64 * TL_NW * 16 == STG && XI * 64 * TL_NW * 16 == TM * BK, "whole load instructions");
-    static_assert(DPW >= 8 && KSTEPS == 4 && (NS - 1) * DPW <= 63, "load schedule, wait counts");
-    static_assert(TL_NW * EW <= STG && TOTAL + 1024 <= 160 * 1024, "LDS");
+    static_assert(DPW >= 8 && KSTEPS == 4 && 2 * DPW + 2 <= 63, "load schedule, wait counts");
+    static_assert(TOTAL + 1024 <= 160 * 1024, "LDS");
 };
 
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f) {
+    [&]<int... I>(std::integer_sequence<int, I...>) { (f(std::integral_constant<int, I>()), ...); }(std::make_integer_sequence<int, N>());
+}
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
 
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_tl_kernel(TlParams P) {
     using LY = TlLayout;
-    constexpr int STG = LY::STG, DPW = LY::DPW, XI = LY::XI, OT = LY::OT, RP = LY::RP, RS16 = LY::RS16, RNI = LY::RNI, RT = LY::RT;
+    constexpr int STG = LY::STG, DPW = LY::DPW, XI = LY::XI;
     constexpr int NW = TL_NW;
 
     extern __shared__ __align__(1024) int8_t lds[];
@@ -111,13 +123,18 @@ __global__ __launch_bounds__(256) void gemm_tl_kernel(TlParams P) {
         const uint32_t dst = lds0 + buf * STG + i * (NW * 1024);
         if (i < XI) dma16(iss_x, x_off[i], dst); else dma16(iss_w, w_off[i - XI], dst);
     };
-    auto issue_done = [&]() __attribute__((always_inline)) {       // on to the next stage
-        ++issued; iss_x += BK; iss_w += BK;
-        if (++iss_s == S) { iss_s = 0; iss_tile += G; if (issued < total_stages) issue_setup(); }
+    // on to the next stage; after the last one the request side stays where it is, and the loads that the remaining
+    // stages still issue (every stage issues its twelve, which keeps the wait counts fixed) fetch that stage again,
+    // into a buffer nobody reads any more
+    auto issue_done = [&]() __attribute__((always_inline)) {
+        if (++issued < total_stages) {
+            iss_x += BK; iss_w += BK;
+            if (++iss_s == S) { iss_s = 0; iss_tile += G; issue_setup(); }
+        }
     };
     issue_setup();
 #pragma unroll 1
-    for (int g = 0; g < NS && g < total_stages; ++g) {
+    for (int g = 0; g < NS; ++g) {                              // (a tile has three stages at least)
 #pragma unroll
         for (int i = 0; i < DPW; ++i) issue_one(i, g);
         issue_done();
@@ -137,22 +154,20 @@ __global__ __launch_bounds__(256) void gemm_tl_kernel(TlParams P) {
         for (int nt = 0; nt < 2; ++nt) fb[kk][nt] = *reinterpret_cast<const v4i*>(st + b_row0 + nt * 32 * BK + sw[kk]);
     };
 
-    // ---- epilogue state (as in gemm_rs.hip with two channel tiles per wavefront)
-    int rs_row[RNI], rs_colo[RNI];
-#pragma unroll
-    for (int i = 0; i < RNI; ++i) {
-        const int s = 64 * i + lane;
-        rs_row[i] = min(s / RS16, 31);
-        rs_colo[i] = wn * 64 + 16 * min(s % RS16, 3);
-    }
-    const int rr_base = ((lane >> 5) * 16 + ((lane & 15) >> 1)) * RP + 16 * ((lane >> 4) & 1) + 8 * (lane & 1);
+    // ---- epilogue state.  The epilogue of a tile runs while the next tile is multiplied: its accumulators move to a
+    // second set of registers (prev), and the 16 half-units of work (a unit is one MFMA tile of 32 tokens x 32 channels;
+    // eight per wavefront) are spread over the k-steps of 16 stages, two results a k-step.
+    int8_t* out_w = lds + LY::OUT + wv * LY::OT;               // [64 channels][32 tokens] of one token group
+    int8_t* res_w = lds + LY::RES + wv * LY::RT;               // [32 tokens][32 channels] of one unit
+    const uint32_t res_off = lds_offset(res_w);
+    const int rr_base = ((lane >> 5) * 16 + ((lane & 15) >> 1)) * 32 + 16 * ((lane >> 4) & 1) + 8 * (lane & 1);
     int st_src[2];
     uint32_t st_dst[2];
 #pragma unroll
     for (int s = 0; s < 2; ++s) {
         const int B = lane >> 4, o_src = lane & 1, b = (lane & 15) >> 1, o_dst = (lane >> 3) & 1, j = lane & 7;
         const int hs = 8 * s + 2 * B + o_src, hd = 8 * s + 2 * B + o_dst;
-        st_src[s] = (16 * (hs % 4) + b) * OP + 8 * (hs / 4);
+        st_src[s] = (16 * (hs % 4) + b) * LY::OPT + 8 * (hs / 4);
         st_dst[s] = (uint32_t)((8 * (hd / 4) + j) * N + 16 * (hd % 4));
     }
     const int32_t rb = P.res_rq.b, rc = P.res_rq.c, rh = P.rnd << ((P.res_rq.c - 1) & 31);
@@ -171,95 +186,38 @@ __global__ __launch_bounds__(256) void gemm_tl_kernel(TlParams P) {
         sh24 = 23;
         res_24 = res_ok;
     }
+    // of the tile whose results wait in prev
+    int64_t p_row = 0;                                          // first token of the wavefront's part
+    int p_n0 = 0;                                               // first channel
+    int32_t c_lo[2], c_hi[2], c_mb[2], c_ad[2], pb[2], pc[2], pbias[2];
+    bool fast24 = false;
+    v2i rw[2] = {};                                             // the unit's residual values, as the accumulators lie
+    v4i ow = {};                                                // its results, four tokens a register
 
-    v16i acc[4][2];
-    __syncthreads();                                            // the ShiftGELU table
-    // the first stage
-    {
-        if (total_stages >= 3) wait_vm<2 * DPW>(); else if (total_stages == 2) wait_vm<DPW>(); else wait_vm0();
-        __syncthreads();
-        read_frags(0, 0);
-        read_frags(0, 1);
-    }
+    v16i acc[4][2], prev[4][2];
 
-    int g = 0, cur = 0;                                         // stage being multiplied (counted over all tiles), its buffer
-#pragma unroll 1
-    for (int t = L; t < ntiles; t += G) {
+    // the residual values of unit u = 2 mt + cb: one load instruction, two lanes a token
+    auto res_issue = [&](int u) __attribute__((always_inline)) {
+        const int64_t r0 = p_row + 32 * (u >> 1);
+        const int rows = (int)max64(min64(M - r0, 32), 0);
+        const int8_t* base = uniform_ptr(rows > 0 ? P.residual + r0 * N : P.residual + (M - 1) * N);
+        const int last = __builtin_amdgcn_readfirstlane(max(rows, 1) - 1);
+        dma16(base, (uint32_t)(__mul24(min(lane >> 1, last), N) + p_n0 + 32 * (u & 1) + 16 * (lane & 1)), res_off);
+    };
+    auto res_read = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = v16i{};
-        int held = 0;
-#pragma unroll 1
-        for (int s = 0; s < S; ++s, ++g) {
-            // ---- first half of the stage: fetch the fragments of its second half, multiply
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                read_frags(cur, kk + 2);
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[kk][mt], fb[kk][nt], acc[mt][nt], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            // ---- second half: the next stage has to be there (loads complete in order: all but those of the one stage
-            // that may have been requested after it), and once every wavefront is here nobody reads this stage's buffer
-            // any more (all its fragments are in registers: the barrier waits for the LDS reads too)
-            if (issued - (g + 2) >= 1) wait_vm<DPW>(); else wait_vm0();
-            __syncthreads();
-            const int nxt = cur + 1 == NS ? 0 : cur + 1;
-            const bool more = g + 1 < total_stages;
-            // stage g + NS goes into the buffer of stage g; after the last stage of a tile the epilogue borrows that
-            // buffer first
-            const bool req = issued < total_stages && s + 1 < S;
-#pragma unroll
-            for (int kk = 2; kk < 4; ++kk) {
-                if (more) read_frags(nxt, kk - 2);
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt) {
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[kk][mt], fb[kk][nt], acc[mt][nt], 0, 0, 0);
-                    if (req) {
-#pragma unroll
-                        for (int i = 0; i < DPW; ++i)
-                            if (i * 8 / DPW == (kk - 2) * 4 + mt) issue_one(i, cur);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            if (req) issue_done();
-            held = cur;
-            cur = nxt;
-        }
-
-        // ---- epilogue of tile t: this wavefront's 4 x 2 MFMA tiles, one group of 32 tokens at a time
-        const int tm = t / P.tiles_n, tn = t % P.tiles_n;
-        const int n0w = tn * TN + wn * 64;
-        const int64_t row_w = (int64_t)tm * TM + wm * 128;      // first token of the wavefront's part
-        int8_t* out_w = lds + held * STG + wv * LY::EW;         // staging: the buffer of the tile's last stage
-        int8_t* res_w = out_w + OT;
-        const uint32_t res_off = lds_offset(res_w);
-        // requantisation constants of the lane's two channels (24-bit form, derivation in gemm_rs.hip)
-        int32_t c_lo[2], c_hi[2], c_mb[2], c_ad[2], pb[2], pc[2], pbias[2];
+        for (int h = 0; h < 2; ++h)
+            rw[h] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(res_w + rr_base + 8 * h * 32));
+    };
+    // constants of the tile in prev: requantisation in the 24-bit form (derivation in gemm_rs.hip) where every channel of
+    // the wavefront admits it
+    auto epi_begin = [&]() __attribute__((always_inline)) {
         bool chan_24 = res_24;
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            const int ch = n0w + 32 * cb + lj;
+            const int ch = p_n0 + 32 * cb + lj;
             pb[cb] = P.rq_b[ch]; pc[cb] = P.rq_c[ch]; pbias[cb] = P.bias ? P.bias[ch] : 0;
         }
-        // the residual tiles of the first two token groups, while the constants are worked out
-        auto res_span_issue = [&](int mt, int half) __attribute__((always_inline)) {
-            const int64_t r0 = row_w + 32 * mt;
-            const int rows = (int)max64(min64(M - r0, 32), 0);
-            const int8_t* base = uniform_ptr(rows > 0 ? P.residual + r0 * N : P.residual + (M - 1) * N);
-            const int last = __builtin_amdgcn_readfirstlane(max(rows, 1) - 1);
-#pragma unroll
-            for (int i = 0; i < RNI; ++i)
-                dma16(base, (uint32_t)(__mul24(min(rs_row[i], last), N) + n0w - wn * 64 + rs_colo[i]), res_off + half * RT + i * 1024);
-        };
-        if (EPI == EPI_RESIDUAL) { res_span_issue(0, 0); res_span_issue(1, 1); }
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
             int32_t lo = 0, hi = 0, mb = 0, ad = 0;
@@ -277,80 +235,214 @@ __global__ __launch_bounds__(256) void gemm_tl_kernel(TlParams P) {
             c_lo[cb] = lo; c_hi[cb] = hi; c_mb[cb] = mb; c_ad[cb] = ad;
         }
         // (nothing in the epilogue is shared between wavefronts: each decides for itself)
-        const bool fast24 = __builtin_amdgcn_ballot_w64(chan_24) == ~0ull;
-        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");  // the last MFMAs have written the accumulators (asm readers below)
-        __builtin_amdgcn_sched_barrier(0);
+        fast24 = __builtin_amdgcn_ballot_w64(chan_24) == ~0ull;
+    };
+    // results 4 d + r0 and 4 d + r0 + 1 of unit (mt, cb), 24-bit form
+    auto epi_pair = [&](auto mtc, auto cbc, auto dc, auto r0c) __attribute__((always_inline)) {
+        constexpr int mt = decltype(mtc)::value, cb = decltype(cbc)::value, d = decltype(dc)::value, r0 = decltype(r0c)::value;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            v2i rw[2][2] = {};
+        for (int r = r0; r < r0 + 2; ++r) {
+            const int32_t m = med3(prev[mt][cb][4 * d + r], c_lo[cb], c_hi[cb]);
+            uint32_t o;
             if (EPI == EPI_RESIDUAL) {
-                // its residual tile has landed: requested two token groups earlier, and what was requested after it is
-                // the next group's residual tile and the stores of the groups in between
-                if (mt == 0) wait_vm<RNI>(); else if (mt == 1) wait_vm<RNI + 2>(); else if (mt == 2) wait_vm<RNI + 4>(); else wait_vm<4>();
-                const int8_t* tr = res_w + (mt & 1) * RT + rr_base;
-#pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h)
-                        rw[cb][h] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(tr + 8 * h * RP + 32 * cb));
+                const int32_t t1 = (__mul24(m, c_mb[cb]) + c_ad[cb]) >> 23;
+                const int32_t res = (int32_t)(int8_t)((uint32_t)rw[d >> 1][d & 1] >> (8 * r));
+                const int32_t t2 = (__mul24(res, rb) + rh) >> rc;
+                o = (uint32_t)clamp8(t1 + t2) & 0xffu;
+            } else {
+                o = (uint32_t)(__mul24(m, c_mb[cb]) + c_ad[cb]) >> 24;
+                if (EPI == EPI_GELU) o = (uint32_t)(uint8_t)gelu_lut[o];
             }
+            if (r == 0) ow[d] = (int)o; else ow[d] |= (int)(o << (8 * r));
+        }
+    };
+    // the same in 64-bit arithmetic, a whole unit
+    auto epi_unit_slow = [&](auto mtc, auto cbc) __attribute__((always_inline)) {
+        constexpr int mt = decltype(mtc)::value, cb = decltype(cbc)::value;
 #pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
-                v4i ow;
+        for (int d = 0; d < 4; ++d) {
+            uint32_t o[4];
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    uint32_t o[4];
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int32_t a = acc[mt][cb][4 * d + r];
-                        if (fast24) {
-                            const int32_t m = med3(a, c_lo[cb], c_hi[cb]);
-                            if (EPI == EPI_RESIDUAL) {
-                                const int32_t t1 = (__mul24(m, c_mb[cb]) + c_ad[cb]) >> 23;
-                                const int32_t res = (int32_t)(int8_t)((uint32_t)rw[cb][d >> 1][d & 1] >> (8 * r));
-                                const int32_t t2 = (__mul24(res, rb) + rh) >> rc;
-                                o[r] = (uint32_t)clamp8(t1 + t2) & 0xffu;
-                            } else {
-                                o[r] = (uint32_t)(__mul24(m, c_mb[cb]) + c_ad[cb]) >> 24;
-                                if (EPI == EPI_GELU) o[r] = (uint32_t)(uint8_t)gelu_lut[o[r]];
-                            }
-                        } else {
-                            int64_t r64 = rnd_shift64(a + pbias[cb], pb[cb], pc[cb], P.rnd);
-                            if (EPI == EPI_RESIDUAL) {
-                                const int32_t res = (int32_t)(int8_t)((uint32_t)rw[cb][d >> 1][d & 1] >> (8 * r));
-                                r64 += rnd_shift64(res, P.res_rq.b, P.res_rq.c, P.rnd);
-                            }
-                            int32_t v = clamp8_64(r64);
-                            if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
-                            o[r] = (uint32_t)v & 0xffu;
-                        }
-                    }
-                    ow[d] = (int)(o[0] | (o[1] << 8) | (o[2] << 16) | (o[3] << 24));
+            for (int r = 0; r < 4; ++r) {
+                int64_t r64 = rnd_shift64(prev[mt][cb][4 * d + r] + pbias[cb], pb[cb], pc[cb], P.rnd);
+                if (EPI == EPI_RESIDUAL) {
+                    const int32_t res = (int32_t)(int8_t)((uint32_t)rw[d >> 1][d & 1] >> (8 * r));
+                    r64 += rnd_shift64(res, P.res_rq.b, P.res_rq.c, P.rnd);
                 }
-                *reinterpret_cast<v4i*>(out_w + (32 * cb + lj) * OP + 16 * lg) = ow;
+                int32_t v = clamp8_64(r64);
+                if (EPI == EPI_GELU) v = gelu_lut[(uint8_t)v];
+                o[r] = (uint32_t)v & 0xffu;
             }
-            if (EPI == EPI_RESIDUAL && mt + 2 < 4) {            // (its half has been read: the values are in use above)
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                res_span_issue(mt + 2, mt & 1);
-            }
-            const int64_t r0 = row_w + 32 * mt;
+            ow[d] = (int)(o[0] | (o[1] << 8) | (o[2] << 16) | (o[3] << 24));
+        }
+    };
+    // a finished unit goes to the staging tile; with the second unit of a token group the group goes to global memory
+    auto epi_put = [&](auto mtc, auto cbc) __attribute__((always_inline)) {
+        constexpr int mt = decltype(mtc)::value, cb = decltype(cbc)::value;
+        *reinterpret_cast<v4i*>(out_w + (32 * cb + lj) * LY::OPT + 16 * lg) = ow;
+        if (cb == 1) {
+            const int64_t r0 = p_row + 32 * mt;
             const int rows = __builtin_amdgcn_readfirstlane((int)max64(min64(M - r0, 32), 0));
             const __amdgpu_buffer_rsrc_t y_buf =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(uniform_ptr(P.y + r0 * N + n0w)), 0, rows * N, 0x00020000);
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t*>(uniform_ptr(P.y + r0 * N + p_n0)), 0, rows * N, 0x00020000);
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
                 const v2i a = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(out_w + st_src[s2]));
-                const v2i b = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(out_w + st_src[s2] + 8 * OP));
+                const v2i b = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(out_w + st_src[s2] + 8 * LY::OPT));
                 __builtin_amdgcn_raw_buffer_store_b128(v4i{a[0], a[1], b[0], b[1]}, y_buf, (int)st_dst[s2], 0, 0);
             }
         }
-        // the held-back stage, once no wavefront uses the staging any more
-        if (issued < total_stages) {
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < DPW; ++i) issue_one(i, held);
-            issue_done();
+    };
+    // the whole epilogue of the tile in prev, nothing else going on (short rows, the last tile, or 64-bit arithmetic)
+    auto epi_alone = [&]() __attribute__((always_inline)) {
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");  // (the last MFMAs have written their results)
+        static_for<8>([&](auto uc) __attribute__((always_inline)) {
+            constexpr int u = decltype(uc)::value;
+            const std::integral_constant<int, u / 2> mtc; const std::integral_constant<int, u % 2> cbc;
+            if (EPI == EPI_RESIDUAL) {
+                if (u > 0) res_issue(u);                        // (unit 0 was requested when the tile ended)
+                wait_vm0();
+                res_read();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // before the next unit's values overwrite the slot
+            }
+            if (fast24) {
+                static_for<8>([&](auto qc) __attribute__((always_inline)) {
+                    constexpr int q = decltype(qc)::value;
+                    epi_pair(mtc, cbc, std::integral_constant<int, q / 2>(), std::integral_constant<int, 2 * (q % 2)>());
+                });
+            } else {
+                epi_unit_slow(mtc, cbc);
+            }
+            epi_put(mtc, cbc);
+        });
+    };
+
+    __syncthreads();                                            // the ShiftGELU table
+    // the first stage
+    {
+        wait_vm<2 * DPW>();
+        __syncthreads();
+        read_frags(0, 0);
+        read_frags(0, 1);
+    }
+
+    int cur = 0;                                                // buffer of the stage being multiplied
+    constexpr bool RES = EPI == EPI_RESIDUAL;
+    // One stage.  U = -1: nothing else; U = 0 .. 15: half-unit U of the epilogue of the tile in prev rides along (unit
+    // U / 2, results 8 (U % 2) .. + 7 of a lane).  Other vector memory instructions of the epilogue, all before the
+    // stage's own loads: with the first half of unit u the request for the residual values of unit u + 1; and after
+    // the second half of a token group's second unit two stores (epi_put, called by the tile loop).
+    int32_t tq = 0;                                             // a result half done
+    auto stage = [&](auto uc) __attribute__((always_inline)) {
+        constexpr int U = decltype(uc)::value;
+        constexpr bool EP = U >= 0;
+        constexpr int unit = EP ? U / 2 : 0, ph = EP ? U % 2 : 0, emt = unit / 2, cb = unit % 2;
+        auto extras = [](int u) constexpr {
+            if (u < 0) return 0;
+            return u % 2 == 0 ? (RES && u / 2 < 7 ? 1 : 0) : ((u / 2) % 2 == 1 ? 2 : 0);
+        };
+        const int nxt = cur + 1 == NS ? 0 : cur + 1;
+        if (EP && ph == 0 && RES) {
+            // requested two stages ago, before the loads of those stages and the stores of the stage between
+            wait_vm<2 * DPW + extras(U - 1)>();
+            res_read();
         }
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (kk == 2) {
+                // the next stage has to be there (loads complete in order; younger than the loads of stage g + 1 are the
+                // stores after the stage before last, the request of the last stage, its loads, the stores after it, the
+                // request of this stage), and once every wavefront is here nobody reads this stage's buffer any more (all
+                // its fragments are in registers: the barrier waits for the LDS reads too)
+                wait_vm<DPW + (U >= 2 && U % 2 == 1 ? extras(U - 2) : 0) + (U >= 1 ? extras(U - 1) : 0) + extras(U)>();
+                __syncthreads();
+            }
+            read_frags(kk < 2 ? cur : nxt, (kk + 2) % 4);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[kk][mt], fb[kk][nt], acc[mt][nt], 0, 0, 0);
+                if (kk >= 2) {                                  // stage g + NS goes into the buffer of stage g
+#pragma unroll
+                    for (int i = 0; i < DPW; ++i)
+                        if (i * 8 / DPW == (kk - 2) * 4 + mt) issue_one(i, cur);
+                }
+                if (EP) {
+                    // half a result per pair of MFMAs, each half ending in a statement that keeps it in its place
+                    const int v = 2 * kk + (mt >> 1), d = 2 * ph + (v >> 2), r = v & 3;     // (constants once the loops are unrolled)
+                    if ((mt & 1) == 0) {
+                        const int32_t m = med3(prev[emt][cb][4 * d + r], c_lo[cb], c_hi[cb]);
+                        if (RES) tq = (__mul24(m, c_mb[cb]) + c_ad[cb]) >> 23;
+                        else {
+                            tq = (int32_t)((uint32_t)(__mul24(m, c_mb[cb]) + c_ad[cb]) >> 24);
+                            if (EPI == EPI_GELU) tq = (int32_t)(uint8_t)gelu_lut[tq];
+                        }
+                        asm volatile("" : "+v"(tq));
+                    } else {
+                        uint32_t o = (uint32_t)tq;
+                        if (RES) {
+                            const int32_t res = (int32_t)(int8_t)((uint32_t)rw[d >> 1][d & 1] >> (8 * r));
+                            const int32_t t2 = (__mul24(res, rb) + rh) >> rc;
+                            o = (uint32_t)clamp8(tq + t2) & 0xffu;
+                        }
+                        int32_t w = r == 0 ? (int32_t)o : (ow[d] | (int32_t)(o << (8 * r)));
+                        asm volatile("" : "+v"(w));
+                        ow[d] = w;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (EP && kk == 0 && ph == 0 && RES && unit < 7) {
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this unit's values are in registers
+                res_issue(unit + 1);
+            }
+        }
+        issue_done();
+        cur = nxt;
+    };
+
+    bool have_prev = false;
+#pragma unroll 1
+    for (int it = 0; it <= my_tiles; ++it) {
+        const bool tile = it < my_tiles;
+        bool ride = false;                                      // the epilogue rides along with this tile's stages
+        if (have_prev) {
+            epi_begin();
+            ride = tile && fast24 && S >= 18;
+            if (!ride) epi_alone();
+        }
+        if (!tile) break;
+        const int t = L + it * G;
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = v16i{};
+        int s = 0;
+        if (ride) {
+            stage(std::integral_constant<int, -1>());
+            stage(std::integral_constant<int, -1>());
+            static_for<16>([&](auto uc) __attribute__((always_inline)) {
+                stage(uc);
+                if (decltype(uc)::value % 2 == 1) epi_put(std::integral_constant<int, decltype(uc)::value / 4>(),
+                                                          std::integral_constant<int, (decltype(uc)::value / 2) % 2>());
+            });
+            s = 18;
+        }
+#pragma unroll 1
+        for (; s < S; ++s) stage(std::integral_constant<int, -1>());
+
+        // the tile's results wait in prev for their epilogue; its first residual values are on their way
+        const int tm = t / P.tiles_n, tn = t % P.tiles_n;
+        p_row = (int64_t)tm * TM + wm * 128;
+        p_n0 = tn * TN + wn * 64;
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) prev[mt][nt] = acc[mt][nt];
+        if (RES) res_issue(0);
+        have_prev = true;
     }
     wait_vm0();
 }

@@ -426,9 +426,12 @@ RS_SHAPES = [(1, 32, 384), (31, 384, 384), (32, 96, 384), (33, 1152, 384), (197,
 
 
 # the kernel with 256 x 128 tiles and both operands streamed: one tile, ragged last tiles, several tiles per workgroup
-# (more than 256 tiles), the shortest K it takes, long K
+# (more than 256 tiles), the shortest K it takes, long K; with 18 stages or more (K >= 2304) and a second tile in the
+# workgroup the epilogue of a tile runs inside the next tile's k-loop: 18 stages exactly, 20 (the last tile's last
+# stages request nothing more), 24
 TL_SHAPES = [(1, 128, 384), (255, 128, 640), (256, 256, 3072), (257, 128, 1024), (700, 384, 768), (5000, 768, 3072),
-             (40000, 256, 384), (33000, 384, 512)]
+             (40000, 256, 384), (33000, 384, 512), (17000, 512, 2304), (9001, 1024, 2560), (33000, 384, 3072),
+             (16500, 512, 2048)]
 
 
 @pytest.mark.parametrize("M,N,K", TL_SHAPES)
