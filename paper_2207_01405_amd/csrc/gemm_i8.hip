@@ -812,7 +812,7 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     const bool ws = ws_plan(a, ncb, unit, nunits, pitch, lds_bytes);
     // rows too long for the weight-stationary kernels: 256 x 128 tiles with both operands streamed (gemm_tl.hip), when
     // there are tiles enough to go round.  Its cost per tile outside the k-loop only pays off for long rows: on the
-    // 768-wide model it takes the second MLP layer (K = 3072) from 210 to 162 us and loses at K = 768 (QKV 174 against
+    // 768-wide model it takes the second MLP layer (K = 3072) from 212 to 150 us and loses at K = 768 (QKV 174 against
     // 124 us with the tiled kernel below)
     if (linear_tl_takes(a) && (a.kernel == LINEAR_BIG_TILES ||
                                (a.kernel == LINEAR_AUTO && !ws && a.K >= 2048 && (a.M + 255) / 256 * (a.N / 128) >= num_cus())))

@@ -1,4 +1,4 @@
-// Pieces shared by the Dense kernels that keep their weights in registers (gemm_rs.hip, gemm_ks.hip): LDS-direct
+// Pieces shared by the Dense kernels built on LDS-direct loads (gemm_rs.hip, gemm_ks.hip, gemm_tl.hip): those
 // loads, scalar pointers, the median of three, the token order of the MFMA "A" operand.
 #pragma once
 #include "ivit_kernels.hpp"
