@@ -249,7 +249,7 @@ def main():
                              gbs=round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1))
     achieved, g_ms, g_ops, g_n = gemm_family(kinds)
     traffic = measured_traffic(args.workload, build_id)
-    roofline = dict(bound="mfma", kernel="Dense kernels with requantisation epilogues (gemm_rs_kernel: QKV, fc1; gemm_ws_kernel: proj, fc2)",
+    roofline = dict(bound="mfma", kernel="Dense kernels with requantisation epilogues (gemm_rs_kernel: QKV, fc1; gemm_ks_kernel: fc2; gemm_ws_kernel: proj)",
                     achieved=round(achieved, 1), peak=PEAK_INT8_TOPS, unit="TOP/s",
                     frac=round(achieved / PEAK_INT8_TOPS, 4), traffic=traffic,
                     traffic_note=None if traffic is not None else "no hardware-counter summary of this build of the library under profiles/",
