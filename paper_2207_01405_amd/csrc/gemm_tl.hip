@@ -460,7 +460,7 @@ hipError_t launch_tl(hipStream_t s, const TlParams& P, int grid) {
 // offsets inside a tile are 32-bit.
 bool linear_tl_takes(const LinearArgs& a) {
     if (a.K < NS * BK || (a.K % BK) != 0 || (a.N % TN) != 0) return false;
-    if ((int64_t)TM * a.K > 0x7fffffffLL || (int64_t)TN * a.K > 0x7fffffffLL || (int64_t)32 * a.N > 0x7fffffffLL) return false;
+    if ((int64_t)TM * a.K > 0x7fffffffLL || (int64_t)TN * a.K > 0x7fffffffLL || a.N >= (1 << 23)) return false;   // (N is a 24-bit factor)
     if ((a.M + TM - 1) / TM * (a.N / TN) > 0x7fffffffLL) return false;
     return (a.ldx == 0 || a.ldx == a.K) && a.M >= 1;
 }
