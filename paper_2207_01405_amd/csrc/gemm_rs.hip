@@ -39,6 +39,8 @@ struct RsParams {
     int rnd;                                 // 1: round to nearest, 0: floor (every requantisation of the epilogue)
 };
 
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory"); }
+
 template <int KS, int NCB, int EPI, int GR>
 struct RsLayout {
     static constexpr int NW = 4 * GR, NT = 64 * NW;               // wavefronts, threads
@@ -389,6 +391,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     v2i rw[NCB][2] = {};
     Cursor c_req, c_res, c_out, c_prev;                         // stage being requested, residual tile being requested, tile k, tile k - 1
     int par = 0;                                                // residual tile k is in half `par` of the residual staging
+    bool stored = false;                                        // the tile step before this one has issued stores
 
     // Token tile k in the stage buffer at offset b0 (the one at b1 holds stage k + 1, the one at b2 is free for stage
     // k + 2): multiply into `cur`.  With one wavefront per SIMD (GR == 1) there are two sets of accumulators and, when
@@ -416,7 +419,9 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             if (ks == SYNC) {
-                wait_vm0();
+                // this wavefront's loads have landed; the stores of the tile before, requested after them, may still be
+                // on their way (memory operations complete in the order of their requests)
+                if (stored) wait_vm<NCB>(); else wait_vm0();
                 __syncthreads();
             }
             // fragment ks + RG - 1: of the next tile once this one runs out (valid since the barrier of this tile)
@@ -444,11 +449,14 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
                 }
             }
             if (ks >= FIRST) {
+                // loads first, stores last: a wait for the loads then leaves the stores out
                 const int j = ks - FIRST;
-                if (ep && j >= 1 && j <= NCB) store_write(y_buf, j - 1, sa, sb);
-                if (ep && j < NCB) store_read(j, sa, sb);
+                constexpr int S0 = KS - FIRST - NCB - 1;        // step of the first store's LDS read
+                static_assert(S0 >= 0 && S0 + 1 >= NI - 1 && S0 + 1 >= RNI - 1, "stores follow the loads");
                 if (j < NI) issue_act_one(q_span, q_dst, j);
                 if (EPI == EPI_RESIDUAL && j < RNI) issue_res_one(r_span, r_dst, j);     // past the last tile: a repeat, never used
+                if (ep && j >= S0 + 1 && j <= S0 + NCB) store_write(y_buf, j - S0 - 1, sa, sb);
+                if (ep && j >= S0 && j < S0 + NCB) store_read(j - S0, sa, sb);
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -464,6 +472,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
             }
         }
         // on to tile k + 1
+        stored = ep;
         c_prev = c_out;
         advance(c_out, n_step);
         advance(c_req, x_step);
