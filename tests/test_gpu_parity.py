@@ -460,6 +460,37 @@ def test_linear_requant_big_tiles(ivit, M, N, K, epi):
         assert bool((y == y2).all())
 
 
+@pytest.mark.parametrize("rounding", ["nearest", "floor"])
+@pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
+def test_linear_requant_big_tiles_mixed_epilogue_forms(ivit, rounding, epi):
+    """Long rows and more tiles than workgroups, so that epilogues run inside the next tile's k-loop; eight channels
+    with a pair outside the 24-bit form make the wavefronts that own them take the 64-bit epilogue between two tiles
+    while the others carry on; both rounding modes.  Every row against the tiled kernel, a sample against the oracle."""
+    M, N, K = 17000, 512, 2304
+    x = synth.make_rows(11, M, K, "normal", 32.0)
+    w, bias, rq_b, rq_c = synth.make_linear(12, N, K)
+    rq_b[64:72] = 2 ** 31 - 1; rq_c[64:72] = 44
+    x[-1, -5:] = -128; w[3, :9] = -128
+    kw_o, kw_g = {}, {}
+    if epi == "residual":
+        res = synth.make_rows(13, M, N, "uniform")
+        kw_o = dict(residual=res, res_rq=(23456, 15)); kw_g = dict(residual=dev(res), res_rq=(23456, 15))
+    elif epi == "gelu":
+        kw_o = dict(gelu=synth.shift_params(32), gelu_rq=(24171, 21)); kw_g = dict(kw_o)
+    ys = {}
+    for kernel in ("big_tiles", "many_rows"):
+        ys[kernel] = empty((M, N))
+        ivit.ivit_linear_requant(dev(x), dev(w), dev(bias), dev(rq_b), dev(rq_c), ys[kernel], kernel=kernel, rounding=rounding, **kw_g)
+    assert bool((ys["big_tiles"] == ys["many_rows"]).all())
+    rows = np.unique(np.concatenate([np.arange(0, 260), np.arange(M - 260, M), np.arange(0, M, 211)]))
+    kw_s = dict(kw_o)
+    if epi == "residual":
+        kw_s["residual"] = res[rows]
+    want = orc.linear_requant(x[rows], w, bias, rq_b, rq_c, floor_shift=(rounding == "floor"), **kw_s)
+    assert_same(host(ys["big_tiles"])[rows], want, "linear (big tiles, mixed forms) %s %s" % (epi, rounding))
+    assert np.abs(want[:, 64:72].astype(np.int32)).max() > 0 and np.abs(want[:, :64].astype(np.int32)).mean() > 2
+
+
 @pytest.mark.parametrize("M,N,K", RS_SHAPES)
 @pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
 def test_linear_requant_weights_in_registers(ivit, M, N, K, epi):
