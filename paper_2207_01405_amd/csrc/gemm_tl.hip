@@ -332,7 +332,7 @@ __global__ __launch_bounds__(256) void gemm_tl_kernel(TlParams P) {
     // U / 2, results 8 (U % 2) .. + 7 of a lane).  Other vector memory instructions of the epilogue, all before the
     // stage's own loads: with the first half of unit u the request for the residual values of unit u + 1; and after
     // the second half of a token group's second unit two stores (epi_put, called by the tile loop).
-    int32_t tq = 0;                                             // a result half done
+    int32_t tq = 0, oq[3] = {};                                 // a result half done; the results waiting for the fourth of their register
     auto stage = [&](auto uc) __attribute__((always_inline)) {
         constexpr int U = decltype(uc)::value;
         constexpr bool EP = U >= 0;
@@ -369,26 +369,33 @@ __global__ __launch_bounds__(256) void gemm_tl_kernel(TlParams P) {
                         if (i * 8 / DPW == (kk - 2) * 4 + mt) issue_one(i, cur);
                 }
                 if (EP) {
-                    // half a result per pair of MFMAs, each half ending in a statement that keeps it in its place
+                    // half a result per pair of MFMAs, each half ending in a statement that keeps it in its place; the
+                    // four results of a register are put together by two byte permutes
                     const int v = 2 * kk + (mt >> 1), d = 2 * ph + (v >> 2), r = v & 3;     // (constants once the loops are unrolled)
                     if ((mt & 1) == 0) {
                         const int32_t m = med3(prev[emt][cb][4 * d + r], c_lo[cb], c_hi[cb]);
                         if (RES) tq = (__mul24(m, c_mb[cb]) + c_ad[cb]) >> 23;
-                        else {
-                            tq = (int32_t)((uint32_t)(__mul24(m, c_mb[cb]) + c_ad[cb]) >> 24);
-                            if (EPI == EPI_GELU) tq = (int32_t)(uint8_t)gelu_lut[tq];
-                        }
+                        else tq = __mul24(m, c_mb[cb]) + c_ad[cb];                          // result in the top byte
+                        if (EPI == EPI_GELU) tq = (int32_t)(uint8_t)gelu_lut[(uint32_t)tq >> 24];   // result in the low byte
                         asm volatile("" : "+v"(tq));
                     } else {
-                        uint32_t o = (uint32_t)tq;
+                        int32_t o = tq;
                         if (RES) {
                             const int32_t res = (int32_t)(int8_t)((uint32_t)rw[d >> 1][d & 1] >> (8 * r));
                             const int32_t t2 = (__mul24(res, rb) + rh) >> rc;
-                            o = (uint32_t)clamp8(tq + t2) & 0xffu;
+                            o = clamp8(tq + t2);                                            // result in the low byte
                         }
-                        int32_t w = r == 0 ? (int32_t)o : (ow[d] | (int32_t)(o << (8 * r)));
-                        asm volatile("" : "+v"(w));
-                        ow[d] = w;
+                        if (r == 3) {
+                            constexpr bool low = EPI != EPI_PLAIN;
+                            const uint32_t p01 = __builtin_amdgcn_perm((uint32_t)oq[1], (uint32_t)oq[0], low ? 0x0c0c0400u : 0x0c0c0703u);
+                            const uint32_t p23 = __builtin_amdgcn_perm((uint32_t)o, (uint32_t)oq[2], low ? 0x04000c0cu : 0x07030c0cu);
+                            o = (int32_t)(p01 | p23);
+                            asm volatile("" : "+v"(o));
+                            ow[d] = o;
+                        } else {
+                            asm volatile("" : "+v"(o));
+                            oq[r] = o;
+                        }
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
