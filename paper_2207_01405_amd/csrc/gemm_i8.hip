@@ -800,10 +800,13 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
         return hipGetLastError();
     }
     // weights in registers: K = 384 / 768 and enough rows for every workgroup to amortise loading them; measured against
-    // the kernels below on the DeiT-S and ViT-B shapes it wins on the layers without a residual (QKV 27.1 -> 23.0 us,
-    // fc1 35.5 -> 29.6 us at K = 384; 122 -> 92 us and 199 -> 149 us at K = 768) and loses on the projection, whose
-    // residual epilogue costs it more instructions per output (16.0 -> 21.2 us, 52 -> 60 us)
-    if (linear_rs_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && !a.residual && a.M >= 4096)))
+    // the kernels below on the DeiT-S and ViT-B shapes it wins on the layers without a residual (QKV 27.1 -> 21.6 us,
+    // fc1 35.5 -> 28.2 us at K = 384; 116 -> 82 us and 179 -> 127 us at K = 768).  With a residual its epilogue costs
+    // more instructions per output: at K = 384 it loses (projection 15.8 -> 19.6 us), at K = 768 it wins when the
+    // channels fill whole 256-channel slabs (N = 768: 52.6 -> 46.9 us at 50432 rows, 15.1 -> 13.6 us at 4100) and
+    // loses otherwise (N = 384: 21.1 -> 23.3 us; N = 192: 33.9 -> 34.5 us)
+    if (linear_rs_takes(a) && (a.kernel == LINEAR_REG_STATIONARY ||
+                               (a.kernel == LINEAR_AUTO && a.M >= 4096 && (!a.residual || (a.K == 768 && a.N % 256 == 0)))))
         return launch_linear_rs(s, a);
     // K = 1536: the same idea with K split over pairs of wavefronts (gemm_ks.hip)
     if (linear_ks_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && a.M >= 4096)))
