@@ -799,26 +799,29 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
         else hipLaunchKernelGGL(gemm_small_kernel<EPI_PLAIN>, g, b, 0, s, P);
         return hipGetLastError();
     }
-    // weights in registers: K = 384 / 768 and enough rows for every workgroup to amortise loading them; measured against
+    // weights in registers: K = 384 / 768 and more rows than a single image has; measured against
     // the kernels below on the DeiT-S and ViT-B shapes it wins on the layers without a residual (QKV 27.1 -> 21.6 us,
     // fc1 35.5 -> 28.2 us at K = 384; 116 -> 82 us and 179 -> 127 us at K = 768).  With a residual its epilogue costs
     // more instructions per output: at K = 384 it loses (projection 15.8 -> 19.6 us), at K = 768 it wins when the
     // channels fill whole 256-channel slabs (N = 768: 52.6 -> 46.9 us at 50432 rows, 15.1 -> 13.6 us at 4100) and
     // loses otherwise (N = 384: 21.1 -> 23.3 us; N = 192: 33.9 -> 34.5 us)
     if (linear_rs_takes(a) && (a.kernel == LINEAR_REG_STATIONARY ||
-                               (a.kernel == LINEAR_AUTO && a.M >= 4096 && (!a.residual || (a.K == 768 && a.N % 256 == 0)))))
+                               (a.kernel == LINEAR_AUTO && a.M > 256 && (!a.residual || (a.K == 768 && a.N % 256 == 0)))))
         return launch_linear_rs(s, a);
-    // K = 1536: the same idea with K split over pairs of wavefronts (gemm_ks.hip)
-    if (linear_ks_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && a.M >= 4096)))
+    // K = 1536: the same idea with K split over pairs of wavefronts (gemm_ks.hip).  Both also win on few rows, down to
+    // what the one-tile-per-workgroup kernel above takes (394 .. 3152 rows: QKV 10.4 -> 8.2 us, fc2 14.4 -> 10.0 us at
+    // the 384-wide model's shapes, 13.2 -> 9.8 us and 13.7 -> 10.4 us at the 768-wide model's)
+    if (linear_ks_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && a.M > 256)))
         return launch_linear_ks(s, a);
     int ncb, unit, nunits, pitch; size_t lds_bytes;
     const bool ws = ws_plan(a, ncb, unit, nunits, pitch, lds_bytes);
     // rows too long for the weight-stationary kernels: 256 x 128 tiles with both operands streamed (gemm_tl.hip), when
-    // there are tiles enough to go round.  Its cost per tile outside the k-loop only pays off for long rows: on the
-    // 768-wide model it takes the second MLP layer (K = 3072) from 212 to 150 us and loses at K = 768 (QKV 174 against
-    // 124 us with the tiled kernel below)
+    // there are tiles for half the compute units at least (6272 x 768 x 3072, 150 tiles: 37.8 -> 31.2 us; with fewer
+    // tiles a launch is one tile's latency either way).  Its cost per tile outside the k-loop only pays off for long
+    // rows: on the 768-wide model it takes the second MLP layer (K = 3072) from 212 to 148 us and loses at K = 768 (QKV
+    // 174 against 124 us with the tiled kernel below)
     if (linear_tl_takes(a) && (a.kernel == LINEAR_BIG_TILES ||
-                               (a.kernel == LINEAR_AUTO && !ws && a.K >= 2048 && (a.M + 255) / 256 * (a.N / 128) >= num_cus())))
+                               (a.kernel == LINEAR_AUTO && !ws && a.K >= 2048 && (a.M + 255) / 256 * (a.N / 128) >= num_cus() / 2)))
         return launch_linear_tl(s, a);
     if (ws) {
         WsParams W;
