@@ -133,7 +133,8 @@ int ivit_linear_requant(void* stream, const int8_t* x, const int8_t* w, const in
  *           IVIT_KERNEL_AUTO            chosen from the shape;
  *           IVIT_KERNEL_MANY_ROWS       never the kernel written for few rows;
  *           IVIT_KERNEL_REG_STATIONARY  the kernels that keep the weights in registers; they take K = 384, 768 or
- *                                       1536 with N % 32 == 0 only, other shapes give IVIT_ERR_SHAPE.
+ *                                       1536 (and K = 192 for layers without a residual) with N % 32 == 0 only,
+ *                                       other shapes give IVIT_ERR_SHAPE.
  *           IVIT_KERNEL_BIG_TILES       the kernel that streams both operands through LDS in 256 x 128 tiles; it
  *                                       takes K % 128 == 0, K >= 384, N % 128 == 0 only (else IVIT_ERR_SHAPE).
  *   rounding  how every dyadic requantisation of the layer (Sec. 3.2, Eq. 8-10: the output's, the residual's, the

@@ -12,8 +12,8 @@
 //   K = 768: the weights leave room for one wavefront per SIMD (GR = 1).  It has two sets of accumulators; while
 // token tile t is multiplied, the results of tile t - 1 are requantised between the MFMAs (an issued MFMA executes in
 // the background, and nothing else could fill the gaps).
-//   K = 384: two wavefronts per SIMD (GR = 2) with one set of accumulators each; a tile is requantised right after
-// its multiply while the other wavefront of the SIMD multiplies.
+//   K = 384 and K = 192: two wavefronts per SIMD (GR = 2) with one set of accumulators each; a tile is requantised
+// right after its multiply while the other wavefront of the SIMD multiplies.
 // Everything else a tile needs (one barrier, the loads of a later tile, the stores of an earlier one) is spread over
 // the k-steps, one piece per step.  What bounds the kernel is the rate at which a SIMD issues instructions of any kind
 // (about one per 4.4 cycles, measured), so the tile loop is written to need few of them: tile bookkeeping in 32-bit
@@ -58,14 +58,17 @@ struct RsLayout {
     static constexpr int XS1 = 0, OUT = 2 * XT, RES = OUT + NW * OT;
     static constexpr int LUT = RES + (EPI == EPI_RESIDUAL ? NW * 2 * RT : 0);
     static constexpr int MAIN = LUT + 256;
-    static constexpr int NCHUNK = NCB * (K / WCK);                 // weight chunks of the prologue
-    static constexpr int WNI = (WWI + NW - 1) / NW;                // load instructions per wavefront and chunk
+    static constexpr int CK = K < WCK ? K : WCK;                   // bytes of K per weight chunk of the prologue
+    static constexpr int CPITCH = CK + 16;                         // its row pitch in LDS
+    static constexpr int CWI = 4 * 32 * (CPITCH / 16) / 64;        // load instructions per chunk: [4 wavefronts][32 channels][CPITCH]
+    static constexpr int NCHUNK = NCB * (K / CK);                  // weight chunks of the prologue
+    static constexpr int WNI = (CWI + NW - 1) / NW;                // load instructions per wavefront and chunk
     static constexpr int WCHUNK = WNI * NW * 1024;                 // LDS bytes of a chunk (whole rounds of all wavefronts)
     static constexpr int STAGING = (NCHUNK > 1 ? 2 : 1) * WCHUNK;  // the chunks pass through the same memory, before the main loop
     static constexpr int XS0 = MAIN > STAGING ? MAIN : STAGING;
     static constexpr int TOTAL = XS0 + XT;
     __host__ __device__ static constexpr int stage_offset(int b) { return b == 0 ? XS0 : XS1 + (b - 1) * XT; }
-    static_assert(K % WCK == 0, "K must be a whole number of weight chunks");
+    static_assert(K % CK == 0 && (4 * 32 * (CPITCH / 16)) % 64 == 0, "K must be a whole number of weight chunks");
     static_assert(TOTAL + 1024 <= 160 * 1024, "LDS");
 };
 
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     constexpr int SYNC = KS / 2;                               // k-step of the barrier
     static_assert(KS % RG == 0, "ring must align with the tile");
     static_assert(SYNC >= 2 && SYNC <= KS - RG, "the first fragments of the next tile are read after the barrier");
-    static_assert(KS - SYNC >= NI && KS - SYNC >= RNI && KS - SYNC >= NCB + 1, "the work after the barrier is spread over its k-steps");
+    static_assert(KS - SYNC >= NI && (EPI != EPI_RESIDUAL || KS - SYNC >= RNI) && KS - SYNC >= NCB + 1, "the work after the barrier is spread over its k-steps");
 
     extern __shared__ __align__(1024) int8_t lds[];
     int8_t* Xs = lds;                                          // stage buffer b at LY::stage_offset(b), XT bytes each
@@ -168,16 +171,16 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
     // of whole rows (two chunks in flight), and every wavefront picks its fragments out of its part of the chunk.
     v4i W[NCB][KS];
     {
-        constexpr int NCHUNK = LY::NCHUNK, KH = K / WCK, W16 = WPITCH / 16;
+        constexpr int NCHUNK = LY::NCHUNK, CK = LY::CK, CPITCH = LY::CPITCH, KH = K / CK, W16 = CPITCH / 16;
         const uint32_t stg = lds_offset(lds);
         auto issue_chunk = [&](int c) __attribute__((always_inline)) {
             const int cb = c / KH, kh = c % KH;
 #pragma unroll
             for (int i = 0; i < WNI; ++i) {                     // (instructions past the chunk repeat its last row into the slack)
                 const int s = 64 * (i * NW + wv) + lane;
-                const int row = min(s / W16, 4 * 32 - 1), piece = min(s % W16, WCK / 16 - 1);
+                const int row = min(s / W16, 4 * 32 - 1), piece = min(s % W16, CK / 16 - 1);
                 const int ch = min((slab * 4 + (row >> 5)) * NCB + cb, Nt - 1) * 32 + (row & 31);
-                dma16(uniform_ptr(P.w), (uint32_t)(ch * K + kh * WCK + 16 * piece), stg + (c & 1) * WCHUNK + (i * NW + wv) * 1024);
+                dma16(uniform_ptr(P.w), (uint32_t)(ch * K + kh * CK + 16 * piece), stg + (c & 1) * WCHUNK + (i * NW + wv) * 1024);
             }
         };
         issue_chunk(0);
@@ -188,13 +191,13 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
             if (c + 1 < NCHUNK) asm volatile("s_waitcnt vmcnt(%0)" : : "n"(WNI) : "memory"); else wait_vm0();
             __syncthreads();
             const int cb = c / KH, kh = c % KH;
-            const int8_t* src = lds + (c & 1) * WCHUNK + (wq * 32 + lj) * WPITCH + 16 * lg;
+            const int8_t* src = lds + (c & 1) * WCHUNK + (wq * 32 + lj) * CPITCH + 16 * lg;
 #pragma unroll
-            for (int s = 0; s < WCK / 32; ++s) {
-                W[cb][kh * (WCK / 32) + s] = *reinterpret_cast<const v4i*>(src + 32 * s);
+            for (int s = 0; s < CK / 32; ++s) {
+                W[cb][kh * (CK / 32) + s] = *reinterpret_cast<const v4i*>(src + 32 * s);
                 // the weights are only ever read by MFMAs, which take this operand from the accumulation registers just
                 // as well: pinning them there leaves the ordinary vector registers to the accumulators and the epilogue
-                asm volatile("" : "+a"(W[cb][kh * (WCK / 32) + s]));
+                asm volatile("" : "+a"(W[cb][kh * (CK / 32) + s]));
             }
             __syncthreads();                                    // everyone has read the chunk: its memory is free again
             if (c + 2 < NCHUNK) issue_chunk(c + 2);
@@ -452,7 +455,7 @@ __global__ __launch_bounds__(256 * GR) void gemm_rs_kernel(RsParams P) {
                 // loads first, stores last: a wait for the loads then leaves the stores out
                 const int j = ks - FIRST;
                 constexpr int S0 = KS - FIRST - NCB - 1;        // step of the first store's LDS read
-                static_assert(S0 >= 0 && S0 + 1 >= NI - 1 && S0 + 1 >= RNI - 1, "stores follow the loads");
+                static_assert(S0 >= 0 && S0 + 1 >= NI - 1 && (EPI != EPI_RESIDUAL || S0 + 1 >= RNI - 1), "stores follow the loads");
                 if (j < NI) issue_act_one(q_span, q_dst, j);
                 if (EPI == EPI_RESIDUAL && j < RNI) issue_res_one(r_span, r_dst, j);     // past the last tile: a repeat, never used
                 if (ep && j >= S0 + 1 && j <= S0 + NCB) store_write(y_buf, j - S0 - 1, sa, sb);
@@ -556,18 +559,21 @@ hipError_t launch_rs_epi(hipStream_t s, RsParams& P, const LinearArgs& a) {
     P.stages = (int)((a.M + 32 * GR - 1) / (32 * GR));
     P.q = std::max(1, std::min(P.stages, num_cus() / P.slabs));
     const int grid = P.q * P.slabs;
-    if (a.residual) return launch_rs<EPI_RESIDUAL, KS, NCB, GR>(s, P, grid);
+    if (KS < 12 && a.residual) return hipErrorInvalidValue;     // (refused by linear_rs_takes)
+    if constexpr (KS >= 12) {                                   // (rows of 192 bytes: the tile's k-steps do not hold a residual layer's loads)
+        if (a.residual) return launch_rs<EPI_RESIDUAL, KS, NCB, GR>(s, P, grid);
+    }
     if (a.gelu) return launch_rs<EPI_GELU, KS, NCB, GR>(s, P, grid);
     return launch_rs<EPI_PLAIN, KS, NCB, GR>(s, P, grid);
 }
 
 }  // namespace
 
-// Shapes this kernel takes: K = 384 or 768 (the weights of a wavefront must fit its registers, and the k-steps are
-// unrolled), N a multiple of 32, dense rows, at most 2^30 of them; offsets inside the weight matrix and inside a token
+// Shapes this kernel takes: K = 384 or 768, or 192 without a residual (the weights of a wavefront must fit its
+// registers, and the k-steps are unrolled), N a multiple of 32, dense rows, at most 2^30 of them; offsets inside the weight matrix and inside a token
 // tile are 32-bit.
 bool linear_rs_takes(const LinearArgs& a) {
-    if (a.K != 384 && a.K != 768) return false;
+    if (a.K != 384 && a.K != 768 && !(a.K == 192 && !a.residual)) return false;
     if ((int64_t)a.N * a.K > 0x7fffffffLL) return false;
     if (a.M > (1 << 30)) return false;                         // row counts are kept in 32 bits
     return (a.N & 31) == 0 && (a.ldx == 0 || a.ldx == a.K) && a.M >= 1;
@@ -579,6 +585,7 @@ hipError_t launch_linear_rs(hipStream_t s, const LinearArgs& a) {
     P.residual = a.residual; P.res_rq = a.res_rq; P.gelu_p = a.gelu_p; P.gelu_rq = a.gelu_rq;
     P.y = a.y; P.M = a.M; P.N = a.N; P.ldx = a.K; P.rnd = a.floor_shift ? 0 : 1;
     // K = 384: 64 channels per wavefront leave room for two wavefronts per SIMD; K = 768: one
+    if (a.K == 192) return launch_rs_epi<6, 2, 2>(s, P, a);
     if (a.K == 384) return launch_rs_epi<12, 2, 2>(s, P, a);
     return launch_rs_epi<24, 2, 1>(s, P, a);
 }

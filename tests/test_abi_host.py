@@ -243,7 +243,8 @@ def test_linear_options_and_probe_arguments(lib):
     empty = binding.Dims(0, 65, 64, 2, 256)
     assert lib.ivit_window_attention_ex(None, None, None, None, 1, None, 1, None, C.byref(empty), DY, SP, DY, None, None,
                                         C.byref(binding.AttentionOptions(1))) == 0
-    # the register-stationary kernels take K = 384, 768 or 1536 with N % 32 == 0 and nothing else
+    # the register-stationary kernels take K = 384, 768 or 1536 (192 without a residual) with N % 32 == 0 and nothing else
+    assert ex(2, K=192, res=FAKE) == E["SHAPE"] and ex(2, K=192, M=0) == 0
     assert ex(2, K=512) == E["SHAPE"] and ex(2, N=48) == E["SHAPE"] and ex(2, K=3072) == E["SHAPE"]
     assert ex(2, K=1536, N=48) == E["SHAPE"] and ex(2, K=1536, M=0) == 0
     assert ex(2, M=0) == 0 and ex(0, M=0) == 0 and ex(None, M=0) == 0 and ex(1, M=0, K=512) == 0

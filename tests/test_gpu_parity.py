@@ -422,7 +422,9 @@ RS_SHAPES = [(1, 32, 384), (31, 384, 384), (32, 96, 384), (33, 1152, 384), (197,
              # K = 1536: the kernel that splits K over pairs of wavefronts (128 channels per workgroup): one tile, an even and an
              # odd number of tiles per workgroup, partial slabs, more workgroups than tiles
              (1, 32, 1536), (32, 128, 1536), (33, 384, 1536), (197, 96, 1536), (1000, 384, 1536), (2500, 416, 1536),
-             (8203, 384, 1536), (16400, 128, 1536), (300, 1536, 1536)]
+             (8203, 384, 1536), (16400, 128, 1536), (300, 1536, 1536),
+             # K = 192 (no residual layers): six k-steps a tile
+             (1, 32, 192), (33, 576, 192), (197, 768, 192), (1000, 96, 192), (8203, 576, 192), (20000, 768, 192)]
 
 
 # the kernel with 256 x 128 tiles and both operands streamed: one tile, ragged last tiles, several tiles per workgroup
@@ -494,6 +496,12 @@ def test_linear_requant_big_tiles_mixed_epilogue_forms(ivit, rounding, epi):
 @pytest.mark.parametrize("M,N,K", RS_SHAPES)
 @pytest.mark.parametrize("epi", ["plain", "residual", "gelu"])
 def test_linear_requant_weights_in_registers(ivit, M, N, K, epi):
+    if K == 192 and epi == "residual":
+        with pytest.raises(ivit.IvitError) as err:
+            ivit.ivit_linear_requant(empty((M, K)), empty((N, K)), None, dev(np.ones(N, np.int32)), dev(np.ones(N, np.int32)), empty((M, N)),
+                                     residual=empty((M, N)), res_rq=(3, 1), kernel="reg_stationary")
+        assert err.value.status == ivit.IVIT_ERR_SHAPE
+        return
     x = synth.make_rows(M + N + K, M, K, "normal", 32.0)
     x[0, :7] = -128                                    # the ABI takes any int8
     w, bias, rq_b, rq_c = synth.make_linear(M * 7 + N, N, K)

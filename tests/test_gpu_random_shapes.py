@@ -71,7 +71,7 @@ def test_linear_random(ivit, dense_path, seed):
     rng = np.random.default_rng(1000 + seed)
     K = 16 * int(rng.choice([1, 2, 3, 5, 6, 8, 12, 16, 24, 25, 48, 96, 100, 192]))
     if seed % 6 == 5 and dense_path == "many_rows":      # a sixth of the draws: the kernel with the weights in registers
-        K, dense_path = int(rng.choice([384, 768, 1536])), "reg_stationary"
+        K, dense_path = int(rng.choice([192, 384, 768, 1536])), "reg_stationary"
     N = int(rng.choice([16, 48, 64, 80, 128, 144, 256, 400, 1000, 7, 33])) if seed % 3 else 16 * int(rng.integers(1, 60))
     if dense_path == "reg_stationary":
         N = 32 * int(rng.integers(1, 40))
@@ -79,6 +79,8 @@ def test_linear_random(ivit, dense_path, seed):
     M = max(1, min(M, int(4e8 / (N * K))))                   # keeps the oracle's triple loop under a second
     regime = ("narrow", "fits32", "general")[seed % 3] if seed % 4 else "narrow"
     epi = ("plain", "residual", "gelu")[(seed // 3) % 3]
+    if dense_path == "reg_stationary" and K == 192 and epi == "residual":
+        epi = "gelu"                                         # (that kernel takes no residual layer at K = 192)
     x = synth.make_rows(seed, M, K, "uniform")
     w = np.clip(np.rint(rng.standard_normal((N, K)) * 40.0), -127, 127).astype(np.int8)
     b, c, bias = _dense_params(rng, N, K, regime)
