@@ -791,28 +791,33 @@ hipError_t launch_linear(hipStream_t s, const LinearArgs& a) {
     // measured on patches-to-logits forwards at batch 1 and 8: up to one tile per CU it always wins (batch 1: DeiT-S 0.77 ->
     // 0.66 ms, ViT-B 1.11 -> 0.74 ms), beyond that only when K is long enough for the split over the four wavefronts to pay
     // (a single image of a wide model: at most 256 rows)
-    const int64_t small_limit = (int64_t)num_cus() * (a.K >= 768 && a.M <= 256 ? 3 : 1);
-    if (small_tiles <= small_limit && a.kernel == LINEAR_AUTO) {
+    // (the kernel with the weights in registers, where it takes the layer, is the faster one beyond one tile per CU:
+    // 197 x 3072 x 768: 13.2 -> 10.4 us)
+    const bool rs_auto = linear_rs_takes(a) && (!a.residual || (a.K == 768 && a.N % 256 == 0));
+    const int64_t small_limit = (int64_t)num_cus() * (a.K >= 768 && a.M <= 256 && !rs_auto ? 3 : 1);
+    // (K = 1536 with a whole image's rows: the K-split kernel below is faster, 197 x 384 x 1536: 11.1 -> 9.8 us)
+    const bool ks_instead = linear_ks_takes(a) && a.M >= 128;
+    if (small_tiles <= small_limit && a.kernel == LINEAR_AUTO && !ks_instead) {
         const dim3 g((unsigned)small_tiles), b(64 * SM_WAVES);
         if (a.residual) hipLaunchKernelGGL(gemm_small_kernel<EPI_RESIDUAL>, g, b, 0, s, P);
         else if (a.gelu) hipLaunchKernelGGL(gemm_small_kernel<EPI_GELU>, g, b, 0, s, P);
         else hipLaunchKernelGGL(gemm_small_kernel<EPI_PLAIN>, g, b, 0, s, P);
         return hipGetLastError();
     }
-    // weights in registers: K = 192 / 384 / 768 and more rows than a single image has (K = 192, 100352 rows: QKV
-    // 39.4 -> 28.1 us, fc1 51.1 -> 36.0 us); measured against
+    // weights in registers: K = 192 / 384 / 768, whatever the one-tile-per-workgroup kernel above leaves (197 rows:
+    // fc1 11.2 -> 8.8 us at K = 384, 13.2 -> 10.4 us at K = 768; K = 192, 100352 rows: QKV 39.4 -> 28.1 us, fc1
+    // 51.1 -> 36.0 us); measured against
     // the kernels below on the DeiT-S and ViT-B shapes it wins on the layers without a residual (QKV 27.1 -> 21.6 us,
     // fc1 35.5 -> 28.2 us at K = 384; 116 -> 82 us and 179 -> 127 us at K = 768).  With a residual its epilogue costs
     // more instructions per output: at K = 384 it loses (projection 15.8 -> 19.6 us), at K = 768 it wins when the
     // channels fill whole 256-channel slabs (N = 768: 52.6 -> 46.9 us at 50432 rows, 15.1 -> 13.6 us at 4100) and
     // loses otherwise (N = 384: 21.1 -> 23.3 us; N = 192: 33.9 -> 34.5 us)
-    if (linear_rs_takes(a) && (a.kernel == LINEAR_REG_STATIONARY ||
-                               (a.kernel == LINEAR_AUTO && a.M > 256 && (!a.residual || (a.K == 768 && a.N % 256 == 0)))))
+    if (linear_rs_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && rs_auto)))
         return launch_linear_rs(s, a);
     // K = 1536: the same idea with K split over pairs of wavefronts (gemm_ks.hip).  Both also win on few rows, down to
     // what the one-tile-per-workgroup kernel above takes (394 .. 3152 rows: QKV 10.4 -> 8.2 us, fc2 14.4 -> 10.0 us at
     // the 384-wide model's shapes, 13.2 -> 9.8 us and 13.7 -> 10.4 us at the 768-wide model's)
-    if (linear_ks_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || (a.kernel == LINEAR_AUTO && a.M > 256)))
+    if (linear_ks_takes(a) && (a.kernel == LINEAR_REG_STATIONARY || a.kernel == LINEAR_AUTO))
         return launch_linear_ks(s, a);
     int ncb, unit, nunits, pitch; size_t lds_bytes;
     const bool ws = ws_plan(a, ncb, unit, nunits, pitch, lds_bytes);
